@@ -1,0 +1,160 @@
+/*
+ * flashoptim.h - C ABI of the MI355X (gfx950) FlashOptim optimizer-step library.
+ *
+ * The library implements the fused per-parameter optimizer step of FlashAdamW,
+ * FlashSGD and FlashLion (paper Section 3.3, Algorithms 4, 5, 6) on the
+ * compressed per-parameter layout of Table 1:
+ *
+ *     theta'  BF16   2 B   low-precision weight the model trains on
+ *     rho     INT8   1 B   weight correction            (Section 3.1, Eq. 1-2, Algorithm 1)
+ *     g       BF16   2 B   gradient (0 B resident with gradient release, Section 3.4)
+ *     m       INT8   1 B   companded momentum code      (Section 3.2, Eq. 3, Algorithm 2)
+ *     v       UINT8  1 B   companded variance code      (Section 3.2, Eq. 4, Algorithm 3; AdamW only)
+ *     scales  FP16   2 B per group of G = 32 consecutive elements, per state
+ *
+ * General conventions
+ *  - Every data pointer is a DEVICE pointer on the current HIP device, owned by the
+ *    caller, and must be 16-byte aligned.  Descriptor arrays and hyper-parameter
+ *    structs are HOST memory and are read before the call returns.
+ *  - A tensor is its flattened, contiguous element sequence; quantisation groups are
+ *    elements [32k, 32k+32) of that sequence, the last group may be short, and groups
+ *    never span tensors.  A scale array holds ceil(numel/32) FP16 bit patterns.
+ *  - All-zero m_q/m_scale/v_q/v_scale buffers are the initial state Q_m(0), Q_v(0)
+ *    (Algorithm 4, lines 1-2): a zero scale decodes to exactly zero.
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ *    stream) and the call returns without waiting.  Buffers may be reused or freed
+ *    by the caller in stream order.
+ *  - Return value: FLASHOPTIM_OK (0) or a negative flashoptim_status.  Arguments are
+ *    validated before anything is enqueued: when an error is returned no buffer has
+ *    been modified.  Nothing throws or aborts.
+ *  - Inputs are expected to be finite.  NaN/Inf values propagate into the results of
+ *    their own element or group but never cause out-of-bounds accesses.
+ *  - Arithmetic: IEEE binary32, round-to-nearest-even, subnormals kept, no fused
+ *    multiply-add, in the order the algorithms print it; divisions by a group scale
+ *    or by a bias correction 1 - beta^t multiply by the correctly rounded FP32
+ *    reciprocal of that scalar.
+ *  - There is no CPU fallback: without a HIP device every compute entry point
+ *    returns FLASHOPTIM_ERR_HIP.
+ */
+#ifndef FLASHOPTIM_H
+#define FLASHOPTIM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum flashoptim_status {
+    FLASHOPTIM_OK = 0,
+    FLASHOPTIM_ERR_INVALID_ARG = -1, /* null pointer, negative count, bad kind, step < 1, ... */
+    FLASHOPTIM_ERR_MISALIGNED = -2,  /* a device pointer is not 16-byte aligned               */
+    FLASHOPTIM_ERR_NUMEL_RANGE = -3, /* numel < 0 or >= 2^40                                  */
+    FLASHOPTIM_ERR_HIP = -4,         /* a HIP runtime call failed (see flashoptim_last_hip_error) */
+    FLASHOPTIM_ERR_BAD_BLOB = -5     /* checkpoint blob too small, or header/table mismatch   */
+} flashoptim_status;
+
+/* Optimizer kinds (checkpoint entry points). */
+enum { FLASHOPTIM_ADAMW = 0, FLASHOPTIM_SGD = 1, FLASHOPTIM_LION = 2 };
+
+/* One parameter tensor in the compressed layout.  lr and weight_decay are per tensor
+ * because the paper's recipes exempt biases and normalisation parameters from weight
+ * decay (Appendix B) and follow a learning-rate schedule (Algorithm 4, Require). */
+typedef struct flashoptim_tensor {
+    void*       param;    /* [numel] BF16 theta', in/out                                    */
+    int8_t*     rho;      /* [numel] INT8 weight correction, in/out                         */
+    const void* grad;     /* [numel] BF16 gradient, in                                      */
+    int8_t*     m_q;      /* [numel] INT8 momentum codes, in/out                            */
+    uint16_t*   m_scale;  /* [ceil(numel/32)] FP16 bits, in/out                             */
+    uint8_t*    v_q;      /* [numel] UINT8 variance codes, in/out; AdamW only, else NULL    */
+    uint16_t*   v_scale;  /* [ceil(numel/32)] FP16 bits, in/out;   AdamW only, else NULL    */
+    int64_t     numel;    /* >= 0; a tensor with numel == 0 is skipped                      */
+    float       lr;       /* eta_t for this tensor                                          */
+    float       weight_decay; /* lambda for this tensor (decoupled, multiplied by lr)       */
+} flashoptim_tensor;
+
+typedef struct flashoptim_adamw_hp {
+    float   beta1, beta2, eps;
+    int64_t step;         /* t >= 1: Algorithm 4 increments t before using it               */
+} flashoptim_adamw_hp;
+
+typedef struct flashoptim_sgd_hp { float momentum; } flashoptim_sgd_hp;
+
+typedef struct flashoptim_lion_hp { float beta1, beta2; } flashoptim_lion_hp;
+
+/* ---- fused steps over a list of tensors ------------------------------------------
+ * One kernel launch for the whole list (hundreds of small tensors fill the chip
+ * through a chunk table that the library builds once per distinct list and caches on
+ * the device).  A list of length one is the gradient-release call (Section 3.4): it
+ * needs no table and no device allocation.  The grad pointers are not part of the
+ * cached identity of a list, so gradients may live in different buffers each step.
+ *
+ * flashoptim_adamw_step: Algorithm 4, lines 9-22 (reconstruct m, v, theta; AdamW
+ *   update with bias correction and decoupled weight decay; quantize m, v; split theta).
+ * flashoptim_sgd_step:   Algorithm 5, lines 8-13 (m <- mu m + g; theta <- theta - eta (m + lambda theta)).
+ * flashoptim_lion_step:  Algorithm 6, lines 8-14 (u = sign(b1 m + (1-b1) g); m <- b2 m + (1-b2) g;
+ *   theta <- theta - eta (u + lambda theta)); sign(0) = 0.
+ * tensors: host array of n_tensors descriptors (n_tensors >= 0). */
+int flashoptim_adamw_step(const flashoptim_tensor* tensors, int64_t n_tensors,
+                          const flashoptim_adamw_hp* hp, void* stream);
+int flashoptim_sgd_step(const flashoptim_tensor* tensors, int64_t n_tensors,
+                        const flashoptim_sgd_hp* hp, void* stream);
+int flashoptim_lion_step(const flashoptim_tensor* tensors, int64_t n_tensors,
+                         const flashoptim_lion_hp* hp, void* stream);
+
+/* ---- weight splitting (Section 3.1, Algorithm 1, N = 127) --------------------------
+ * split:       theta (FP32) -> theta' = BF16 round-to-nearest-even, rho = Round(e / (ULP(theta')/2) * 127)
+ *              Used once at the start of training (Algorithm 4, line 3).
+ * reconstruct: theta_hat = theta' + (rho/127) * ULP(theta')/2   (Eq. 2)
+ * n >= 0 elements; all pointers device memory. */
+int flashoptim_split_weights(const float* theta, void* param_bf16, int8_t* rho, int64_t n, void* stream);
+int flashoptim_reconstruct_weights(const void* param_bf16, const int8_t* rho, float* theta, int64_t n,
+                                   void* stream);
+
+/* ---- companded 8-bit state codecs (Section 3.2, Algorithms 2 and 3) -----------------
+ * quantize_momentum:   per group s = FP16(max|m|), code = Round(127 * 2m'/(1+|m'|)), m' = m/s
+ * dequantize_momentum: m = (z / (2 - |z|)) * s, z = code/127
+ * quantize_variance:   per group s = FP16(max sqrt(v)), code = Round(255 * sqrt(v)/s)
+ * dequantize_variance: v = ((code/255) * s)^2
+ * n >= 0 elements, scale arrays of ceil(n/32) FP16 bit patterns; all device memory. */
+int flashoptim_quantize_momentum(const float* m, int8_t* q, uint16_t* scale, int64_t n, void* stream);
+int flashoptim_dequantize_momentum(const int8_t* q, const uint16_t* scale, float* m, int64_t n, void* stream);
+int flashoptim_quantize_variance(const float* v, uint8_t* q, uint16_t* scale, int64_t n, void* stream);
+int flashoptim_dequantize_variance(const uint8_t* q, const uint16_t* scale, float* v, int64_t n, void* stream);
+
+/* ---- checkpoint (Section 3.4, "Checkpoint size": 2 + 1 + 1 + 1 bytes per parameter) --
+ * The paper fixes the content, not a container.  Blob layout, little-endian:
+ *   header (64 B): "FOPTCKPT" | u32 version = 1 | u32 kind | i64 step | i64 n_tensors |
+ *                  i64 total_bytes | zero padding
+ *   table: per tensor i64 numel | i64 offset of its first section from the blob start;
+ *          padded to a multiple of 64 B
+ *   per tensor, in list order, each section starting on a 64-byte boundary and zero
+ *   padded: theta' (2n) | rho (n) | m codes (n) | m scales (2 ceil(n/32)) |
+ *   AdamW only: v codes (n) | v scales (2 ceil(n/32))
+ * checkpoint_size: total blob bytes for a list (numels: host array), or a negative status.
+ * checkpoint_pack:   gathers the tensors' state into `blob` (DEVICE memory, 16-byte aligned,
+ *                    blob_bytes >= checkpoint_size).  grad fields are ignored.
+ * checkpoint_unpack: scatters `blob` (DEVICE memory) back into the tensors' buffers and
+ *                    returns the stored step in *step_out (host).  The header and table
+ *                    are validated against (kind, list) first; this reads the header back to
+ *                    the host and therefore waits for prior work on `stream`. */
+int64_t flashoptim_checkpoint_size(int kind, const int64_t* numels, int64_t n_tensors);
+int flashoptim_checkpoint_pack(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, int64_t step,
+                               void* blob, int64_t blob_bytes, void* stream);
+int flashoptim_checkpoint_unpack(int kind, const void* blob, int64_t blob_bytes,
+                                 const flashoptim_tensor* tensors, int64_t n_tensors, int64_t* step_out,
+                                 void* stream);
+
+/* ---- housekeeping --------------------------------------------------------------------
+ * strerror: static string for a status.  last_hip_error: hipError_t value of the most recent
+ * failed HIP call on this thread (0 if none).  release_cache: frees the cached device chunk
+ * tables (synchronises the device first).  version: (major << 16) | minor. */
+const char* flashoptim_strerror(int status);
+int flashoptim_last_hip_error(void);
+int flashoptim_release_cache(void);
+int flashoptim_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHOPTIM_H */

@@ -1,0 +1,13 @@
+"""MI355X-native FlashOptim optimizer-step library: thin Python binding over the C ABI.
+
+Importing the package does not load the HIP library; the first call does, and it fails
+loudly if the library has not been built (python paper_2602_23349_amd/build.py).
+"""
+from .binding import (  # noqa: F401
+    FlashOptimError, TensorList, ParamBuffers, library_path, load_library,
+    adamw_step, sgd_step, lion_step,
+    split_weights, reconstruct_weights,
+    quantize_momentum, dequantize_momentum, quantize_variance, dequantize_variance,
+    checkpoint_size, checkpoint_pack, checkpoint_unpack,
+    strerror, release_cache, version, EXPORTED_SYMBOLS, KIND,
+)

@@ -1,0 +1,236 @@
+"""ctypes binding of include/flashoptim.h: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (without the
+`flashoptim_` prefix) and does nothing but turn torch tensors into device pointers.
+torch is used for device memory and streams only.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libflashoptim.so")
+_lib = None
+
+KIND = {"adamw": 0, "sgd": 1, "lion": 2}
+
+EXPORTED_SYMBOLS = [
+    "flashoptim_adamw_step", "flashoptim_sgd_step", "flashoptim_lion_step",
+    "flashoptim_split_weights", "flashoptim_reconstruct_weights",
+    "flashoptim_quantize_momentum", "flashoptim_dequantize_momentum",
+    "flashoptim_quantize_variance", "flashoptim_dequantize_variance",
+    "flashoptim_checkpoint_size", "flashoptim_checkpoint_pack", "flashoptim_checkpoint_unpack",
+    "flashoptim_strerror", "flashoptim_last_hip_error", "flashoptim_release_cache", "flashoptim_version",
+]
+
+
+class FlashOptimError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = strerror(status)
+        if status == -4:
+            msg += f" (hipError_t {load_library().flashoptim_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{status}]")
+
+
+class _Tensor(C.Structure):
+    _fields_ = [("param", C.c_void_p), ("rho", C.c_void_p), ("grad", C.c_void_p),
+                ("m_q", C.c_void_p), ("m_scale", C.c_void_p), ("v_q", C.c_void_p), ("v_scale", C.c_void_p),
+                ("numel", C.c_int64), ("lr", C.c_float), ("weight_decay", C.c_float)]
+
+
+class _AdamWHp(C.Structure):
+    _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("step", C.c_int64)]
+
+
+class _SgdHp(C.Structure):
+    _fields_ = [("momentum", C.c_float)]
+
+
+class _LionHp(C.Structure):
+    _fields_ = [("beta1", C.c_float), ("beta2", C.c_float)]
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads the in-tree HIP library.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python paper_2602_23349_amd/build.py`")
+    L = C.CDLL(_LIB_PATH)
+    vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int
+    L.flashoptim_adamw_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_AdamWHp), vp]
+    L.flashoptim_sgd_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_SgdHp), vp]
+    L.flashoptim_lion_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_LionHp), vp]
+    for name in ("flashoptim_split_weights", "flashoptim_reconstruct_weights", "flashoptim_quantize_momentum",
+                 "flashoptim_dequantize_momentum", "flashoptim_quantize_variance", "flashoptim_dequantize_variance"):
+        getattr(L, name).argtypes = [vp, vp, vp, i64, vp]
+    L.flashoptim_checkpoint_size.argtypes = [i32, C.POINTER(i64), i64]
+    L.flashoptim_checkpoint_size.restype = i64
+    L.flashoptim_checkpoint_pack.argtypes = [i32, C.POINTER(_Tensor), i64, i64, vp, i64, vp]
+    L.flashoptim_checkpoint_unpack.argtypes = [i32, vp, i64, C.POINTER(_Tensor), i64, C.POINTER(i64), vp]
+    L.flashoptim_strerror.argtypes = [i32]
+    L.flashoptim_strerror.restype = C.c_char_p
+    for name in EXPORTED_SYMBOLS:
+        if name not in ("flashoptim_checkpoint_size", "flashoptim_strerror"):
+            getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(status, where):
+    if status != 0:
+        raise FlashOptimError(status, where)
+
+
+class ParamBuffers:
+    """Device buffers of one parameter in the compressed layout (allocation only)."""
+
+    def __init__(self, numel, kind, device="cuda", with_grad=True):
+        ng = (numel + 31) // 32
+        self.numel, self.kind = int(numel), kind
+        self.param = torch.zeros(numel, dtype=torch.bfloat16, device=device)
+        self.rho = torch.zeros(numel, dtype=torch.int8, device=device)
+        self.grad = torch.zeros(numel, dtype=torch.bfloat16, device=device) if with_grad else None
+        self.m_q = torch.zeros(numel, dtype=torch.int8, device=device)
+        self.m_scale = torch.zeros(ng, dtype=torch.float16, device=device)
+        self.v_q = torch.zeros(numel, dtype=torch.uint8, device=device) if kind == "adamw" else None
+        self.v_scale = torch.zeros(ng, dtype=torch.float16, device=device) if kind == "adamw" else None
+        self.lr, self.weight_decay = 0.0, 0.0
+
+
+class TensorList:
+    """A host array of flashoptim_tensor descriptors, built once and reused across steps."""
+
+    def __init__(self, buffers):
+        self.buffers = list(buffers)
+        self.n = len(self.buffers)
+        self.array = (_Tensor * max(self.n, 1))()
+        for i, b in enumerate(self.buffers):
+            d = self.array[i]
+            d.param, d.rho, d.grad = _ptr(b.param), _ptr(b.rho), _ptr(b.grad)
+            d.m_q, d.m_scale, d.v_q, d.v_scale = _ptr(b.m_q), _ptr(b.m_scale), _ptr(b.v_q), _ptr(b.v_scale)
+            d.numel, d.lr, d.weight_decay = b.numel, b.lr, b.weight_decay
+
+    def set_hyper(self, i, lr=None, weight_decay=None):
+        if lr is not None:
+            self.array[i].lr = lr
+        if weight_decay is not None:
+            self.array[i].weight_decay = weight_decay
+
+    def set_grad(self, i, grad):
+        self.array[i].grad = _ptr(grad)
+
+    def slice(self, i):
+        """A one-element list viewing tensor i (for per-tensor, gradient-release style calls)."""
+        out = TensorList.__new__(TensorList)
+        out.buffers, out.n = [self.buffers[i]], 1
+        out.array = (_Tensor * 1)()
+        C.memmove(out.array, C.byref(self.array[i]), C.sizeof(_Tensor))
+        return out
+
+
+def _as_list(tensors):
+    return tensors if isinstance(tensors, TensorList) else TensorList(tensors)
+
+
+def adamw_step(tensors, beta1, beta2, eps, step, stream=None):
+    tl = _as_list(tensors)
+    hp = _AdamWHp(beta1, beta2, eps, int(step))
+    _check(load_library().flashoptim_adamw_step(tl.array, tl.n, C.byref(hp), _stream(stream)), "flashoptim_adamw_step")
+
+
+def sgd_step(tensors, momentum, stream=None):
+    tl = _as_list(tensors)
+    hp = _SgdHp(momentum)
+    _check(load_library().flashoptim_sgd_step(tl.array, tl.n, C.byref(hp), _stream(stream)), "flashoptim_sgd_step")
+
+
+def lion_step(tensors, beta1, beta2, stream=None):
+    tl = _as_list(tensors)
+    hp = _LionHp(beta1, beta2)
+    _check(load_library().flashoptim_lion_step(tl.array, tl.n, C.byref(hp), _stream(stream)), "flashoptim_lion_step")
+
+
+def split_weights(theta, param_bf16, rho, stream=None):
+    n = theta.numel()
+    _check(load_library().flashoptim_split_weights(_ptr(theta), _ptr(param_bf16), _ptr(rho), n, _stream(stream)),
+           "flashoptim_split_weights")
+
+
+def reconstruct_weights(param_bf16, rho, theta, stream=None):
+    n = param_bf16.numel()
+    _check(load_library().flashoptim_reconstruct_weights(_ptr(param_bf16), _ptr(rho), _ptr(theta), n, _stream(stream)),
+           "flashoptim_reconstruct_weights")
+
+
+def quantize_momentum(m, q, scale, stream=None):
+    _check(load_library().flashoptim_quantize_momentum(_ptr(m), _ptr(q), _ptr(scale), m.numel(), _stream(stream)),
+           "flashoptim_quantize_momentum")
+
+
+def dequantize_momentum(q, scale, m, stream=None):
+    _check(load_library().flashoptim_dequantize_momentum(_ptr(q), _ptr(scale), _ptr(m), q.numel(), _stream(stream)),
+           "flashoptim_dequantize_momentum")
+
+
+def quantize_variance(v, q, scale, stream=None):
+    _check(load_library().flashoptim_quantize_variance(_ptr(v), _ptr(q), _ptr(scale), v.numel(), _stream(stream)),
+           "flashoptim_quantize_variance")
+
+
+def dequantize_variance(q, scale, v, stream=None):
+    _check(load_library().flashoptim_dequantize_variance(_ptr(q), _ptr(scale), _ptr(v), q.numel(), _stream(stream)),
+           "flashoptim_dequantize_variance")
+
+
+def checkpoint_size(kind, numels):
+    arr = (C.c_int64 * max(len(numels), 1))(*[int(x) for x in numels])
+    r = load_library().flashoptim_checkpoint_size(KIND[kind], arr, len(numels))
+    if r < 0:
+        raise FlashOptimError(int(r), "flashoptim_checkpoint_size")
+    return int(r)
+
+
+def checkpoint_pack(kind, tensors, step, blob, stream=None):
+    tl = _as_list(tensors)
+    _check(load_library().flashoptim_checkpoint_pack(KIND[kind], tl.array, tl.n, int(step), _ptr(blob),
+                                                     blob.numel() * blob.element_size(), _stream(stream)),
+           "flashoptim_checkpoint_pack")
+
+
+def checkpoint_unpack(kind, blob, tensors, stream=None):
+    tl = _as_list(tensors)
+    step = C.c_int64(0)
+    _check(load_library().flashoptim_checkpoint_unpack(KIND[kind], _ptr(blob), blob.numel() * blob.element_size(),
+                                                       tl.array, tl.n, C.byref(step), _stream(stream)),
+           "flashoptim_checkpoint_unpack")
+    return int(step.value)
+
+
+def strerror(status):
+    return load_library().flashoptim_strerror(int(status)).decode()
+
+
+def release_cache():
+    _check(load_library().flashoptim_release_cache(), "flashoptim_release_cache")
+
+
+def version():
+    return int(load_library().flashoptim_version())

@@ -1,0 +1,506 @@
+// Host side of the FlashOptim C ABI (include/flashoptim.h): argument validation, the
+// cached device chunk tables that let one launch cover a whole parameter list, per-call
+// scalar set-up, and the checkpoint container.
+//
+// Nothing here computes on the CPU what the GPU should: if HIP is unavailable every
+// compute entry point returns FLASHOPTIM_ERR_HIP.
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <list>
+#include <mutex>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "flashoptim.h"
+#include "flashoptim_device.h"
+
+namespace {
+
+using fo::CopySegment;
+using fo::StepArgs;
+using fo::StepConsts;
+using fo::TensorDev;
+
+constexpr int64_t kMaxNumel = (int64_t)1 << 40;
+constexpr int kVersion = (0 << 16) | 1;
+
+thread_local int g_last_hip_error = 0;
+
+#define FO_HIP(expr)                                         \
+    do {                                                     \
+        hipError_t e_ = (expr);                              \
+        if (e_ != hipSuccess) {                              \
+            g_last_hip_error = (int)e_;                      \
+            (void)hipGetLastError();                         \
+            return FLASHOPTIM_ERR_HIP;                       \
+        }                                                    \
+    } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int64_t n_groups(int64_t n) { return (n + fo::kGroup - 1) / fo::kGroup; }
+inline int64_t align64(int64_t x) { return (x + 63) & ~(int64_t)63; }
+
+// ----------------------------------------------------- cached device tables --
+//
+// A "plan" is what a multi-tensor launch needs on the device: the tensor table and the
+// chunk table.  It is keyed by the list's identity (device, kind, every state pointer and
+// numel; NOT the gradient pointers or lr/wd, which legitimately change from step to step).
+// The tensor table is re-uploaded (72 B per tensor, through pinned staging, in stream
+// order) only when its content differs from what the device already holds.
+
+struct Staging {          // pinned host buffer + the event that marks its last copy done
+    void* host = nullptr;
+    size_t bytes = 0;
+    hipEvent_t done = nullptr;
+    bool in_flight = false;
+};
+
+struct Plan {
+    int device = 0;
+    void* d_table = nullptr;       // TensorDev[] or CopySegment[]
+    size_t table_bytes = 0;
+    uint2* d_chunks = nullptr;
+    int64_t n_chunks = 0;
+    std::string uploaded;          // bytes of the table the device currently holds
+    Staging ring[4];
+    int next_slot = 0;
+};
+
+std::mutex g_mu;
+std::unordered_map<std::string, std::list<std::pair<std::string, Plan>>::iterator> g_index;
+std::list<std::pair<std::string, Plan>> g_plans;   // most recently used first
+constexpr size_t kMaxPlans = 64;
+
+void destroy_plan(Plan& p) {
+    int cur = 0;
+    (void)hipGetDevice(&cur);
+    (void)hipSetDevice(p.device);
+    for (auto& s : p.ring) {
+        if (s.done) { if (s.in_flight) (void)hipEventSynchronize(s.done); (void)hipEventDestroy(s.done); }
+        if (s.host) (void)hipHostFree(s.host);
+        s = Staging();
+    }
+    if (p.d_table) (void)hipFree(p.d_table);
+    if (p.d_chunks) (void)hipFree(p.d_chunks);
+    p.d_table = nullptr; p.d_chunks = nullptr;
+    (void)hipSetDevice(cur);
+}
+
+// Puts `bytes` of `src` into p.d_table in stream order, via a pinned ring slot.
+int upload_table(Plan& p, const void* src, size_t bytes, hipStream_t stream) {
+    Staging& s = p.ring[p.next_slot];
+    p.next_slot = (p.next_slot + 1) % 4;
+    if (s.in_flight) { FO_HIP(hipEventSynchronize(s.done)); s.in_flight = false; }
+    if (s.bytes < bytes) {
+        if (s.host) { FO_HIP(hipHostFree(s.host)); s.host = nullptr; s.bytes = 0; }
+        FO_HIP(hipHostMalloc(&s.host, bytes, hipHostMallocDefault));
+        s.bytes = bytes;
+    }
+    if (!s.done) FO_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+    std::memcpy(s.host, src, bytes);
+    FO_HIP(hipMemcpyAsync(p.d_table, s.host, bytes, hipMemcpyHostToDevice, stream));
+    FO_HIP(hipEventRecord(s.done, stream));
+    s.in_flight = true;
+    p.uploaded.assign(static_cast<const char*>(src), bytes);
+    return FLASHOPTIM_OK;
+}
+
+// Finds or creates the plan for `key`.  `chunks` is consumed only on creation.
+int get_plan(const std::string& key, size_t table_bytes, const std::vector<uint2>& chunks, Plan** out) {
+    auto it = g_index.find(key);
+    if (it != g_index.end()) {
+        g_plans.splice(g_plans.begin(), g_plans, it->second);
+        *out = &g_plans.front().second;
+        return FLASHOPTIM_OK;
+    }
+    Plan p;
+    FO_HIP(hipGetDevice(&p.device));
+    p.table_bytes = table_bytes;
+    p.n_chunks = (int64_t)chunks.size();
+    hipError_t e = hipMalloc(&p.d_table, table_bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&p.d_chunks, chunks.size() * sizeof(uint2));
+    // one-time, blocking upload of the chunk table (it never changes for this list)
+    if (e == hipSuccess) e = hipMemcpy(p.d_chunks, chunks.data(), chunks.size() * sizeof(uint2), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        (void)hipGetLastError();
+        destroy_plan(p);
+        return FLASHOPTIM_ERR_HIP;
+    }
+    g_plans.emplace_front(key, p);
+    g_index[key] = g_plans.begin();
+    while (g_plans.size() > kMaxPlans) {
+        // the evicted plan's buffers may still be read by enqueued work: wait for the device
+        (void)hipDeviceSynchronize();
+        destroy_plan(g_plans.back().second);
+        g_index.erase(g_plans.back().first);
+        g_plans.pop_back();
+    }
+    *out = &g_plans.front().second;
+    return FLASHOPTIM_OK;
+}
+
+void append(std::string& k, const void* p, size_t n) { k.append(static_cast<const char*>(p), n); }
+
+// ------------------------------------------------------------------- steps --
+
+int validate_tensors(const flashoptim_tensor* t, int64_t n, bool has_v) {
+    if (n < 0 || (n > 0 && t == nullptr)) return FLASHOPTIM_ERR_INVALID_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        const flashoptim_tensor& x = t[i];
+        if (x.numel < 0 || x.numel >= kMaxNumel) return FLASHOPTIM_ERR_NUMEL_RANGE;
+        if (x.numel == 0) continue;
+        if (!x.param || !x.rho || !x.m_q || !x.m_scale) return FLASHOPTIM_ERR_INVALID_ARG;
+        if (has_v && (!x.v_q || !x.v_scale)) return FLASHOPTIM_ERR_INVALID_ARG;
+        if (!aligned16(x.param) || !aligned16(x.rho) || !aligned16(x.m_q) || !aligned16(x.m_scale))
+            return FLASHOPTIM_ERR_MISALIGNED;
+        if (has_v && (!aligned16(x.v_q) || !aligned16(x.v_scale))) return FLASHOPTIM_ERR_MISALIGNED;
+    }
+    return FLASHOPTIM_OK;
+}
+
+TensorDev to_dev(const flashoptim_tensor& x, bool has_v) {
+    TensorDev d;
+    d.param = x.param; d.rho = x.rho; d.grad = x.grad; d.m_q = x.m_q; d.m_scale = x.m_scale;
+    d.v_q = has_v ? x.v_q : nullptr; d.v_scale = has_v ? x.v_scale : nullptr;
+    d.numel = x.numel; d.lr = x.lr; d.wd = x.weight_decay;
+    return d;
+}
+
+int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, const StepConsts& c, void* stream_) {
+    const bool has_v = (kind == FLASHOPTIM_ADAMW);
+    int rc = validate_tensors(tensors, n_tensors, has_v);
+    if (rc != FLASHOPTIM_OK) return rc;
+    for (int64_t i = 0; i < n_tensors; ++i) {
+        if (tensors[i].numel == 0) continue;
+        if (!tensors[i].grad) return FLASHOPTIM_ERR_INVALID_ARG;
+        if (!aligned16(tensors[i].grad)) return FLASHOPTIM_ERR_MISALIGNED;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+
+    // live tensors only
+    std::vector<TensorDev> live;
+    live.reserve((size_t)n_tensors);
+    for (int64_t i = 0; i < n_tensors; ++i)
+        if (tensors[i].numel > 0) live.push_back(to_dev(tensors[i], has_v));
+    if (live.empty()) return FLASHOPTIM_OK;
+
+    StepArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.c = c;
+
+    if (live.size() == 1) {
+        // gradient-release call: no table, no allocation, no lock
+        a.single = live[0];
+        const int64_t blocks = (live[0].numel + fo::kChunkElems - 1) / fo::kChunkElems;
+        fo::launch_step(kind, true, a, blocks, stream);
+        FO_HIP(hipGetLastError());
+        return FLASHOPTIM_OK;
+    }
+
+    int device = 0;
+    FO_HIP(hipGetDevice(&device));
+    std::string key;
+    key.reserve(16 + live.size() * 56);
+    const int32_t tag[2] = {kind, device};
+    append(key, tag, sizeof(tag));
+    for (const TensorDev& d : live) {
+        const void* ids[6] = {d.param, d.rho, d.m_q, d.m_scale, d.v_q, d.v_scale};
+        append(key, ids, sizeof(ids));
+        append(key, &d.numel, sizeof(d.numel));
+    }
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    Plan* plan = nullptr;
+    std::vector<uint2> chunks;
+    if (g_index.find(key) == g_index.end()) {
+        for (size_t ti = 0; ti < live.size(); ++ti) {
+            const int64_t nc = (live[ti].numel + fo::kChunkElems - 1) / fo::kChunkElems;
+            for (int64_t ci = 0; ci < nc; ++ci) chunks.push_back(make_uint2((unsigned)ti, (unsigned)ci));
+        }
+    }
+    rc = get_plan(key, live.size() * sizeof(TensorDev), chunks, &plan);
+    if (rc != FLASHOPTIM_OK) return rc;
+
+    const size_t bytes = live.size() * sizeof(TensorDev);
+    if (plan->uploaded.size() != bytes || std::memcmp(plan->uploaded.data(), live.data(), bytes) != 0) {
+        rc = upload_table(*plan, live.data(), bytes, stream);
+        if (rc != FLASHOPTIM_OK) return rc;
+    }
+    a.tensors = static_cast<const TensorDev*>(plan->d_table);
+    a.chunks = plan->d_chunks;
+    fo::launch_step(kind, false, a, plan->n_chunks, stream);
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+// 1 / (float)(1 - beta^t): the bias correction is formed in double and rounded to FP32
+// once; its reciprocal is one FP32 division.
+float recip_bias_correction(float beta, int64_t t) {
+    const float bc = (float)(1.0 - std::pow((double)beta, (double)t));
+    return 1.0f / bc;
+}
+
+// ---------------------------------------------------------------- checkpoint --
+
+const char kMagic[8] = {'F', 'O', 'P', 'T', 'C', 'K', 'P', 'T'};
+
+int64_t tensor_payload(int64_t n, int kind) {
+    int64_t b = align64(2 * n) + align64(n) + align64(n) + align64(2 * n_groups(n));
+    if (kind == FLASHOPTIM_ADAMW) b += align64(n) + align64(2 * n_groups(n));
+    return b;
+}
+
+void put_i64(uint8_t* p, int64_t v) { for (int i = 0; i < 8; ++i) p[i] = (uint8_t)((uint64_t)v >> (8 * i)); }
+void put_u32(uint8_t* p, uint32_t v) { for (int i = 0; i < 4; ++i) p[i] = (uint8_t)(v >> (8 * i)); }
+int64_t get_i64(const uint8_t* p) { uint64_t v = 0; for (int i = 0; i < 8; ++i) v |= (uint64_t)p[i] << (8 * i); return (int64_t)v; }
+uint32_t get_u32(const uint8_t* p) { uint32_t v = 0; for (int i = 0; i < 4; ++i) v |= (uint32_t)p[i] << (8 * i); return v; }
+
+std::vector<uint8_t> build_header(int kind, const flashoptim_tensor* t, int64_t n, int64_t step, int64_t total) {
+    std::vector<uint8_t> h((size_t)(64 + align64(16 * n)), 0);
+    std::memcpy(h.data(), kMagic, 8);
+    put_u32(h.data() + 8, 1u);
+    put_u32(h.data() + 12, (uint32_t)kind);
+    put_i64(h.data() + 16, step);
+    put_i64(h.data() + 24, n);
+    put_i64(h.data() + 32, total);
+    int64_t off = (int64_t)h.size();
+    for (int64_t i = 0; i < n; ++i) {
+        put_i64(h.data() + 64 + 16 * i, t[i].numel);
+        put_i64(h.data() + 64 + 16 * i + 8, off);
+        off += tensor_payload(t[i].numel, kind);
+    }
+    return h;
+}
+
+// Segments (one per section per tensor) between the tensors' buffers and the blob.
+void build_segments(int kind, const flashoptim_tensor* t, int64_t n, uint8_t* blob, bool pack,
+                    std::vector<CopySegment>& segs) {
+    int64_t off = 64 + align64(16 * n);
+    auto add = [&](const void* tensor_buf, int64_t bytes) {
+        if (bytes > 0) {
+            CopySegment s;
+            if (pack) { s.src = static_cast<const uint8_t*>(tensor_buf); s.dst = blob + off; s.pad_bytes = align64(bytes); }
+            else { s.src = blob + off; s.dst = static_cast<uint8_t*>(const_cast<void*>(tensor_buf)); s.pad_bytes = bytes; }
+            s.bytes = bytes;
+            segs.push_back(s);
+        }
+        off += align64(bytes);
+    };
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t ne = t[i].numel, ng = n_groups(ne);
+        add(t[i].param, 2 * ne); add(t[i].rho, ne); add(t[i].m_q, ne); add(t[i].m_scale, 2 * ng);
+        if (kind == FLASHOPTIM_ADAMW) { add(t[i].v_q, ne); add(t[i].v_scale, 2 * ng); }
+    }
+}
+
+int run_copy(const std::vector<CopySegment>& segs, hipStream_t stream) {
+    if (segs.empty()) return FLASHOPTIM_OK;
+    std::vector<uint2> chunks;
+    for (size_t si = 0; si < segs.size(); ++si) {
+        const int64_t nc = (segs[si].pad_bytes + fo::kCopyChunkBytes - 1) / fo::kCopyChunkBytes;
+        for (int64_t ci = 0; ci < nc; ++ci) chunks.push_back(make_uint2((unsigned)si, (unsigned)ci));
+    }
+    int device = 0;
+    FO_HIP(hipGetDevice(&device));
+    std::string key;
+    const int32_t tag[2] = {-1, device};
+    append(key, tag, sizeof(tag));
+    append(key, segs.data(), segs.size() * sizeof(CopySegment));
+    std::lock_guard<std::mutex> lock(g_mu);
+    Plan* plan = nullptr;
+    int rc = get_plan(key, segs.size() * sizeof(CopySegment), chunks, &plan);
+    if (rc != FLASHOPTIM_OK) return rc;
+    if (plan->uploaded.empty()) {
+        rc = upload_table(*plan, segs.data(), segs.size() * sizeof(CopySegment), stream);
+        if (rc != FLASHOPTIM_OK) return rc;
+    }
+    fo::launch_copy(static_cast<const CopySegment*>(plan->d_table), plan->d_chunks, plan->n_chunks, stream);
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int check_elementwise(const void* a, const void* b, const void* c, int64_t n) {
+    if (n < 0 || n >= kMaxNumel) return FLASHOPTIM_ERR_NUMEL_RANGE;
+    if (n == 0) return FLASHOPTIM_OK;
+    if (!a || !b || !c) return FLASHOPTIM_ERR_INVALID_ARG;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return FLASHOPTIM_ERR_MISALIGNED;
+    return FLASHOPTIM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int flashoptim_adamw_step(const flashoptim_tensor* tensors, int64_t n_tensors, const flashoptim_adamw_hp* hp,
+                          void* stream) {
+    if (!hp || hp->step < 1) return FLASHOPTIM_ERR_INVALID_ARG;
+    StepConsts c;
+    std::memset(&c, 0, sizeof(c));
+    c.beta1 = hp->beta1; c.beta2 = hp->beta2;
+    c.omb1 = 1.0f - hp->beta1; c.omb2 = 1.0f - hp->beta2;
+    c.rbc1 = recip_bias_correction(hp->beta1, hp->step);
+    c.rbc2 = recip_bias_correction(hp->beta2, hp->step);
+    c.eps = hp->eps;
+    return run_step(FLASHOPTIM_ADAMW, tensors, n_tensors, c, stream);
+}
+
+int flashoptim_sgd_step(const flashoptim_tensor* tensors, int64_t n_tensors, const flashoptim_sgd_hp* hp,
+                        void* stream) {
+    if (!hp) return FLASHOPTIM_ERR_INVALID_ARG;
+    StepConsts c;
+    std::memset(&c, 0, sizeof(c));
+    c.beta1 = hp->momentum;
+    return run_step(FLASHOPTIM_SGD, tensors, n_tensors, c, stream);
+}
+
+int flashoptim_lion_step(const flashoptim_tensor* tensors, int64_t n_tensors, const flashoptim_lion_hp* hp,
+                         void* stream) {
+    if (!hp) return FLASHOPTIM_ERR_INVALID_ARG;
+    StepConsts c;
+    std::memset(&c, 0, sizeof(c));
+    c.beta1 = hp->beta1; c.beta2 = hp->beta2;
+    c.omb1 = 1.0f - hp->beta1; c.omb2 = 1.0f - hp->beta2;
+    return run_step(FLASHOPTIM_LION, tensors, n_tensors, c, stream);
+}
+
+int flashoptim_split_weights(const float* theta, void* param_bf16, int8_t* rho, int64_t n, void* stream) {
+    int rc = check_elementwise(theta, param_bf16, rho, n);
+    if (rc != FLASHOPTIM_OK || n == 0) return rc;
+    fo::launch_split(theta, param_bf16, rho, n, static_cast<hipStream_t>(stream));
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_reconstruct_weights(const void* param_bf16, const int8_t* rho, float* theta, int64_t n, void* stream) {
+    int rc = check_elementwise(param_bf16, rho, theta, n);
+    if (rc != FLASHOPTIM_OK || n == 0) return rc;
+    fo::launch_reconstruct(param_bf16, rho, theta, n, static_cast<hipStream_t>(stream));
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_quantize_momentum(const float* m, int8_t* q, uint16_t* scale, int64_t n, void* stream) {
+    int rc = check_elementwise(m, q, scale, n);
+    if (rc != FLASHOPTIM_OK || n == 0) return rc;
+    fo::launch_quantize(false, m, q, scale, n, static_cast<hipStream_t>(stream));
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_dequantize_momentum(const int8_t* q, const uint16_t* scale, float* m, int64_t n, void* stream) {
+    int rc = check_elementwise(q, scale, m, n);
+    if (rc != FLASHOPTIM_OK || n == 0) return rc;
+    fo::launch_dequantize(false, q, scale, m, n, static_cast<hipStream_t>(stream));
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_quantize_variance(const float* v, uint8_t* q, uint16_t* scale, int64_t n, void* stream) {
+    int rc = check_elementwise(v, q, scale, n);
+    if (rc != FLASHOPTIM_OK || n == 0) return rc;
+    fo::launch_quantize(true, v, q, scale, n, static_cast<hipStream_t>(stream));
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_dequantize_variance(const uint8_t* q, const uint16_t* scale, float* v, int64_t n, void* stream) {
+    int rc = check_elementwise(q, scale, v, n);
+    if (rc != FLASHOPTIM_OK || n == 0) return rc;
+    fo::launch_dequantize(true, q, scale, v, n, static_cast<hipStream_t>(stream));
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int64_t flashoptim_checkpoint_size(int kind, const int64_t* numels, int64_t n_tensors) {
+    if (kind < 0 || kind > 2 || n_tensors < 0 || (n_tensors > 0 && !numels)) return FLASHOPTIM_ERR_INVALID_ARG;
+    int64_t total = 64 + align64(16 * n_tensors);
+    for (int64_t i = 0; i < n_tensors; ++i) {
+        if (numels[i] < 0 || numels[i] >= kMaxNumel) return FLASHOPTIM_ERR_NUMEL_RANGE;
+        total += tensor_payload(numels[i], kind);
+    }
+    return total;
+}
+
+static int64_t list_size(int kind, const flashoptim_tensor* t, int64_t n) {
+    std::vector<int64_t> numels((size_t)n);
+    for (int64_t i = 0; i < n; ++i) numels[(size_t)i] = t[i].numel;
+    return flashoptim_checkpoint_size(kind, numels.data(), n);
+}
+
+int flashoptim_checkpoint_pack(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, int64_t step,
+                               void* blob, int64_t blob_bytes, void* stream_) {
+    if (kind < 0 || kind > 2 || !blob) return FLASHOPTIM_ERR_INVALID_ARG;
+    int rc = validate_tensors(tensors, n_tensors, kind == FLASHOPTIM_ADAMW);
+    if (rc != FLASHOPTIM_OK) return rc;
+    if (!aligned16(blob)) return FLASHOPTIM_ERR_MISALIGNED;
+    const int64_t total = list_size(kind, tensors, n_tensors);
+    if (total < 0) return (int)total;
+    if (blob_bytes < total) return FLASHOPTIM_ERR_BAD_BLOB;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const std::vector<uint8_t> header = build_header(kind, tensors, n_tensors, step, total);
+    // header: small blocking copy after the stream's earlier work (the blob may be in use by it)
+    FO_HIP(hipStreamSynchronize(stream));
+    FO_HIP(hipMemcpy(blob, header.data(), header.size(), hipMemcpyHostToDevice));
+    std::vector<CopySegment> segs;
+    build_segments(kind, tensors, n_tensors, static_cast<uint8_t*>(blob), true, segs);
+    return run_copy(segs, stream);
+}
+
+int flashoptim_checkpoint_unpack(int kind, const void* blob, int64_t blob_bytes, const flashoptim_tensor* tensors,
+                                 int64_t n_tensors, int64_t* step_out, void* stream_) {
+    if (kind < 0 || kind > 2 || !blob || !step_out) return FLASHOPTIM_ERR_INVALID_ARG;
+    int rc = validate_tensors(tensors, n_tensors, kind == FLASHOPTIM_ADAMW);
+    if (rc != FLASHOPTIM_OK) return rc;
+    if (!aligned16(blob)) return FLASHOPTIM_ERR_MISALIGNED;
+    const int64_t total = list_size(kind, tensors, n_tensors);
+    if (total < 0) return (int)total;
+    if (blob_bytes < total) return FLASHOPTIM_ERR_BAD_BLOB;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const std::vector<uint8_t> want = build_header(kind, tensors, n_tensors, 0, total);
+    std::vector<uint8_t> got(want.size());
+    FO_HIP(hipStreamSynchronize(stream));
+    FO_HIP(hipMemcpy(got.data(), blob, got.size(), hipMemcpyDeviceToHost));
+    // everything but the step field must match what this (kind, list) would have written
+    if (std::memcmp(got.data(), want.data(), 16) != 0) return FLASHOPTIM_ERR_BAD_BLOB;
+    if (std::memcmp(got.data() + 24, want.data() + 24, got.size() - 24) != 0) return FLASHOPTIM_ERR_BAD_BLOB;
+    std::vector<CopySegment> segs;
+    build_segments(kind, tensors, n_tensors, static_cast<uint8_t*>(const_cast<void*>(blob)), false, segs);
+    rc = run_copy(segs, stream);
+    if (rc != FLASHOPTIM_OK) return rc;
+    *step_out = get_i64(got.data() + 16);
+    (void)get_u32;
+    return FLASHOPTIM_OK;
+}
+
+const char* flashoptim_strerror(int status) {
+    switch (status) {
+        case FLASHOPTIM_OK: return "ok";
+        case FLASHOPTIM_ERR_INVALID_ARG: return "invalid argument";
+        case FLASHOPTIM_ERR_MISALIGNED: return "device pointer is not 16-byte aligned";
+        case FLASHOPTIM_ERR_NUMEL_RANGE: return "numel out of range";
+        case FLASHOPTIM_ERR_HIP: return "HIP runtime error";
+        case FLASHOPTIM_ERR_BAD_BLOB: return "checkpoint blob too small or does not match the tensor list";
+        default: return "unknown status";
+    }
+}
+
+int flashoptim_last_hip_error(void) { return g_last_hip_error; }
+
+int flashoptim_release_cache(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!g_plans.empty()) (void)hipDeviceSynchronize();
+    for (auto& kv : g_plans) destroy_plan(kv.second);
+    g_plans.clear();
+    g_index.clear();
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_version(void) { return kVersion; }
+
+}  // extern "C"

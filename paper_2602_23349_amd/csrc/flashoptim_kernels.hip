@@ -1,0 +1,493 @@
+// FlashOptim device code for gfx950 (MI355X): the fused optimizer-step kernels
+// (paper Algorithms 4, 5, 6), the standalone codecs (Algorithms 1, 2, 3) and the
+// checkpoint gather/scatter copy.
+//
+// Numerical contract.  Every floating-point operation is one IEEE binary32
+// operation (round-to-nearest-even, subnormals kept).  This file must be built
+// with -ffp-contract=off and correctly rounded division / square root (hipcc's
+// default), because 8-bit codes and correction bytes are compared bit for bit
+// against an independent CPU implementation of the same algorithms.
+//
+// The step is bandwidth-bound by definition (12.25 algorithmic bytes per parameter
+// for AdamW), but an exactly rounded body costs on the order of a hundred VALU
+// issue slots per parameter, which at 8 TB/s is of the same order as the chip's
+// non-packed FP32 rate.  The design choices below are about keeping VALU work per
+// element low without changing a single rounding:
+//   * decoding a state code is a function of one byte: rho/127, code/255 and
+//     phi_m^-1(code/127) come from three 256-entry LDS tables that each workgroup
+//     fills once with the same IEEE divisions the definition uses;
+//   * 2^l scalings of Algorithm 1 are single v_ldexp_f32 operations (exact, or one
+//     rounding when the result is subnormal - the same rounding the two-factor
+//     form of Algorithm 1 performs);
+//   * Round(x) to an 8-bit integer is one FP32 addition of 1.5 * 2^23, whose low
+//     mantissa byte is the round-half-even integer in two's complement;
+//   * BF16 rounding uses the hardware v_cvt_pk_bf16_f32 (two elements per issue).
+//
+// Work decomposition.  A lane owns 16 consecutive elements per tile, so every
+// stream moves as 128-bit vectors and a quantisation group (32 elements) is exactly
+// two adjacent lanes: the group absmax needs one DPP lane swap and no LDS.
+// A workgroup (256 lanes) handles one chunk of kChunkElems consecutive elements of
+// one tensor; a chunk table maps blockIdx.x -> (tensor, chunk) so that one launch
+// covers a whole parameter list.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "flashoptim_device.h"
+
+namespace fo {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+
+// ------------------------------------------------------------------ helpers --
+
+__device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
+__device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
+
+// Value held by the lane's partner in its quad pair (lane ^ 1).
+__device__ __forceinline__ float swap_pair(float x) {
+    return u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), 0xB1 /* quad_perm [1,0,3,2] */,
+                                                     0xf, 0xf, false));
+}
+
+// Round-half-even of y (|y| <= 2^21) to an integer, returned in two's complement in the
+// low bits of the result.
+__device__ __forceinline__ uint32_t round_to_int_bits(float y) { return f2u(y + 12582912.0f); }
+
+// log2 of half the BF16 ULP of the value whose BF16 bit pattern is `b` (Algorithm 1:
+// l = floor(log2 ULP(theta')) - 1).  Zero and subnormals use the lowest binade's spacing.
+__device__ __forceinline__ int half_ulp_log2(uint32_t b) {
+    int E = (int)((b >> 7) & 0xffu);
+    E = E < 1 ? 1 : E;
+    return E - 135;
+}
+
+// C^-1: theta' (bits in the low 16 of b, value `base`) and q = rho/127 -> theta_hat (Eq. 2).
+__device__ __forceinline__ float reconstruct1(uint32_t b, float base, float q) {
+    return base + ldexpf(q, half_ulp_log2(b));
+}
+
+// Second half of C for one element whose BF16 rounding `b` (low 16 bits) is known:
+// rho = Round(Clamp(e * 2^-l, -1, 1) * 127) as a byte (Eq. 1).  Non-finite theta' -> 0.
+__device__ __forceinline__ uint32_t rho_byte(float theta, uint32_t b) {
+    const float base = u2f(b << 16);
+    const float e = theta - base;
+    const int E = (int)((b >> 7) & 0xffu);
+    const float en = ldexpf(e, 135 - (E < 1 ? 1 : E));
+    const float c = __builtin_amdgcn_fmed3f(en, -1.0f, 1.0f);
+    const uint32_t r = round_to_int_bits(c * 127.0f) & 0xffu;
+    return E == 255 ? 0u : r;
+}
+
+// BF16 round-to-nearest-even of two floats: a in the low half, b in the high half.
+__device__ __forceinline__ uint32_t bf16_pack(float a, float b) {
+    floatx2_t f = {a, b};
+    bf16x2_t r = __builtin_convertvector(f, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// FP16 scale of a group from its FP32 absmax: saturate at 65504, round to nearest even.
+// Returns the FP16 bits; *s is the scale as the decoder will read it, *r its reciprocal
+// (0 when the scale is 0, so that every code of the group becomes 0).
+__device__ __forceinline__ uint32_t group_scale(float absmax, float* r) {
+    const float a = fminf(absmax, 65504.0f);
+    const _Float16 h = (_Float16)a;
+    const float s = (float)h;
+    *r = (s == 0.0f) ? 0.0f : 1.0f / s;
+    return (uint32_t)__builtin_bit_cast(uint16_t, h);
+}
+
+// Q_m code of one element given the reciprocal group scale (Algorithm 2, lines 4-6).
+__device__ __forceinline__ uint32_t m_code(float m, float r) {
+    const float m1 = m * r;
+    const float num = 2.0f * m1;
+    const float den = 1.0f + fabsf(m1);
+    const float m2 = num / den;
+    const float y = __builtin_amdgcn_fmed3f(m2 * 127.0f, -127.0f, 127.0f);
+    return round_to_int_bits(y) & 0xffu;
+}
+
+// Q_v code of one element from sqrt(v) and the reciprocal group scale (Algorithm 3, line 5).
+__device__ __forceinline__ uint32_t v_code(float vroot, float r) {
+    const float y = __builtin_amdgcn_fmed3f((vroot * r) * 255.0f, 0.0f, 255.0f);
+    return round_to_int_bits(y) & 0xffu;
+}
+
+__device__ __forceinline__ uint32_t pack4(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
+    return c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+}
+
+// ------------------------------------------------------------- decode tables --
+
+struct DecodeTables {
+    float rho[256];   // (float)(int8)i / 127
+    float m[256];     // phi_m^-1((float)(int8)i / 127)
+    float v[256];     // (float)i / 255
+};
+
+__device__ __forceinline__ void fill_tables(DecodeTables& t, int tid) {
+    // one entry per lane; blockDim.x == 256
+    const float sb = (float)(int)(int8_t)tid;
+    const float z = sb / 127.0f;
+    t.rho[tid] = z;
+    t.m[tid] = z / (2.0f - fabsf(z));
+    t.v[tid] = (float)tid / 255.0f;
+}
+
+// -------------------------------------------------------------- lane vectors --
+
+struct LaneIO {
+    uint32_t p[8];    // 16 BF16 theta'
+    uint32_t g[8];    // 16 BF16 gradients
+    uint32_t r[4];    // 16 INT8 rho
+    uint32_t mq[4];   // 16 INT8 momentum codes
+    uint32_t vq[4];   // 16 UINT8 variance codes
+    uint32_t ms, vs;  // FP16 scale bits of the lane's group
+};
+
+template <bool HAS_V>
+__device__ __forceinline__ void load_full(LaneIO& x, const TensorDev& T, int64_t off) {
+    const uint4* p = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(T.param) + off);
+    const uint4* g = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(T.grad) + off);
+    uint4 a = p[0], b = p[1];
+    x.p[0] = a.x; x.p[1] = a.y; x.p[2] = a.z; x.p[3] = a.w; x.p[4] = b.x; x.p[5] = b.y; x.p[6] = b.z; x.p[7] = b.w;
+    a = g[0]; b = g[1];
+    x.g[0] = a.x; x.g[1] = a.y; x.g[2] = a.z; x.g[3] = a.w; x.g[4] = b.x; x.g[5] = b.y; x.g[6] = b.z; x.g[7] = b.w;
+    a = *reinterpret_cast<const uint4*>(T.rho + off);
+    x.r[0] = a.x; x.r[1] = a.y; x.r[2] = a.z; x.r[3] = a.w;
+    a = *reinterpret_cast<const uint4*>(T.m_q + off);
+    x.mq[0] = a.x; x.mq[1] = a.y; x.mq[2] = a.z; x.mq[3] = a.w;
+    x.ms = T.m_scale[off >> 5];
+    if (HAS_V) {
+        a = *reinterpret_cast<const uint4*>(T.v_q + off);
+        x.vq[0] = a.x; x.vq[1] = a.y; x.vq[2] = a.z; x.vq[3] = a.w;
+        x.vs = T.v_scale[off >> 5];
+    }
+}
+
+// Ragged end of a tensor: element-wise loads, missing elements read as zero (a zero
+// element yields zero moments and therefore never raises its group's absmax).
+template <bool HAS_V>
+__device__ __forceinline__ void load_tail(LaneIO& x, const TensorDev& T, int64_t off, int cnt) {
+    const uint16_t* p = reinterpret_cast<const uint16_t*>(T.param) + off;
+    const uint16_t* g = reinterpret_cast<const uint16_t*>(T.grad) + off;
+    const uint8_t* r = reinterpret_cast<const uint8_t*>(T.rho) + off;
+    const uint8_t* mq = reinterpret_cast<const uint8_t*>(T.m_q) + off;
+    const uint8_t* vq = T.v_q + off;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        uint32_t lo = (2 * j < cnt) ? p[2 * j] : 0u, hi = (2 * j + 1 < cnt) ? p[2 * j + 1] : 0u;
+        x.p[j] = lo | (hi << 16);
+        lo = (2 * j < cnt) ? g[2 * j] : 0u; hi = (2 * j + 1 < cnt) ? g[2 * j + 1] : 0u;
+        x.g[j] = lo | (hi << 16);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        uint32_t w = 0, wm = 0, wv = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (4 * j + k < cnt) {
+                w |= (uint32_t)r[4 * j + k] << (8 * k);
+                wm |= (uint32_t)mq[4 * j + k] << (8 * k);
+                if (HAS_V) wv |= (uint32_t)vq[4 * j + k] << (8 * k);
+            }
+        }
+        x.r[j] = w; x.mq[j] = wm; x.vq[j] = wv;
+    }
+    x.ms = 0; x.vs = 0;
+    if (cnt > 0) {
+        x.ms = T.m_scale[off >> 5];
+        if (HAS_V) x.vs = T.v_scale[off >> 5];
+    }
+}
+
+template <bool HAS_V>
+__device__ __forceinline__ void store_full(const LaneIO& y, const TensorDev& T, int64_t off, bool group_leader) {
+    uint4* p = reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(T.param) + off);
+    p[0] = make_uint4(y.p[0], y.p[1], y.p[2], y.p[3]);
+    p[1] = make_uint4(y.p[4], y.p[5], y.p[6], y.p[7]);
+    *reinterpret_cast<uint4*>(T.rho + off) = make_uint4(y.r[0], y.r[1], y.r[2], y.r[3]);
+    *reinterpret_cast<uint4*>(T.m_q + off) = make_uint4(y.mq[0], y.mq[1], y.mq[2], y.mq[3]);
+    if (HAS_V) *reinterpret_cast<uint4*>(T.v_q + off) = make_uint4(y.vq[0], y.vq[1], y.vq[2], y.vq[3]);
+    if (group_leader) {
+        T.m_scale[off >> 5] = (uint16_t)y.ms;
+        if (HAS_V) T.v_scale[off >> 5] = (uint16_t)y.vs;
+    }
+}
+
+template <bool HAS_V>
+__device__ __forceinline__ void store_tail(const LaneIO& y, const TensorDev& T, int64_t off, int cnt,
+                                           bool group_leader) {
+    uint16_t* p = reinterpret_cast<uint16_t*>(T.param) + off;
+    uint8_t* r = reinterpret_cast<uint8_t*>(T.rho) + off;
+    uint8_t* mq = reinterpret_cast<uint8_t*>(T.m_q) + off;
+    uint8_t* vq = T.v_q + off;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        if (i < cnt) {
+            p[i] = (uint16_t)(y.p[i >> 1] >> (16 * (i & 1)));
+            r[i] = (uint8_t)(y.r[i >> 2] >> (8 * (i & 3)));
+            mq[i] = (uint8_t)(y.mq[i >> 2] >> (8 * (i & 3)));
+            if (HAS_V) vq[i] = (uint8_t)(y.vq[i >> 2] >> (8 * (i & 3)));
+        }
+    }
+    if (group_leader && cnt > 0) {
+        T.m_scale[off >> 5] = (uint16_t)y.ms;
+        if (HAS_V) T.v_scale[off >> 5] = (uint16_t)y.vs;
+    }
+}
+
+// ------------------------------------------------------- the per-lane update --
+//
+// KIND: 0 AdamW (Algorithm 4), 1 SGD (Algorithm 5), 2 Lion (Algorithm 6).
+// Operates on the 16 elements of one lane; the lane's pair partner (lane ^ 1) holds the
+// other half of the same 32-element group and must execute this function together with it.
+template <int KIND>
+__device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const DecodeTables& tab,
+                                            const StepConsts& c, float lr, float wd) {
+    constexpr bool HAS_V = (KIND == 0);
+    const float s_m = (float)__builtin_bit_cast(_Float16, (uint16_t)x.ms);
+    const float s_v = HAS_V ? (float)__builtin_bit_cast(_Float16, (uint16_t)x.vs) : 0.0f;
+
+    float mt[16];     // new momentum
+    float vr[16];     // sqrt of the new variance (AdamW)
+    float tht[16];    // new master weight
+    float amax_m = 0.0f, amax_v = 0.0f;
+
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t pw = x.p[i >> 1], gw = x.g[i >> 1];
+        const uint32_t pb = (i & 1) ? (pw >> 16) : (pw & 0xffffu);
+        const float base = (i & 1) ? u2f(pw & 0xffff0000u) : u2f(pw << 16);
+        const float g = (i & 1) ? u2f(gw & 0xffff0000u) : u2f(gw << 16);
+        const uint32_t rb = (x.r[i >> 2] >> (8 * (i & 3))) & 0xffu;
+        const uint32_t mb = (x.mq[i >> 2] >> (8 * (i & 3))) & 0xffu;
+        // prologue: reconstruct optimizer state and master weight
+        const float m = tab.m[mb] * s_m;                         // Q_m^-1
+        const float th = reconstruct1(pb, base, tab.rho[rb]);    // C^-1
+        float m_new, th_new;
+        if (KIND == 0) {
+            const uint32_t vb = (x.vq[i >> 2] >> (8 * (i & 3))) & 0xffu;
+            const float v1 = tab.v[vb] * s_v;                    // Q_v^-1
+            const float v = v1 * v1;
+            m_new = (c.beta1 * m) + (c.omb1 * g);
+            const float gg = g * g;
+            const float v_new = (c.beta2 * v) + (c.omb2 * gg);
+            const float mhat = m_new * c.rbc1;
+            const float vhat = v_new * c.rbc2;
+            const float den = sqrtf(vhat) + c.eps;
+            const float upd = (mhat / den) + (wd * th);
+            th_new = th - (lr * upd);
+            const float root = sqrtf(v_new);                     // v' of Algorithm 3
+            vr[i] = root;
+            amax_v = fmaxf(amax_v, root);
+        } else if (KIND == 1) {
+            m_new = (c.beta1 * m) + g;                           // beta1 carries the momentum mu
+            th_new = th - (lr * (m_new + (wd * th)));
+        } else {
+            const float cc = (c.beta1 * m) + (c.omb1 * g);
+            const float u = (cc > 0.0f) ? 1.0f : ((cc < 0.0f) ? -1.0f : 0.0f);
+            m_new = (c.beta2 * m) + (c.omb2 * g);
+            th_new = th - (lr * (u + (wd * th)));
+        }
+        mt[i] = m_new;
+        tht[i] = th_new;
+        amax_m = fmaxf(amax_m, fabsf(m_new));
+    }
+
+    // epilogue: group scales (one DPP swap joins the two lanes of a group)
+    amax_m = fmaxf(amax_m, swap_pair(amax_m));
+    float r_m, r_v = 0.0f;
+    y.ms = group_scale(amax_m, &r_m);
+    if (HAS_V) {
+        amax_v = fmaxf(amax_v, swap_pair(amax_v));
+        y.vs = group_scale(amax_v, &r_v);
+    }
+
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        y.mq[j] = pack4(m_code(mt[4 * j], r_m), m_code(mt[4 * j + 1], r_m),
+                        m_code(mt[4 * j + 2], r_m), m_code(mt[4 * j + 3], r_m));
+        if (HAS_V)
+            y.vq[j] = pack4(v_code(vr[4 * j], r_v), v_code(vr[4 * j + 1], r_v),
+                            v_code(vr[4 * j + 2], r_v), v_code(vr[4 * j + 3], r_v));
+    }
+    // epilogue: split the new master weight
+#pragma unroll
+    for (int j = 0; j < 8; ++j) y.p[j] = bf16_pack(tht[2 * j], tht[2 * j + 1]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t w0 = y.p[2 * j], w1 = y.p[2 * j + 1];
+        y.r[j] = pack4(rho_byte(tht[4 * j], w0 & 0xffffu), rho_byte(tht[4 * j + 1], w0 >> 16),
+                       rho_byte(tht[4 * j + 2], w1 & 0xffffu), rho_byte(tht[4 * j + 3], w1 >> 16));
+    }
+}
+
+// ------------------------------------------------------------ step kernels --
+
+template <int KIND, bool DIRECT>
+__global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
+    constexpr bool HAS_V = (KIND == 0);
+    __shared__ DecodeTables tab;
+    const int tid = (int)threadIdx.x;
+    fill_tables(tab, tid);
+
+    TensorDev T;
+    int64_t chunk;
+    if (DIRECT) {
+        T = a.single;
+        chunk = (int64_t)blockIdx.x;
+    } else {
+        const uint2 ck = a.chunks[blockIdx.x];
+        T = a.tensors[ck.x];
+        chunk = (int64_t)ck.y;
+    }
+    __syncthreads();
+
+    const int64_t begin = chunk * kChunkElems;
+    const int64_t end = (T.numel - begin < kChunkElems) ? T.numel : begin + kChunkElems;
+    const bool leader = (tid & 1) == 0;
+
+    for (int64_t off = begin + (int64_t)tid * kVec; (off & ~(int64_t)31) < end; off += kTileElems) {
+        const int64_t left = end - off;
+        const int cnt = left >= kVec ? kVec : (left > 0 ? (int)left : 0);
+        LaneIO x, y;
+        if (cnt == kVec) load_full<HAS_V>(x, T, off);
+        else load_tail<HAS_V>(x, T, off, cnt);
+        update_lane<KIND>(x, y, tab, a.c, T.lr, T.wd);
+        if (cnt == kVec) store_full<HAS_V>(y, T, off, leader);
+        else store_tail<HAS_V>(y, T, off, cnt, leader);
+    }
+}
+
+template __global__ void step_kernel<0, false>(StepArgs);
+template __global__ void step_kernel<0, true>(StepArgs);
+template __global__ void step_kernel<1, false>(StepArgs);
+template __global__ void step_kernel<1, true>(StepArgs);
+template __global__ void step_kernel<2, false>(StepArgs);
+template __global__ void step_kernel<2, true>(StepArgs);
+
+void launch_step(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
+    const dim3 grid((unsigned)n_blocks), block(kThreads);
+    if (kind == 0) {
+        if (direct) hipLaunchKernelGGL((step_kernel<0, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((step_kernel<0, false>), grid, block, 0, s, a);
+    } else if (kind == 1) {
+        if (direct) hipLaunchKernelGGL((step_kernel<1, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((step_kernel<1, false>), grid, block, 0, s, a);
+    } else {
+        if (direct) hipLaunchKernelGGL((step_kernel<2, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((step_kernel<2, false>), grid, block, 0, s, a);
+    }
+}
+
+// -------------------------------------------------------- standalone codecs --
+//
+// Not on the per-step path (used at initialisation, for inspection and by tests):
+// one lane per element / per group, plain global accesses.
+
+__global__ __launch_bounds__(kThreads) void split_kernel(const float* theta, uint16_t* param, int8_t* rho,
+                                                         int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    const float t = theta[i];
+    const uint32_t b = bf16_pack(t, 0.0f) & 0xffffu;
+    param[i] = (uint16_t)b;
+    rho[i] = (int8_t)rho_byte(t, b);
+}
+
+__global__ __launch_bounds__(kThreads) void reconstruct_kernel(const uint16_t* param, const int8_t* rho,
+                                                               float* theta, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t b = param[i];
+    const float q = (float)(int)rho[i] / 127.0f;
+    theta[i] = reconstruct1(b, u2f(b << 16), q);
+}
+
+// One lane per group of 32.
+template <bool VARIANCE>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const float* x, uint8_t* q, uint16_t* scale,
+                                                            int64_t n) {
+    const int64_t grp = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t o = grp * kGroup;
+    if (o >= n) return;
+    const int cnt = (n - o < kGroup) ? (int)(n - o) : kGroup;
+    float a = 0.0f;
+    for (int i = 0; i < cnt; ++i) {
+        const float t = VARIANCE ? sqrtf(x[o + i]) : fabsf(x[o + i]);
+        a = fmaxf(a, t);
+    }
+    float r;
+    scale[grp] = (uint16_t)group_scale(a, &r);
+    for (int i = 0; i < cnt; ++i)
+        q[o + i] = (uint8_t)(VARIANCE ? v_code(sqrtf(x[o + i]), r) : m_code(x[o + i], r));
+}
+
+template <bool VARIANCE>
+__global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* q, const uint16_t* scale, float* x,
+                                                              int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    const float s = (float)__builtin_bit_cast(_Float16, scale[i >> 5]);
+    if (VARIANCE) {
+        const float v1 = ((float)q[i] / 255.0f) * s;
+        x[i] = v1 * v1;
+    } else {
+        const float z = (float)(int)(int8_t)q[i] / 127.0f;
+        x[i] = (z / (2.0f - fabsf(z))) * s;
+    }
+}
+
+static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads); }
+
+void launch_split(const float* theta, void* param, int8_t* rho, int64_t n, hipStream_t s) {
+    hipLaunchKernelGGL(split_kernel, dim3(blocks_for(n)), dim3(kThreads), 0, s, theta, (uint16_t*)param, rho, n);
+}
+void launch_reconstruct(const void* param, const int8_t* rho, float* theta, int64_t n, hipStream_t s) {
+    hipLaunchKernelGGL(reconstruct_kernel, dim3(blocks_for(n)), dim3(kThreads), 0, s, (const uint16_t*)param, rho,
+                       theta, n);
+}
+void launch_quantize(bool variance, const float* x, void* q, uint16_t* scale, int64_t n, hipStream_t s) {
+    const int64_t groups = (n + kGroup - 1) / kGroup;
+    if (variance) hipLaunchKernelGGL((quantize_kernel<true>), dim3(blocks_for(groups)), dim3(kThreads), 0, s, x,
+                                     (uint8_t*)q, scale, n);
+    else hipLaunchKernelGGL((quantize_kernel<false>), dim3(blocks_for(groups)), dim3(kThreads), 0, s, x,
+                            (uint8_t*)q, scale, n);
+}
+void launch_dequantize(bool variance, const void* q, const uint16_t* scale, float* x, int64_t n, hipStream_t s) {
+    if (variance) hipLaunchKernelGGL((dequantize_kernel<true>), dim3(blocks_for(n)), dim3(kThreads), 0, s,
+                                     (const uint8_t*)q, scale, x, n);
+    else hipLaunchKernelGGL((dequantize_kernel<false>), dim3(blocks_for(n)), dim3(kThreads), 0, s,
+                            (const uint8_t*)q, scale, x, n);
+}
+
+// ----------------------------------------------------------- checkpoint copy --
+//
+// Gather / scatter of byte segments: each workgroup copies one kCopyChunkBytes piece of one
+// segment with 128-bit accesses (segment starts are 16-byte aligned on both sides), the
+// ragged end byte by byte, and - when packing - zero-fills the padding up to pad_bytes.
+
+__global__ __launch_bounds__(kThreads) void copy_kernel(const CopySegment* segs, const uint2* chunks) {
+    const uint2 ck = chunks[blockIdx.x];
+    const CopySegment sg = segs[ck.x];
+    const int64_t begin = (int64_t)ck.y * kCopyChunkBytes;
+    const int64_t total = sg.pad_bytes;                  // >= sg.bytes
+    const int64_t end = (total - begin < kCopyChunkBytes) ? total : begin + kCopyChunkBytes;
+    const uint8_t* src = sg.src;
+    uint8_t* dst = sg.dst;
+    for (int64_t o = begin + (int64_t)threadIdx.x * 16; o < end; o += (int64_t)kThreads * 16) {
+        if (o + 16 <= sg.bytes) {
+            *reinterpret_cast<uint4*>(dst + o) = *reinterpret_cast<const uint4*>(src + o);
+        } else {
+            for (int k = 0; k < 16 && o + k < end; ++k) dst[o + k] = (o + k < sg.bytes) ? src[o + k] : (uint8_t)0;
+        }
+    }
+}
+
+void launch_copy(const CopySegment* segs, const uint2* chunks, int64_t n_chunks, hipStream_t s) {
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)n_chunks), dim3(kThreads), 0, s, segs, chunks);
+}
+
+}  // namespace fo

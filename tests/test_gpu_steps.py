@@ -1,0 +1,201 @@
+"""GPU parity of the fused optimizer steps against the CPU oracle on the small and medium
+workloads: flat 2^20 tensor (AdamW, 1 and 100 steps after 10 warm-up steps), the GPT-2 124M
+list (SGD, Lion), the ResNet-50 list (AdamW, heavy-tailed gradients), ragged tensor sizes, and
+hand-built edge cases.  All calls go through the C ABI via the Python binding."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_23349_amd as fo
+import workloads as W
+from helpers import (bits16, compare_state, download, grads_for, to_dev_u16, total_mismatches, upload_state,
+                     weight_decay_for)
+
+pytestmark = pytest.mark.gpu
+
+ADAMW = dict(lr=1e-3, wd=0.01, beta1=0.9, beta2=0.999, eps=1e-8)
+SGD = dict(lr=1e-2, wd=5e-4, momentum=0.9)
+LION = dict(lr=1e-4, wd=0.1, beta1=0.9, beta2=0.99)
+
+
+def _g_bits(g):
+    return g.view(torch.int16).numpy().view(np.uint16)
+
+
+def _oracle_step(kind, st, g, lr, wd, hp, t):
+    if kind == "adamw":
+        oracle.adamw_step(st, g, lr, wd, hp["beta1"], hp["beta2"], hp["eps"], t)
+    elif kind == "sgd":
+        oracle.sgd_step(st, g, lr, wd, hp["momentum"])
+    else:
+        oracle.lion_step(st, g, lr, wd, hp["beta1"], hp["beta2"])
+
+
+def _gpu_step(kind, tl, hp, t):
+    if kind == "adamw":
+        fo.adamw_step(tl, hp["beta1"], hp["beta2"], hp["eps"], t)
+    elif kind == "sgd":
+        fo.sgd_step(tl, hp["momentum"])
+    else:
+        fo.lion_step(tl, hp["beta1"], hp["beta2"])
+
+
+def test_flat_tensor_adamw_1_and_100_steps():
+    # workload 1: 2^20 parameters, states from 10 warm-up steps (run by the oracle), then parity after
+    # 1 and after 100 further steps
+    spec = W.flat_tensor(1 << 20)[0]
+    st = oracle.TensorState(W.theta0(spec, 0, seed=0).numpy(), "adamw")
+    for t in range(1, 11):
+        oracle.adamw_step(st, _g_bits(W.grad_bf16(spec, 0, t, seed=0)), ADAMW["lr"], ADAMW["wd"], 0.9, 0.999, 1e-8, t)
+    buf = upload_state(st)
+    buf.lr, buf.weight_decay = ADAMW["lr"], ADAMW["wd"]
+    tl = fo.TensorList([buf])
+    report = []
+    for t in range(11, 111):
+        g = W.grad_bf16(spec, 0, t, seed=0)
+        buf.grad.copy_(g.cuda())
+        fo.adamw_step(tl, 0.9, 0.999, 1e-8, t)
+        oracle.adamw_step(st, _g_bits(g), ADAMW["lr"], ADAMW["wd"], 0.9, 0.999, 1e-8, t)
+        if t in (11, 12, 20, 60, 110):
+            compare_state(download(buf), st, where=f"flat t={t}", report=report)
+    print("mismatch report (where, stream, n_diff, max_lsb, n):", [r for r in report if r[2]])
+    assert total_mismatches(report) == 0     # designed to be exact; the 1e-5 allowance is unused
+
+
+@pytest.mark.parametrize("kind,hp", [("adamw", ADAMW), ("sgd", SGD), ("lion", LION)])
+def test_ragged_sizes_multi_tensor(kind, hp):
+    # tensors whose sizes straddle the group / vector / tile / chunk boundaries, in ONE launch
+    specs = W.odd_sizes()
+    states = [oracle.TensorState(W.theta0(sp, i, seed=3).numpy(), kind) for i, sp in enumerate(specs)]
+    bufs = [upload_state(s) for s in states]
+    for b, sp in zip(bufs, specs):
+        b.lr, b.weight_decay = hp["lr"], weight_decay_for(sp, hp["wd"])
+    tl = fo.TensorList(bufs)
+    report = []
+    for t in (1, 2, 3):
+        grads = grads_for(specs, t, seed=3, per_tensor_sigma=True)
+        for b, g in zip(bufs, grads):
+            b.grad.copy_(g.cuda())
+        _gpu_step(kind, tl, hp, t)
+        for i, (s, g, sp) in enumerate(zip(states, grads, specs)):
+            _oracle_step(kind, s, _g_bits(g), hp["lr"], weight_decay_for(sp, hp["wd"]), hp, t)
+            compare_state(download(bufs[i]), s, where=f"{kind} {sp.name} t={t}", report=report)
+    assert total_mismatches(report) == 0
+
+
+def test_single_tensor_direct_path_matches_list_path():
+    # a list of length one takes the table-free launch (the gradient-release call)
+    spec = W.ParamSpec("x", (3 * 8192 + 4096 + 77,), "matrix")
+    st = oracle.TensorState(W.theta0(spec, 0, seed=4).numpy(), "adamw")
+    buf = upload_state(st)
+    buf.lr, buf.weight_decay = ADAMW["lr"], ADAMW["wd"]
+    tl = fo.TensorList([buf])
+    for t in (1, 2):
+        g = W.grad_bf16(spec, 0, t, seed=4)
+        buf.grad.copy_(g.cuda())
+        fo.adamw_step(tl, 0.9, 0.999, 1e-8, t)
+        oracle.adamw_step(st, _g_bits(g), ADAMW["lr"], ADAMW["wd"], 0.9, 0.999, 1e-8, t)
+    rep = compare_state(download(buf), st, where="direct")
+    assert sum(r[1] for r in rep) == 0
+
+
+def test_edge_values_in_one_step():
+    # zero weights (theta' = 0 path), exact powers of two, BF16-subnormal weights, zero gradients,
+    # huge and tiny gradients (scale saturation / underflow), zero state
+    n = 32 * 12
+    theta = np.zeros(n, np.float32)
+    theta[32:64] = 1.0
+    theta[64:96] = -2.0 ** -126
+    theta[96:128] = np.float32(1e-40)
+    theta[128:160] = 3.0e38
+    theta[160:] = (np.random.default_rng(5).standard_normal(n - 160) * 0.02).astype(np.float32)
+    g = np.zeros(n, np.float32)
+    g[0:16] = 1e-3
+    g[40:48] = -7.0
+    g[192:224] = 1e-20      # v underflows towards subnormals, FP16 scale underflows
+    g[224:256] = 3e4        # sqrt(v) fits, m scale near the FP16 maximum
+    g[256:288] = 1e30       # g^2 overflows FP32: v = inf, both scales saturate at 65504
+    g[288:] = np.random.default_rng(6).standard_normal(n - 288) * 1e-3
+    gb = torch.from_numpy(g).to(torch.bfloat16)
+    for kind, hp in (("adamw", ADAMW), ("sgd", SGD), ("lion", LION)):
+        st = oracle.TensorState(theta, kind)
+        buf = upload_state(st)
+        buf.lr, buf.weight_decay = hp["lr"], hp["wd"]
+        buf.grad.copy_(gb.cuda())
+        tl = fo.TensorList([buf])
+        for t in (1, 2):
+            _gpu_step(kind, tl, hp, t)
+            _oracle_step(kind, st, _g_bits(gb), hp["lr"], hp["wd"], hp, t)
+            rep = compare_state(download(buf), st, where=f"edge {kind} t={t}")
+            assert sum(r[1] for r in rep) == 0
+            assert np.isfinite(oracle.bf16_to_f32(st.thp)).all()
+
+
+def _run_list(kind, hp, specs, seed, dist, scale, per_tensor_sigma, steps, nthreads=0):
+    states = [oracle.TensorState(W.theta0(sp, i, seed=seed).numpy(), kind) for i, sp in enumerate(specs)]
+    bufs = [upload_state(s) for s in states]
+    for b, sp in zip(bufs, specs):
+        b.lr, b.weight_decay = hp["lr"], weight_decay_for(sp, hp["wd"])
+    tl = fo.TensorList(bufs)
+    report = []
+    subnormal_scales = 0
+    for t in steps:
+        grads = grads_for(specs, t, seed=seed, dist=dist, scale=scale, per_tensor_sigma=per_tensor_sigma)
+        for b, g in zip(bufs, grads):
+            b.grad.copy_(g.cuda(), non_blocking=False)
+        _gpu_step(kind, tl, hp, t)
+        torch.cuda.synchronize()
+        for i, (s, g, sp) in enumerate(zip(states, grads, specs)):
+            _oracle_step(kind, s, _g_bits(g), hp["lr"], weight_decay_for(sp, hp["wd"]), hp, t)
+            compare_state(download(bufs[i]), s, where=f"{kind} {sp.name} t={t}", report=report)
+            subnormal_scales += int(((s.ms > 0) & (s.ms < 0x0400)).sum())
+    bad = [r for r in report if r[2]]
+    print(f"{kind}: {len(specs)} tensors, steps {list(steps)}: code mismatches {bad if bad else 'none'}; "
+          f"groups with FP16-subnormal momentum scales: {subnormal_scales}")
+    assert total_mismatches(report) == 0
+
+
+def test_gpt2_list_sgd():
+    # workload 2: GPT-2 124M parameter list, per-tensor gradient scale log-uniform in [1e-5, 1e-2]
+    _run_list("sgd", SGD, W.gpt2_small(), seed=0, dist="normal", scale=None, per_tensor_sigma=True, steps=(1, 2, 3))
+
+
+def test_gpt2_list_lion():
+    _run_list("lion", LION, W.gpt2_small(), seed=0, dist="normal", scale=None, per_tensor_sigma=True, steps=(1, 2, 3))
+
+
+def test_resnet50_list_adamw_heavy_tailed():
+    # workload 3: ResNet-50 list (161 tensors, 107 of them under 4K elements), Student-t(3) gradients
+    _run_list("adamw", ADAMW, W.resnet50(), seed=0, dist="student3", scale=1e-3, per_tensor_sigma=False, steps=(1, 2, 3))
+
+
+def test_checkpoint_pack_unpack_small_lists():
+    for kind in ("adamw", "sgd"):
+        specs = W.odd_sizes()[:14]
+        states = []
+        for i, sp in enumerate(specs):
+            s = oracle.TensorState(W.theta0(sp, i, seed=9).numpy(), kind)
+            rs = W.random_state(sp.numel, i, seed=9, with_variance=(kind == "adamw"))
+            s.rho = rs["rho"].numpy(); s.mq = rs["mq"].numpy()
+            s.ms = rs["ms"].view(torch.int16).numpy().view(np.uint16)
+            if kind == "adamw":
+                s.vq = rs["vq"].numpy(); s.vs = rs["vs"].view(torch.int16).numpy().view(np.uint16)
+            states.append(s)
+        bufs = [upload_state(s, with_grad=False) for s in states]
+        size = fo.checkpoint_size(kind, [s.n for s in states])
+        blob = torch.full((size,), 0xAB, dtype=torch.uint8, device="cuda")
+        fo.checkpoint_pack(kind, bufs, 4242, blob)
+        want = oracle.checkpoint_pack(kind, states, 4242)
+        assert np.array_equal(blob.cpu().numpy(), want)
+        fresh = [fo.ParamBuffers(s.n, kind, with_grad=False) for s in states]
+        assert fo.checkpoint_unpack(kind, blob, fresh) == 4242
+        for f, s in zip(fresh, states):
+            rep = compare_state(download(f), s, where="unpack")
+            assert sum(r[1] for r in rep) == 0
+        # a blob packed for another list is rejected and nothing is written
+        with pytest.raises(fo.FlashOptimError):
+            fo.checkpoint_unpack(kind, blob, fresh[:-1])
+        blob2 = blob.clone(); blob2[0] = 0
+        with pytest.raises(fo.FlashOptimError):
+            fo.checkpoint_unpack(kind, blob2, fresh)
