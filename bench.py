@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused FlashOptim optimizer step on one MI355X.
+
+Default workload (the one the headline metric is quoted on): FlashAdamW over the
+Llama-3.1-8B parameter list (291 tensors, 8,030,261,248 parameters, 57.2 GB of resident
+state), one fused multi-tensor launch per step, synthetic values.  A "step" is one pass of the
+whole path: reconstruct master weights and states, AdamW update from BF16 gradients, re-quantise
+states, re-split weights.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line:  params/s (value), ms per step, the HBM roofline of the step kernel
+(algorithmic bytes per launch / mean launch time measured with HIP events on the launch stream),
+and the CPU oracle's throughput on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+BYTES_PER_PARAM = {"adamw": 12.25, "sgd": 10.125, "lion": 10.125}   # read + written, incl. FP16 scales
+HYPER = {
+    "adamw": dict(lr=1e-3, wd=0.01, beta1=0.9, beta2=0.999, eps=1e-8),
+    "sgd": dict(lr=1e-2, wd=5e-4, momentum=0.9),
+    "lion": dict(lr=1e-4, wd=0.1, beta1=0.9, beta2=0.99),
+}
+WORKLOADS = {
+    # name: (optimizer, shapes function name, gradient distribution, gradient scale / per-tensor sigma)
+    "llama31_8b_adamw": ("adamw", "llama31_8b", "normal", 1e-4),
+    "llama31_8b_sgd": ("sgd", "llama31_8b", "normal", 1e-4),
+    "llama31_8b_lion": ("lion", "llama31_8b", "normal", 1e-4),
+    "gpt2_sgd": ("sgd", "gpt2_small", "normal", None),
+    "gpt2_lion": ("lion", "gpt2_small", "normal", None),
+    "resnet50_adamw": ("adamw", "resnet50", "student3", 1e-3),
+    "flat_adamw": ("adamw", "flat_tensor", "normal", 1e-3),
+}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama31_8b_adamw", choices=sorted(WORKLOADS))
+    ap.add_argument("--mode", default="fused", choices=["fused", "grad_release", "ckpt_pack", "ckpt_unpack"],
+                    help="fused: one multi-tensor launch per step; grad_release: one call per tensor in "
+                         "reverse list order with a single reused gradient buffer; ckpt_pack / ckpt_unpack: "
+                         "a 'step' is one checkpoint gather / scatter of the whole list (a plain copy)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def build_state(fo, W, torch, specs, kind, hp, dist, scale, seed, with_grads):
+    """Device buffers for the whole list: theta_0 is drawn per tensor in FP32 on the device and split by
+    the library; gradients are drawn in BF16 on the device."""
+    bufs = []
+    for i, sp in enumerate(specs):
+        b = fo.ParamBuffers(sp.numel, kind, device="cuda", with_grad=with_grads)
+        th = W.theta0(sp, i, seed=seed, device="cuda")
+        fo.split_weights(th, b.param, b.rho)
+        del th
+        if with_grads:
+            sc = W.tensor_sigma(i, seed) if scale is None else scale
+            b.grad.copy_(W.grad_bf16(sp, i, 1, seed=seed, device="cuda", dist=dist, scale=sc))
+        b.lr, b.weight_decay = hp["lr"], (hp["wd"] if sp.role == "matrix" else 0.0)
+        bufs.append(b)
+    torch.cuda.synchronize()
+    return bufs
+
+
+def step_call(fo, kind, tl, hp, t):
+    if kind == "adamw":
+        fo.adamw_step(tl, hp["beta1"], hp["beta2"], hp["eps"], t)
+    elif kind == "sgd":
+        fo.sgd_step(tl, hp["momentum"])
+    else:
+        fo.lion_step(tl, hp["beta1"], hp["beta2"])
+
+
+def cpu_baseline(W, specs, kind, hp, dist, scale, seed, target_seconds):
+    """The oracle, as it stands, on a bounded sample of the same workload, on this host's cores."""
+    import numpy as np
+    import torch
+    import oracle
+
+    # sample: the first tensors of the list up to ~64M parameters (for the Llama list: the leading
+    # 64M-element slice of the embedding plus nothing else would be unrepresentative, so take one
+    # decoder layer's tensors when the list has them)
+    names = [s.name for s in specs]
+    if any(n.startswith("layers.0.") for n in names):
+        sample = [(i, s) for i, s in enumerate(specs) if s.name.startswith("layers.0.")]
+        what = "decoder layer 0 of the list (9 tensors)"
+    else:
+        sample, tot = [], 0
+        for i, s in enumerate(specs):
+            if tot > 64e6:
+                break
+            sample.append((i, s)); tot += s.numel
+        what = f"first {len(sample)} tensors of the list"
+    n = sum(s.numel for _, s in sample)
+    states, grads = [], []
+    for i, s in sample:
+        states.append(oracle.TensorState(W.theta0(s, i, seed=seed).numpy(), kind))
+        sc = W.tensor_sigma(i, seed) if scale is None else scale
+        grads.append(W.grad_bf16(s, i, 1, seed=seed, dist=dist, scale=sc).view(torch.int16).numpy().view(np.uint16))
+    threads = oracle.max_threads()
+
+    def one(t):
+        for (i, s), st, g in zip(sample, states, grads):
+            wd = hp["wd"] if s.role == "matrix" else 0.0
+            if kind == "adamw":
+                oracle.adamw_step(st, g, hp["lr"], wd, hp["beta1"], hp["beta2"], hp["eps"], t)
+            elif kind == "sgd":
+                oracle.sgd_step(st, g, hp["lr"], wd, hp["momentum"])
+            else:
+                oracle.lion_step(st, g, hp["lr"], wd, hp["beta1"], hp["beta2"])
+
+    one(1)                                  # untimed: page in, reach a non-zero state
+    t0 = time.perf_counter(); one(2); dt = time.perf_counter() - t0
+    reps = max(1, min(200, int(target_seconds / max(dt, 1e-3))))
+    t0 = time.perf_counter()
+    for r in range(reps):
+        one(3 + r)
+    total = time.perf_counter() - t0
+    return {"value": n * reps / total, "unit": "params/s", "cores": threads, "kind": "oracle",
+            "sample": f"{what}: {n} params x {reps} steps, {total:.1f} s"}
+
+
+def read_traffic(kind, workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary
+    for this workload has been recorded under profiles/."""
+    path = os.path.join(ROOT, "profiles", f"{kind}_step_{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=", 1)
+            try:
+                vals[k.strip()] = float(v.split()[0])
+            except ValueError:
+                pass
+    if "HBM_BYTES_PER_LAUNCH" in vals:
+        return vals["HBM_BYTES_PER_LAUNCH"]
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1. "
+              "The step needs no communication: a multi-GPU job runs this same kernel on each rank's shard.",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2602_23349_amd as fo
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    fo.load_library()
+    torch.cuda.set_device(0)
+
+    kind, shape_fn, dist, scale = WORKLOADS[args.workload]
+    hp = HYPER[kind]
+    specs = getattr(W, shape_fn)()
+    n_params = sum(s.numel for s in specs)
+    seed = 0
+    release = args.mode == "grad_release"
+    ckpt = args.mode.startswith("ckpt")
+
+    bufs = build_state(fo, W, torch, specs, kind, hp, dist, scale, seed, with_grads=not (release or ckpt))
+    tl = fo.TensorList(bufs)
+    stream = torch.cuda.current_stream()
+
+    if ckpt:
+        blob = torch.empty(fo.checkpoint_size(kind, [s.numel for s in specs]), dtype=torch.uint8, device="cuda")
+        fo.checkpoint_pack(kind, tl, 1, blob)
+
+        def do_step(t):
+            if args.mode == "ckpt_pack":
+                fo.checkpoint_pack(kind, tl, t, blob)
+            else:
+                fo.checkpoint_unpack(kind, blob, tl)
+    elif release:
+        # one reusable gradient buffer of the largest tensor's size; per-tensor calls in reverse order
+        gmax = max(s.numel for s in specs)
+        gbuf = W.grad_bf16(W.ParamSpec("g", (gmax,), "matrix"), 0, 1, seed=seed, device="cuda", dist="normal",
+                           scale=scale or 1e-3)
+        singles = []
+        for i in reversed(range(len(specs))):
+            tl.set_grad(i, gbuf)
+            singles.append(tl.slice(i))
+
+        def do_step(t):
+            for s in singles:
+                step_call(fo, kind, s, hp, t)
+    else:
+        def do_step(t):
+            step_call(fo, kind, tl, hp, t)
+
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        do_step(t)
+    torch.cuda.synchronize()
+
+    # timed region: K steps, HIP events on the stream the kernels are launched on
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    wall0 = time.perf_counter()
+    ev[0].record(stream)
+    for k in range(args.steps):
+        t += 1
+        do_step(t)
+        ev[k + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    per_step_ms = [ev[k].elapsed_time(ev[k + 1]) for k in range(args.steps)]
+    total_ms = ev[0].elapsed_time(ev[args.steps])
+    ms_per_step = total_ms / args.steps
+    value = n_params * args.steps / (total_ms * 1e-3)
+
+    launches = len(specs) if release else 1
+    algo_bytes = BYTES_PER_PARAM[kind] * n_params           # per step = per launch in fused mode
+    if ckpt:
+        payload = sum(2 * s.numel + s.numel * (3 if kind == "adamw" else 2)
+                      + 2 * ((s.numel + 31) // 32) * (2 if kind == "adamw" else 1) for s in specs)
+        algo_bytes = 2.0 * payload                          # every payload byte is read once and written once
+    achieved = algo_bytes / (ms_per_step * 1e-3) / 1e9
+    traffic = None if (release or ckpt) else read_traffic(kind, args.workload)
+    out = {
+        "metric": "optimizer_step_params_per_sec", "value": value, "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "optimizer": kind, "tensors": len(specs), "params": n_params,
+                   "mode": args.mode, "launches_per_step": launches,
+                   "resident_bytes_per_param": (7.125 if kind == "adamw" else 6.0625) - (2 if release else 0),
+                   "min_ms_step": min(per_step_ms), "max_ms_step": max(per_step_ms),
+                   "wall_ms_per_step": wall * 1e3 / args.steps},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "kernel": ("fo::copy_kernel" if ckpt else
+                                f"fo::step_kernel<{['adamw', 'sgd', 'lion'].index(kind)}, {'true' if release else 'false'}>"),
+                     "algorithmic_bytes_per_launch": algo_bytes if not release else None,
+                     "bytes_per_param": BYTES_PER_PARAM[kind]},
+    }
+    if not args.no_cpu_baseline and not ckpt:
+        del bufs, tl
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(W, specs, kind, hp, dist, scale, seed, args.cpu_seconds)
+        out["cpu_baseline"]["gpu_over_cpu"] = value / out["cpu_baseline"]["value"]
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

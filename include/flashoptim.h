@@ -28,7 +28,8 @@
  *    validated before anything is enqueued: when an error is returned no buffer has
  *    been modified.  Nothing throws or aborts.
  *  - Inputs are expected to be finite.  NaN/Inf values propagate into the results of
- *    their own element or group but never cause out-of-bounds accesses.
+ *    their own element or group but never cause out-of-bounds accesses.  An infinite
+ *    weight keeps rho = 0; the rho byte stored next to a NaN weight is unspecified.
  *  - Arithmetic: IEEE binary32, round-to-nearest-even, subnormals kept, no fused
  *    multiply-add, in the order the algorithms print it; divisions by a group scale
  *    or by a bias correction 1 - beta^t multiply by the correctly rounded FP32

@@ -347,6 +347,7 @@ int flashoptim_adamw_step(const flashoptim_tensor* tensors, int64_t n_tensors, c
     c.rbc1 = recip_bias_correction(hp->beta1, hp->step);
     c.rbc2 = recip_bias_correction(hp->beta2, hp->step);
     c.eps = hp->eps;
+    c.root_bc2 = (float)std::sqrt(1.0 / (double)c.rbc2);
     return run_step(FLASHOPTIM_ADAMW, tensors, n_tensors, c, stream);
 }
 

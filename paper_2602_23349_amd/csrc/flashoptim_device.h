@@ -35,7 +35,7 @@ struct StepConsts {
     float omb1, omb2;     // 1.0f - beta (FP32 subtraction)
     float rbc1, rbc2;     // 1.0f / (float)(1 - beta^t), AdamW only
     float eps;
-    float pad_;
+    float root_bc2;       // (float)sqrt(1 / (double)rbc2): used only to pre-estimate variance codes
 };
 
 struct StepArgs {

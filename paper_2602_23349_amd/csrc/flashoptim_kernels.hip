@@ -21,7 +21,15 @@
 //     form of Algorithm 1 performs);
 //   * Round(x) to an 8-bit integer is one FP32 addition of 1.5 * 2^23, whose low
 //     mantissa byte is the round-half-even integer in two's complement;
-//   * BF16 rounding uses the hardware v_cvt_pk_bf16_f32 (two elements per issue).
+//   * BF16 rounding uses the hardware v_cvt_pk_bf16_f32 (two elements per issue);
+//   * an 8-bit state code is Round(y) of a value y whose exact evaluation needs an IEEE
+//     division (momentum) or square root (variance).  The kernel first evaluates y with the
+//     1-ulp hardware reciprocal / with the square root it already has from the update; the
+//     result provably differs from the exact y by less than a small delta, so unless it
+//     lands within delta of a rounding tie the code is already decided.  Only when some
+//     lane of the wavefront is that close to a tie (a few percent of the wavefronts) are the
+//     few elements concerned recomputed with the exact sequence.  Codes are bit-identical
+//     to the exact evaluation in every case.
 //
 // Work decomposition.  A lane owns 16 consecutive elements per tile, so every
 // stream moves as 128-bit vectors and a quantisation group (32 elements) is exactly
@@ -69,15 +77,16 @@ __device__ __forceinline__ float reconstruct1(uint32_t b, float base, float q) {
 }
 
 // Second half of C for one element whose BF16 rounding `b` (low 16 bits) is known:
-// rho = Round(Clamp(e * 2^-l, -1, 1) * 127) as a byte (Eq. 1).  Non-finite theta' -> 0.
-__device__ __forceinline__ uint32_t rho_byte(float theta, uint32_t b) {
+// rho = Round(Clamp(e * 2^-l, -1, 1) * 127) (Eq. 1); the result's low byte is the code.
+// For a finite theta' round-to-nearest guarantees |e| <= 2^l, so the clamp is the identity.
+// For theta' = +-inf, e is -+inf or NaN, and the low mantissa byte of (+-inf or NaN) + 1.5*2^23
+// is 0: the correction of a non-finite weight is 0 without a separate test.
+__device__ __forceinline__ uint32_t rho_bits(float theta, uint32_t b) {
     const float base = u2f(b << 16);
     const float e = theta - base;
     const int E = (int)((b >> 7) & 0xffu);
     const float en = ldexpf(e, 135 - (E < 1 ? 1 : E));
-    const float c = __builtin_amdgcn_fmed3f(en, -1.0f, 1.0f);
-    const uint32_t r = round_to_int_bits(c * 127.0f) & 0xffu;
-    return E == 255 ? 0u : r;
+    return round_to_int_bits(en * 127.0f);
 }
 
 // BF16 round-to-nearest-even of two floats: a in the low half, b in the high half.
@@ -98,25 +107,58 @@ __device__ __forceinline__ uint32_t group_scale(float absmax, float* r) {
     return (uint32_t)__builtin_bit_cast(uint16_t, h);
 }
 
-// Q_m code of one element given the reciprocal group scale (Algorithm 2, lines 4-6).
-__device__ __forceinline__ uint32_t m_code(float m, float r) {
+// Exact Q_m code (low byte of the result) of one element given the reciprocal group scale
+// (Algorithm 2, lines 4-6).
+__device__ __forceinline__ uint32_t m_code_exact(float m, float r) {
     const float m1 = m * r;
     const float num = 2.0f * m1;
     const float den = 1.0f + fabsf(m1);
     const float m2 = num / den;
     const float y = __builtin_amdgcn_fmed3f(m2 * 127.0f, -127.0f, 127.0f);
-    return round_to_int_bits(y) & 0xffu;
+    return round_to_int_bits(y);
 }
 
-// Q_v code of one element from sqrt(v) and the reciprocal group scale (Algorithm 3, line 5).
-__device__ __forceinline__ uint32_t v_code(float vroot, float r) {
-    const float y = __builtin_amdgcn_fmed3f((vroot * r) * 255.0f, 0.0f, 255.0f);
-    return round_to_int_bits(y) & 0xffu;
+// Same code through the hardware reciprocal.  m1 and den are formed exactly as above; the
+// quotient uses v_rcp_f32 (1 ulp), so y differs from the exact y by at most
+// (2 + 1 + 1 + 2) * 2^-24 * 128 < 4.6e-5 wherever the clamp is not active.  *resid is the
+// distance of y from the integer it rounds to.
+constexpr float kTieWindowM = 1.0e-4f;
+__device__ __forceinline__ uint32_t m_code_fast(float m, float r, float* resid) {
+    const float m1 = m * r;
+    const float den = 1.0f + fabsf(m1);
+    const float rc = __builtin_amdgcn_rcpf(den);
+    const float y = __builtin_amdgcn_fmed3f((m1 * rc) * 254.0f, -127.0f, 127.0f);
+    const float t = y + 12582912.0f;
+    *resid = fabsf((t - 12582912.0f) - y);
+    return f2u(t);
 }
 
-__device__ __forceinline__ uint32_t pack4(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
-    return c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+// Exact Q_v code of one element from v and the reciprocal group scale (Algorithm 3, lines 2, 5).
+__device__ __forceinline__ uint32_t v_code_exact(float v, float r) {
+    const float y = __builtin_amdgcn_fmed3f((sqrtf(v) * r) * 255.0f, 0.0f, 255.0f);
+    return round_to_int_bits(y);
 }
+
+// Same code from root_hat = sqrt(v * rbc2) (exactly rounded, already computed for the update)
+// and kr255 = ((sqrt(1/rbc2) rounded) * r) * 255.  Relative errors: v*rbc2 (1), its root
+// (0.5 + 1), the three roundings inside kr255 (3), this product (1), against the three
+// roundings of the exact chain (3): below 9.5 * 2^-24 * 255 < 1.45e-4 in y.
+constexpr float kTieWindowV = 2.5e-4f;
+__device__ __forceinline__ uint32_t v_code_fast(float root_hat, float kr255, float* resid) {
+    const float y = __builtin_amdgcn_fmed3f(root_hat * kr255, 0.0f, 255.0f);
+    const float t = y + 12582912.0f;
+    *resid = fabsf((t - 12582912.0f) - y);
+    return f2u(t);
+}
+
+// Low bytes of four words -> one word (c0 in byte 0).
+__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
+    const uint32_t t01 = __builtin_amdgcn_perm(c1, c0, 0x0c0c0400u);
+    const uint32_t t23 = __builtin_amdgcn_perm(c3, c2, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(t23, t01, 0x05040100u);
+}
+
+__device__ __forceinline__ bool any_lane(bool p) { return __builtin_amdgcn_ballot_w64(p) != 0; }
 
 // ------------------------------------------------------------- decode tables --
 
@@ -251,7 +293,8 @@ __device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const De
     const float s_v = HAS_V ? (float)__builtin_bit_cast(_Float16, (uint16_t)x.vs) : 0.0f;
 
     float mt[16];     // new momentum
-    float vr[16];     // sqrt of the new variance (AdamW)
+    float vt[16];     // new variance (AdamW)
+    float rh[16];     // sqrt of the bias-corrected new variance (AdamW)
     float tht[16];    // new master weight
     float amax_m = 0.0f, amax_v = 0.0f;
 
@@ -276,12 +319,13 @@ __device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const De
             const float v_new = (c.beta2 * v) + (c.omb2 * gg);
             const float mhat = m_new * c.rbc1;
             const float vhat = v_new * c.rbc2;
-            const float den = sqrtf(vhat) + c.eps;
+            const float root_hat = sqrtf(vhat);
+            const float den = root_hat + c.eps;
             const float upd = (mhat / den) + (wd * th);
             th_new = th - (lr * upd);
-            const float root = sqrtf(v_new);                     // v' of Algorithm 3
-            vr[i] = root;
-            amax_v = fmaxf(amax_v, root);
+            vt[i] = v_new;
+            rh[i] = root_hat;
+            amax_v = fmaxf(amax_v, v_new);
         } else if (KIND == 1) {
             m_new = (c.beta1 * m) + g;                           // beta1 carries the momentum mu
             th_new = th - (lr * (m_new + (wd * th)));
@@ -296,22 +340,48 @@ __device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const De
         amax_m = fmaxf(amax_m, fabsf(m_new));
     }
 
-    // epilogue: group scales (one DPP swap joins the two lanes of a group)
+    // epilogue: group scales (one DPP swap joins the two lanes of a group).  The square root
+    // is monotone, so the group maximum of sqrt(v) is the square root of the maximum of v.
     amax_m = fmaxf(amax_m, swap_pair(amax_m));
-    float r_m, r_v = 0.0f;
+    float r_m, r_v = 0.0f, kr255 = 0.0f;
     y.ms = group_scale(amax_m, &r_m);
     if (HAS_V) {
         amax_v = fmaxf(amax_v, swap_pair(amax_v));
-        y.vs = group_scale(amax_v, &r_v);
+        y.vs = group_scale(sqrtf(amax_v), &r_v);
+        kr255 = (c.root_bc2 * r_v) * 255.0f;
     }
 
+    // epilogue: state codes, four at a time; exact recomputation only near rounding ties
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        y.mq[j] = pack4(m_code(mt[4 * j], r_m), m_code(mt[4 * j + 1], r_m),
-                        m_code(mt[4 * j + 2], r_m), m_code(mt[4 * j + 3], r_m));
-        if (HAS_V)
-            y.vq[j] = pack4(v_code(vr[4 * j], r_v), v_code(vr[4 * j + 1], r_v),
-                            v_code(vr[4 * j + 2], r_v), v_code(vr[4 * j + 3], r_v));
+        uint32_t cm[4];
+        float dm = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float d;
+            cm[k] = m_code_fast(mt[4 * j + k], r_m, &d);
+            dm = fmaxf(dm, d);
+        }
+        if (any_lane(dm > 0.5f - kTieWindowM)) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) cm[k] = m_code_exact(mt[4 * j + k], r_m);
+        }
+        y.mq[j] = pack_low_bytes(cm[0], cm[1], cm[2], cm[3]);
+        if (HAS_V) {
+            uint32_t cv[4];
+            float dv = 0.0f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float d;
+                cv[k] = v_code_fast(rh[4 * j + k], kr255, &d);
+                dv = fmaxf(dv, d);
+            }
+            if (any_lane(dv > 0.5f - kTieWindowV)) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) cv[k] = v_code_exact(vt[4 * j + k], r_v);
+            }
+            y.vq[j] = pack_low_bytes(cv[0], cv[1], cv[2], cv[3]);
+        }
     }
     // epilogue: split the new master weight
 #pragma unroll
@@ -319,8 +389,8 @@ __device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const De
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t w0 = y.p[2 * j], w1 = y.p[2 * j + 1];
-        y.r[j] = pack4(rho_byte(tht[4 * j], w0 & 0xffffu), rho_byte(tht[4 * j + 1], w0 >> 16),
-                       rho_byte(tht[4 * j + 2], w1 & 0xffffu), rho_byte(tht[4 * j + 3], w1 >> 16));
+        y.r[j] = pack_low_bytes(rho_bits(tht[4 * j], w0 & 0xffffu), rho_bits(tht[4 * j + 1], w0 >> 16),
+                                rho_bits(tht[4 * j + 2], w1 & 0xffffu), rho_bits(tht[4 * j + 3], w1 >> 16));
     }
 }
 
@@ -394,7 +464,7 @@ __global__ __launch_bounds__(kThreads) void split_kernel(const float* theta, uin
     const float t = theta[i];
     const uint32_t b = bf16_pack(t, 0.0f) & 0xffffu;
     param[i] = (uint16_t)b;
-    rho[i] = (int8_t)rho_byte(t, b);
+    rho[i] = (int8_t)(rho_bits(t, b) & 0xffu);
 }
 
 __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const uint16_t* param, const int8_t* rho,
@@ -422,7 +492,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float* x, uint
     float r;
     scale[grp] = (uint16_t)group_scale(a, &r);
     for (int i = 0; i < cnt; ++i)
-        q[o + i] = (uint8_t)(VARIANCE ? v_code(sqrtf(x[o + i]), r) : m_code(x[o + i], r));
+        q[o + i] = (uint8_t)((VARIANCE ? v_code_exact(x[o + i], r) : m_code_exact(x[o + i], r)) & 0xffu);
 }
 
 template <bool VARIANCE>

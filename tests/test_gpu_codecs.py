@@ -48,7 +48,9 @@ def test_split_matches_oracle():
     gp, gr = bits16(p), r.cpu().numpy()
     ok = ~np.isnan(x)
     assert np.array_equal(gp[ok], thp[ok])
-    assert np.array_equal(gr, rho)
+    assert np.array_equal(gr[ok], rho[ok])      # incl. +-inf and values that round to +-inf: rho = 0
+    assert np.all(rho[np.isinf(oracle.bf16_to_f32(thp))] == 0)
+    # NaN weights: theta' is a NaN; the correction byte of a NaN is unspecified
     nan_p = gp[~ok]
     assert np.all((nan_p & 0x7F80) == 0x7F80) and np.all((nan_p & 0x7F) != 0)
 
