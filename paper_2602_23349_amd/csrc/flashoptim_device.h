@@ -12,8 +12,7 @@ constexpr int kGroup = 32;                         // quantisation group (Algori
 constexpr int kThreads = 256;                      // lanes per workgroup
 constexpr int kVec = 16;                           // consecutive elements per lane per tile
 constexpr int kTileElems = kThreads * kVec;        // 4096 elements per workgroup pass
-constexpr int kTilesPerChunk = 2;
-constexpr int kChunkElems = kTileElems * kTilesPerChunk;   // elements per workgroup
+constexpr int kChunkElems = kTileElems;             // one tile per workgroup
 constexpr int kCopyChunkBytes = 64 * 1024;         // checkpoint copy: bytes per workgroup
 
 // One tensor as the kernels see it (device pointers), 72 bytes.

@@ -50,6 +50,33 @@ typedef float floatx2_t __attribute__((ext_vector_type(2)));
 
 // ------------------------------------------------------------------ helpers --
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+#ifndef FO_NT_LOAD
+#define FO_NT_LOAD 1
+#endif
+#ifndef FO_NT_STORE
+#define FO_NT_STORE 1
+#endif
+
+// 128-bit global accesses of the streaming data (each byte is touched once per step).
+__device__ __forceinline__ uint4 ld128(const void* p) {
+#if FO_NT_LOAD
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+#else
+    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(p);
+#endif
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st128(void* p, uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    const u32x4_t v = {a, b, c, d};
+#if FO_NT_STORE
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(p));
+#else
+    *reinterpret_cast<u32x4_t*>(p) = v;
+#endif
+}
+
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 
@@ -105,6 +132,21 @@ __device__ __forceinline__ uint32_t group_scale(float absmax, float* r) {
     const float s = (float)h;
     *r = (s == 0.0f) ? 0.0f : 1.0f / s;
     return (uint32_t)__builtin_bit_cast(uint16_t, h);
+}
+
+// Correctly rounded square root for x = 0, x >= 2^-96, inf (negative / NaN give NaN): the
+// hardware root is within 1 ulp, and the signs of the two residuals x - s*(s -+ ulp), each one
+// fused multiply-add, pick the neighbour when it is the nearer one.  Below 2^-96 the residuals
+// would leave the normal range; callers check the range and use sqrtf() otherwise.
+constexpr uint32_t kSqrtFastMinBits = 0x0f800000u;   // 2^-96
+__device__ __forceinline__ float sqrt_rn_midrange(float x) {
+    float s = __builtin_amdgcn_sqrtf(x);
+    const float s_dn = u2f(f2u(s) - 1u), s_up = u2f(f2u(s) + 1u);
+    const float r_dn = fmaf(-s_dn, s, x);
+    const float r_up = fmaf(-s_up, s, x);
+    s = (r_dn <= 0.0f) ? s_dn : s;
+    s = (r_up > 0.0f) ? s_up : s;
+    return s;
 }
 
 // Exact Q_m code (low byte of the result) of one element given the reciprocal group scale
@@ -168,13 +210,29 @@ struct DecodeTables {
     float v[256];     // (float)i / 255
 };
 
+// The three tables as compile-time constants.  The compiler evaluates constant expressions in
+// IEEE binary32 with round-to-nearest-even, so every entry is the result of the same single
+// divisions the definitions prescribe (Algorithm 1 line 11; Algorithm 2 lines 10-11;
+// Algorithm 3 line 10).
+constexpr DecodeTables make_decode_tables() {
+    DecodeTables t{};
+    for (int i = 0; i < 256; ++i) {
+        const int sb = i < 128 ? i : i - 256;
+        const float z = (float)sb / 127.0f;
+        const float az = z < 0.0f ? -z : z;
+        t.rho[i] = z;
+        t.m[i] = z / (2.0f - az);
+        t.v[i] = (float)i / 255.0f;
+    }
+    return t;
+}
+__device__ const DecodeTables g_decode_tables = make_decode_tables();
+
+// Each workgroup stages the tables in LDS (one entry of each per lane; blockDim.x == 256).
 __device__ __forceinline__ void fill_tables(DecodeTables& t, int tid) {
-    // one entry per lane; blockDim.x == 256
-    const float sb = (float)(int)(int8_t)tid;
-    const float z = sb / 127.0f;
-    t.rho[tid] = z;
-    t.m[tid] = z / (2.0f - fabsf(z));
-    t.v[tid] = (float)tid / 255.0f;
+    t.rho[tid] = g_decode_tables.rho[tid];
+    t.m[tid] = g_decode_tables.m[tid];
+    t.v[tid] = g_decode_tables.v[tid];
 }
 
 // -------------------------------------------------------------- lane vectors --
@@ -190,19 +248,19 @@ struct LaneIO {
 
 template <bool HAS_V>
 __device__ __forceinline__ void load_full(LaneIO& x, const TensorDev& T, int64_t off) {
-    const uint4* p = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(T.param) + off);
-    const uint4* g = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(T.grad) + off);
-    uint4 a = p[0], b = p[1];
+    const uint16_t* p = reinterpret_cast<const uint16_t*>(T.param) + off;
+    const uint16_t* g = reinterpret_cast<const uint16_t*>(T.grad) + off;
+    uint4 a = ld128(p), b = ld128(p + 8);
     x.p[0] = a.x; x.p[1] = a.y; x.p[2] = a.z; x.p[3] = a.w; x.p[4] = b.x; x.p[5] = b.y; x.p[6] = b.z; x.p[7] = b.w;
-    a = g[0]; b = g[1];
+    a = ld128(g); b = ld128(g + 8);
     x.g[0] = a.x; x.g[1] = a.y; x.g[2] = a.z; x.g[3] = a.w; x.g[4] = b.x; x.g[5] = b.y; x.g[6] = b.z; x.g[7] = b.w;
-    a = *reinterpret_cast<const uint4*>(T.rho + off);
+    a = ld128(T.rho + off);
     x.r[0] = a.x; x.r[1] = a.y; x.r[2] = a.z; x.r[3] = a.w;
-    a = *reinterpret_cast<const uint4*>(T.m_q + off);
+    a = ld128(T.m_q + off);
     x.mq[0] = a.x; x.mq[1] = a.y; x.mq[2] = a.z; x.mq[3] = a.w;
     x.ms = T.m_scale[off >> 5];
     if (HAS_V) {
-        a = *reinterpret_cast<const uint4*>(T.v_q + off);
+        a = ld128(T.v_q + off);
         x.vq[0] = a.x; x.vq[1] = a.y; x.vq[2] = a.z; x.vq[3] = a.w;
         x.vs = T.v_scale[off >> 5];
     }
@@ -246,12 +304,12 @@ __device__ __forceinline__ void load_tail(LaneIO& x, const TensorDev& T, int64_t
 
 template <bool HAS_V>
 __device__ __forceinline__ void store_full(const LaneIO& y, const TensorDev& T, int64_t off, bool group_leader) {
-    uint4* p = reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(T.param) + off);
-    p[0] = make_uint4(y.p[0], y.p[1], y.p[2], y.p[3]);
-    p[1] = make_uint4(y.p[4], y.p[5], y.p[6], y.p[7]);
-    *reinterpret_cast<uint4*>(T.rho + off) = make_uint4(y.r[0], y.r[1], y.r[2], y.r[3]);
-    *reinterpret_cast<uint4*>(T.m_q + off) = make_uint4(y.mq[0], y.mq[1], y.mq[2], y.mq[3]);
-    if (HAS_V) *reinterpret_cast<uint4*>(T.v_q + off) = make_uint4(y.vq[0], y.vq[1], y.vq[2], y.vq[3]);
+    uint16_t* p = reinterpret_cast<uint16_t*>(T.param) + off;
+    st128(p, y.p[0], y.p[1], y.p[2], y.p[3]);
+    st128(p + 8, y.p[4], y.p[5], y.p[6], y.p[7]);
+    st128(T.rho + off, y.r[0], y.r[1], y.r[2], y.r[3]);
+    st128(T.m_q + off, y.mq[0], y.mq[1], y.mq[2], y.mq[3]);
+    if (HAS_V) st128(T.v_q + off, y.vq[0], y.vq[1], y.vq[2], y.vq[3]);
     if (group_leader) {
         T.m_scale[off >> 5] = (uint16_t)y.ms;
         if (HAS_V) T.v_scale[off >> 5] = (uint16_t)y.vs;
@@ -295,52 +353,78 @@ __device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const De
     float mt[16];     // new momentum
     float vt[16];     // new variance (AdamW)
     float rh[16];     // sqrt of the bias-corrected new variance (AdamW)
-    float tht[16];    // new master weight
     float amax_m = 0.0f, amax_v = 0.0f;
 
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const uint32_t pw = x.p[i >> 1], gw = x.g[i >> 1];
-        const uint32_t pb = (i & 1) ? (pw >> 16) : (pw & 0xffffu);
-        const float base = (i & 1) ? u2f(pw & 0xffff0000u) : u2f(pw << 16);
-        const float g = (i & 1) ? u2f(gw & 0xffff0000u) : u2f(gw << 16);
-        const uint32_t rb = (x.r[i >> 2] >> (8 * (i & 3))) & 0xffu;
-        const uint32_t mb = (x.mq[i >> 2] >> (8 * (i & 3))) & 0xffu;
-        // prologue: reconstruct optimizer state and master weight
-        const float m = tab.m[mb] * s_m;                         // Q_m^-1
-        const float th = reconstruct1(pb, base, tab.rho[rb]);    // C^-1
-        float m_new, th_new;
-        if (KIND == 0) {
-            const uint32_t vb = (x.vq[i >> 2] >> (8 * (i & 3))) & 0xffu;
-            const float v1 = tab.v[vb] * s_v;                    // Q_v^-1
-            const float v = v1 * v1;
-            m_new = (c.beta1 * m) + (c.omb1 * g);
-            const float gg = g * g;
-            const float v_new = (c.beta2 * v) + (c.omb2 * gg);
-            const float mhat = m_new * c.rbc1;
-            const float vhat = v_new * c.rbc2;
-            const float root_hat = sqrtf(vhat);
-            const float den = root_hat + c.eps;
-            const float upd = (mhat / den) + (wd * th);
-            th_new = th - (lr * upd);
-            vt[i] = v_new;
-            rh[i] = root_hat;
-            amax_v = fmaxf(amax_v, v_new);
-        } else if (KIND == 1) {
-            m_new = (c.beta1 * m) + g;                           // beta1 carries the momentum mu
-            th_new = th - (lr * (m_new + (wd * th)));
-        } else {
-            const float cc = (c.beta1 * m) + (c.omb1 * g);
-            const float u = (cc > 0.0f) ? 1.0f : ((cc < 0.0f) ? -1.0f : 0.0f);
-            m_new = (c.beta2 * m) + (c.omb2 * g);
-            th_new = th - (lr * (u + (wd * th)));
+    for (int j = 0; j < 4; ++j) {
+        // four elements at a time (one word of each byte stream)
+        float th4[4], mh4[4], vh4[4];
+        float tht[4];     // new master weights of this block
+        uint32_t vmin = 0xffffffffu;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int i = 4 * j + k;
+            const uint32_t pw = x.p[i >> 1], gw = x.g[i >> 1];
+            const uint32_t pb = (i & 1) ? (pw >> 16) : (pw & 0xffffu);
+            const float base = (i & 1) ? u2f(pw & 0xffff0000u) : u2f(pw << 16);
+            const float g = (i & 1) ? u2f(gw & 0xffff0000u) : u2f(gw << 16);
+            const uint32_t rb = (x.r[j] >> (8 * k)) & 0xffu;
+            const uint32_t mb = (x.mq[j] >> (8 * k)) & 0xffu;
+            // prologue: reconstruct optimizer state and master weight
+            const float m = tab.m[mb] * s_m;                         // Q_m^-1
+            const float th = reconstruct1(pb, base, tab.rho[rb]);    // C^-1
+            float m_new;
+            if (KIND == 0) {
+                const uint32_t vb = (x.vq[j] >> (8 * k)) & 0xffu;
+                const float v1 = tab.v[vb] * s_v;                    // Q_v^-1
+                const float v = v1 * v1;
+                m_new = (c.beta1 * m) + (c.omb1 * g);
+                const float gg = g * g;
+                const float v_new = (c.beta2 * v) + (c.omb2 * gg);
+                mh4[k] = m_new * c.rbc1;
+                const float vhat = v_new * c.rbc2;
+                vh4[k] = vhat;
+                th4[k] = th;
+                vt[i] = v_new;
+                amax_v = fmaxf(amax_v, v_new);
+                vmin = min(vmin, f2u(vhat) - 1u);    // 0 -> 0xffffffff: zero is fine for the fast root
+            } else if (KIND == 1) {
+                m_new = (c.beta1 * m) + g;                           // beta1 carries the momentum mu
+                tht[k] = th - (lr * (m_new + (wd * th)));
+            } else {
+                const float cc = (c.beta1 * m) + (c.omb1 * g);
+                const float u = (cc > 0.0f) ? 1.0f : ((cc < 0.0f) ? -1.0f : 0.0f);
+                m_new = (c.beta2 * m) + (c.omb2 * g);
+                tht[k] = th - (lr * (u + (wd * th)));
+            }
+            mt[i] = m_new;
+            amax_m = fmaxf(amax_m, fabsf(m_new));
         }
-        mt[i] = m_new;
-        tht[i] = th_new;
-        amax_m = fmaxf(amax_m, fabsf(m_new));
+        if (KIND == 0) {
+            // sqrt(v_hat): the short sequence unless some lane holds a value below 2^-96
+            if (any_lane(vmin < kSqrtFastMinBits - 1u)) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrtf(vh4[k]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrt_rn_midrange(vh4[k]);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float den = rh[4 * j + k] + c.eps;
+                const float upd = (mh4[k] / den) + (wd * th4[k]);
+                tht[k] = th4[k] - (lr * upd);
+            }
+        }
+        // epilogue, part 1: split the new master weights of this block
+        const uint32_t w0 = bf16_pack(tht[0], tht[1]), w1 = bf16_pack(tht[2], tht[3]);
+        y.p[2 * j] = w0;
+        y.p[2 * j + 1] = w1;
+        y.r[j] = pack_low_bytes(rho_bits(tht[0], w0 & 0xffffu), rho_bits(tht[1], w0 >> 16),
+                                rho_bits(tht[2], w1 & 0xffffu), rho_bits(tht[3], w1 >> 16));
     }
 
-    // epilogue: group scales (one DPP swap joins the two lanes of a group).  The square root
+    // epilogue, part 2: group scales (one DPP swap joins the two lanes of a group).  The square root
     // is monotone, so the group maximum of sqrt(v) is the square root of the maximum of v.
     amax_m = fmaxf(amax_m, swap_pair(amax_m));
     float r_m, r_v = 0.0f, kr255 = 0.0f;
@@ -383,15 +467,6 @@ __device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const De
             y.vq[j] = pack_low_bytes(cv[0], cv[1], cv[2], cv[3]);
         }
     }
-    // epilogue: split the new master weight
-#pragma unroll
-    for (int j = 0; j < 8; ++j) y.p[j] = bf16_pack(tht[2 * j], tht[2 * j + 1]);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t w0 = y.p[2 * j], w1 = y.p[2 * j + 1];
-        y.r[j] = pack_low_bytes(rho_bits(tht[4 * j], w0 & 0xffffu), rho_bits(tht[4 * j + 1], w0 >> 16),
-                                rho_bits(tht[4 * j + 2], w1 & 0xffffu), rho_bits(tht[4 * j + 3], w1 >> 16));
-    }
 }
 
 // ------------------------------------------------------------ step kernels --
@@ -401,7 +476,6 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     constexpr bool HAS_V = (KIND == 0);
     __shared__ DecodeTables tab;
     const int tid = (int)threadIdx.x;
-    fill_tables(tab, tid);
 
     TensorDev T;
     int64_t chunk;
@@ -413,22 +487,23 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         T = a.tensors[ck.x];
         chunk = (int64_t)ck.y;
     }
+    // one tile per workgroup: its streaming loads go out first, the decode tables are staged
+    // into LDS while they are in flight
+    static_assert(kChunkElems == kTileElems, "one tile per workgroup");
+    const int64_t off = chunk * kChunkElems + (int64_t)tid * kVec;
+    const int64_t left = T.numel - off;
+    const int cnt = left >= kVec ? kVec : (left > 0 ? (int)left : 0);
+    LaneIO x, y;
+    if (cnt == kVec) load_full<HAS_V>(x, T, off);
+    else load_tail<HAS_V>(x, T, off, cnt);
+    fill_tables(tab, tid);
     __syncthreads();
-
-    const int64_t begin = chunk * kChunkElems;
-    const int64_t end = (T.numel - begin < kChunkElems) ? T.numel : begin + kChunkElems;
+    // Both lanes of a group run the update together (the partner of a lane with cnt == 0 may
+    // hold elements); lanes past the end compute on zeros and store nothing.
+    update_lane<KIND>(x, y, tab, a.c, T.lr, T.wd);
     const bool leader = (tid & 1) == 0;
-
-    for (int64_t off = begin + (int64_t)tid * kVec; (off & ~(int64_t)31) < end; off += kTileElems) {
-        const int64_t left = end - off;
-        const int cnt = left >= kVec ? kVec : (left > 0 ? (int)left : 0);
-        LaneIO x, y;
-        if (cnt == kVec) load_full<HAS_V>(x, T, off);
-        else load_tail<HAS_V>(x, T, off, cnt);
-        update_lane<KIND>(x, y, tab, a.c, T.lr, T.wd);
-        if (cnt == kVec) store_full<HAS_V>(y, T, off, leader);
-        else store_tail<HAS_V>(y, T, off, cnt, leader);
-    }
+    if (cnt == kVec) store_full<HAS_V>(y, T, off, leader);
+    else store_tail<HAS_V>(y, T, off, cnt, leader);
 }
 
 template __global__ void step_kernel<0, false>(StepArgs);
