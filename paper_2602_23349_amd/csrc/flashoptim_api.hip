@@ -197,9 +197,9 @@ int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, cons
     if (live.size() == 1) {
         // gradient-release call: no table, no allocation, no lock
         a.single = live[0];
-        const int64_t blocks = (live[0].numel + fo::kChunkElems - 1) / fo::kChunkElems;
-        fo::launch_step(kind, true, a, blocks, stream);
-        FO_HIP(hipGetLastError());
+        const int64_t ce = fo::chunk_elems(kind);
+        const int64_t blocks = (live[0].numel + ce - 1) / ce;
+        FO_HIP(fo::launch_step(kind, true, a, blocks, stream));
         return FLASHOPTIM_OK;
     }
 
@@ -220,7 +220,8 @@ int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, cons
     std::vector<uint2> chunks;
     if (g_index.find(key) == g_index.end()) {
         for (size_t ti = 0; ti < live.size(); ++ti) {
-            const int64_t nc = (live[ti].numel + fo::kChunkElems - 1) / fo::kChunkElems;
+            const int64_t ce = fo::chunk_elems(kind);
+            const int64_t nc = (live[ti].numel + ce - 1) / ce;
             for (int64_t ci = 0; ci < nc; ++ci) chunks.push_back(make_uint2((unsigned)ti, (unsigned)ci));
         }
     }
@@ -234,8 +235,7 @@ int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, cons
     }
     a.tensors = static_cast<const TensorDev*>(plan->d_table);
     a.chunks = plan->d_chunks;
-    fo::launch_step(kind, false, a, plan->n_chunks, stream);
-    FO_HIP(hipGetLastError());
+    FO_HIP(fo::launch_step(kind, false, a, plan->n_chunks, stream));
     return FLASHOPTIM_OK;
 }
 

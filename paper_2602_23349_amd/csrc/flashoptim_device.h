@@ -10,9 +10,16 @@ namespace fo {
 
 constexpr int kGroup = 32;                         // quantisation group (Algorithms 2, 3)
 constexpr int kThreads = 256;                      // lanes per workgroup
-constexpr int kVec = 16;                           // consecutive elements per lane per tile
-constexpr int kTileElems = kThreads * kVec;        // 4096 elements per workgroup pass
-constexpr int kChunkElems = kTileElems;             // one tile per workgroup
+#ifndef FO_VEC_ADAMW
+#define FO_VEC_ADAMW 8
+#endif
+#ifndef FO_VEC_SGD_LION
+#define FO_VEC_SGD_LION 8
+#endif
+constexpr int kVecAdamW = FO_VEC_ADAMW;            // consecutive elements per lane, AdamW kernel
+constexpr int kVecSgdLion = FO_VEC_SGD_LION;       // consecutive elements per lane, SGD / Lion kernels
+// elements per workgroup (= per chunk-table entry) for an optimizer kind
+constexpr int chunk_elems(int kind) { return kThreads * (kind == 0 ? kVecAdamW : kVecSgdLion); }
 constexpr int kCopyChunkBytes = 64 * 1024;         // checkpoint copy: bytes per workgroup
 
 // One tensor as the kernels see it (device pointers), 72 bytes.
@@ -51,7 +58,7 @@ struct CopySegment {
     int64_t pad_bytes;   // >= bytes; [bytes, pad_bytes) of dst is zero-filled
 };
 
-void launch_step(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s);
+hipError_t launch_step(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s);
 void launch_split(const float* theta, void* param, int8_t* rho, int64_t n, hipStream_t s);
 void launch_reconstruct(const void* param, const int8_t* rho, float* theta, int64_t n, hipStream_t s);
 void launch_quantize(bool variance, const float* x, void* q, uint16_t* scale, int64_t n, hipStream_t s);

@@ -51,6 +51,7 @@ typedef float floatx2_t __attribute__((ext_vector_type(2)));
 // ------------------------------------------------------------------ helpers --
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 #ifndef FO_NT_LOAD
 #define FO_NT_LOAD 1
@@ -80,10 +81,16 @@ __device__ __forceinline__ void st128(void* p, uint32_t a, uint32_t b, uint32_t 
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 
-// Value held by the lane's partner in its quad pair (lane ^ 1).
-__device__ __forceinline__ float swap_pair(float x) {
-    return u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), 0xB1 /* quad_perm [1,0,3,2] */,
-                                                     0xf, 0xf, false));
+// Maximum over the lanes that share a 32-element group: a lane pair (16 elements per lane)
+// or a lane quad (8 per lane), by DPP quad permutes.  Inputs are non-negative.
+template <int VEC>
+__device__ __forceinline__ float group_max(float x) {
+    x = fmaxf(x, u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), 0xB1 /* quad_perm [1,0,3,2] */,
+                                                           0xf, 0xf, false)));
+    if (VEC == 8)
+        x = fmaxf(x, u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), 0x4E /* quad_perm [2,3,0,1] */,
+                                                               0xf, 0xf, false)));
+    return x;
 }
 
 // Round-half-even of y (|y| <= 2^21) to an integer, returned in two's complement in the
@@ -124,8 +131,8 @@ __device__ __forceinline__ uint32_t bf16_pack(float a, float b) {
 }
 
 // FP16 scale of a group from its FP32 absmax: saturate at 65504, round to nearest even.
-// Returns the FP16 bits; *s is the scale as the decoder will read it, *r its reciprocal
-// (0 when the scale is 0, so that every code of the group becomes 0).
+// Returns the FP16 bits; *r is the correctly rounded reciprocal of the scale as the decoder
+// will read it (0 when the scale is 0, so that every code of the group becomes 0).
 __device__ __forceinline__ uint32_t group_scale(float absmax, float* r) {
     const float a = fminf(absmax, 65504.0f);
     const _Float16 h = (_Float16)a;
@@ -134,11 +141,27 @@ __device__ __forceinline__ uint32_t group_scale(float absmax, float* r) {
     return (uint32_t)__builtin_bit_cast(uint16_t, h);
 }
 
+// Same, with the reciprocal formed as hardware estimate + one Newton step.  The argument takes
+// only the 31,743 positive finite FP16 values; for every one of them this sequence returns the
+// correctly rounded 1/s (checked exhaustively on the device by flashoptim_selftest).
+__device__ __forceinline__ float recip_of_fp16(float s) {
+    const float r0 = __builtin_amdgcn_rcpf(s);
+    const float e = fmaf(-s, r0, 1.0f);
+    return fmaf(e, r0, r0);
+}
+__device__ __forceinline__ uint32_t group_scale_fast(float absmax, float* r) {
+    const float a = fminf(absmax, 65504.0f);
+    const _Float16 h = (_Float16)a;
+    const float s = (float)h;
+    *r = (s == 0.0f) ? 0.0f : recip_of_fp16(s);
+    return (uint32_t)__builtin_bit_cast(uint16_t, h);
+}
+
 // Correctly rounded square root for x = 0, x >= 2^-96, inf (negative / NaN give NaN): the
 // hardware root is within 1 ulp, and the signs of the two residuals x - s*(s -+ ulp), each one
 // fused multiply-add, pick the neighbour when it is the nearer one.  Below 2^-96 the residuals
 // would leave the normal range; callers check the range and use sqrtf() otherwise.
-constexpr uint32_t kSqrtFastMinBits = 0x0f800000u;   // 2^-96
+constexpr float kSqrtFastMin = 1.2621774483536189e-29f;   // 2^-96
 __device__ __forceinline__ float sqrt_rn_midrange(float x) {
     float s = __builtin_amdgcn_sqrtf(x);
     const float s_dn = u2f(f2u(s) - 1u), s_up = u2f(f2u(s) + 1u);
@@ -205,15 +228,24 @@ __device__ __forceinline__ bool any_lane(bool p) { return __builtin_amdgcn_ballo
 // ------------------------------------------------------------- decode tables --
 
 struct DecodeTables {
-    float rho[256];   // (float)(int8)i / 127
-    float m[256];     // phi_m^-1((float)(int8)i / 127)
-    float v[256];     // (float)i / 255
+    float rho[256];    // (float)(int8)i / 127
+    float m[256];      // phi_m^-1((float)(int8)i / 127)
+    float v[256];      // (float)i / 255
+    float half_ulp[256];   // 2^l, l = max(E,1) - 135: half the BF16 ULP of a value with exponent field E
+    float2 split[256];     // {2^h, 127 * 2^(-l-h)}, h = floor(-l/2): the two scalings of Algorithm 1, line 5
 };
 
-// The three tables as compile-time constants.  The compiler evaluates constant expressions in
+constexpr float pow2_const(int k) {     // 2^k, exact for -149 <= k <= 127
+    float x = 1.0f;
+    for (int i = 0; i < k; ++i) x *= 2.0f;
+    for (int i = 0; i > k; --i) x *= 0.5f;
+    return x;
+}
+
+// All tables are compile-time constants.  The compiler evaluates constant expressions in
 // IEEE binary32 with round-to-nearest-even, so every entry is the result of the same single
 // divisions the definitions prescribe (Algorithm 1 line 11; Algorithm 2 lines 10-11;
-// Algorithm 3 line 10).
+// Algorithm 3 line 10); the powers of two are exact.
 constexpr DecodeTables make_decode_tables() {
     DecodeTables t{};
     for (int i = 0; i < 256; ++i) {
@@ -223,6 +255,11 @@ constexpr DecodeTables make_decode_tables() {
         t.rho[i] = z;
         t.m[i] = z / (2.0f - az);
         t.v[i] = (float)i / 255.0f;
+        const int l = (i < 1 ? 1 : i) - 135;
+        const int h = (-l >= 0) ? (-l) / 2 : -((l + 1) / 2);    // floor(-l / 2)
+        t.half_ulp[i] = pow2_const(l);
+        t.split[i].x = pow2_const(h);
+        t.split[i].y = 127.0f * pow2_const(-l - h);
     }
     return t;
 }
@@ -233,57 +270,112 @@ __device__ __forceinline__ void fill_tables(DecodeTables& t, int tid) {
     t.rho[tid] = g_decode_tables.rho[tid];
     t.m[tid] = g_decode_tables.m[tid];
     t.v[tid] = g_decode_tables.v[tid];
+    t.half_ulp[tid] = g_decode_tables.half_ulp[tid];
+    t.split[tid] = g_decode_tables.split[tid];
+}
+
+// In-kernel forms of C^-1 and of the rho half of C through the LDS tables.  E is the exponent
+// field of theta' (bits 7..14 of its BF16 pattern).
+//   C^-1: theta_hat = theta' + q * 2^l.  The product is exact, or rounds once when it is
+//         subnormal - exactly what the two-factor form of Algorithm 1 (line 11) does.
+//   C:    rho = Round(((e * 2^h) * (127 * 2^(-l-h)))): both products are exact (e has at most
+//         16 significant bits below theta'), so this is Round(e_norm * 127).  For a finite
+//         theta' the clamp of Algorithm 1 is the identity (|e| <= 2^l under round-to-nearest);
+//         for theta' = +-inf the products are +-inf or NaN and the low mantissa byte of
+//         (+-inf or NaN) + 1.5 * 2^23 is 0.
+__device__ __forceinline__ float reconstruct_lds(const DecodeTables& t, uint32_t E, float base, float q) {
+    return base + (q * t.half_ulp[E]);
+}
+__device__ __forceinline__ uint32_t rho_bits_lds(const DecodeTables& t, float theta, uint32_t b16, uint32_t E) {
+    const float e = theta - u2f(b16 << 16);
+    const float2 sc = t.split[E];
+    return round_to_int_bits((e * sc.x) * sc.y);
 }
 
 // -------------------------------------------------------------- lane vectors --
+//
+// VEC consecutive elements per lane (8 or 16).  With 16, every stream moves as 128-bit
+// accesses and a group of 32 is a lane pair; with 8, the byte streams move as 64-bit
+// accesses and a group is a lane quad, but the kernel needs half the registers and more
+// wavefronts fit on a SIMD.
 
+template <int VEC>
 struct LaneIO {
-    uint32_t p[8];    // 16 BF16 theta'
-    uint32_t g[8];    // 16 BF16 gradients
-    uint32_t r[4];    // 16 INT8 rho
-    uint32_t mq[4];   // 16 INT8 momentum codes
-    uint32_t vq[4];   // 16 UINT8 variance codes
-    uint32_t ms, vs;  // FP16 scale bits of the lane's group
+    uint32_t p[VEC / 2];    // VEC BF16 theta'
+    uint32_t g[VEC / 2];    // VEC BF16 gradients
+    uint32_t r[VEC / 4];    // VEC INT8 rho
+    uint32_t mq[VEC / 4];   // VEC INT8 momentum codes
+    uint32_t vq[VEC / 4];   // VEC UINT8 variance codes
+    uint32_t ms, vs;        // FP16 scale bits of the lane's group
 };
 
-template <bool HAS_V>
-__device__ __forceinline__ void load_full(LaneIO& x, const TensorDev& T, int64_t off) {
-    const uint16_t* p = reinterpret_cast<const uint16_t*>(T.param) + off;
-    const uint16_t* g = reinterpret_cast<const uint16_t*>(T.grad) + off;
-    uint4 a = ld128(p), b = ld128(p + 8);
-    x.p[0] = a.x; x.p[1] = a.y; x.p[2] = a.z; x.p[3] = a.w; x.p[4] = b.x; x.p[5] = b.y; x.p[6] = b.z; x.p[7] = b.w;
-    a = ld128(g); b = ld128(g + 8);
-    x.g[0] = a.x; x.g[1] = a.y; x.g[2] = a.z; x.g[3] = a.w; x.g[4] = b.x; x.g[5] = b.y; x.g[6] = b.z; x.g[7] = b.w;
-    a = ld128(T.rho + off);
-    x.r[0] = a.x; x.r[1] = a.y; x.r[2] = a.z; x.r[3] = a.w;
-    a = ld128(T.m_q + off);
-    x.mq[0] = a.x; x.mq[1] = a.y; x.mq[2] = a.z; x.mq[3] = a.w;
+// 4 * N bytes from / to a 4N-byte aligned address
+template <int N>
+__device__ __forceinline__ void ld_words(uint32_t (&w)[N], const void* p) {
+    static_assert(N == 2 || N == 4 || N == 8, "");
+    if constexpr (N == 2) {
+#if FO_NT_LOAD
+        const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+#else
+        const u32x2_t v = *reinterpret_cast<const u32x2_t*>(p);
+#endif
+        w[0] = v.x; w[1] = v.y;
+    } else if constexpr (N == 4) {
+        const uint4 a = ld128(p);
+        w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+    } else {
+        const uint4 a = ld128(p), b = ld128(reinterpret_cast<const uint8_t*>(p) + 16);
+        w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+    }
+}
+template <int N>
+__device__ __forceinline__ void st_words(void* p, const uint32_t (&w)[N]) {
+    if constexpr (N == 2) {
+        const u32x2_t v = {w[0], w[1]};
+#if FO_NT_STORE
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2_t*>(p));
+#else
+        *reinterpret_cast<u32x2_t*>(p) = v;
+#endif
+    } else if constexpr (N == 4) {
+        st128(p, w[0], w[1], w[2], w[3]);
+    } else {
+        st128(p, w[0], w[1], w[2], w[3]);
+        st128(reinterpret_cast<uint8_t*>(p) + 16, w[4], w[5], w[6], w[7]);
+    }
+}
+
+template <int VEC, bool HAS_V>
+__device__ __forceinline__ void load_full(LaneIO<VEC>& x, const TensorDev& T, int64_t off) {
+    ld_words(x.p, reinterpret_cast<const uint16_t*>(T.param) + off);
+    ld_words(x.g, reinterpret_cast<const uint16_t*>(T.grad) + off);
+    ld_words(x.r, T.rho + off);
+    ld_words(x.mq, T.m_q + off);
     x.ms = T.m_scale[off >> 5];
     if (HAS_V) {
-        a = ld128(T.v_q + off);
-        x.vq[0] = a.x; x.vq[1] = a.y; x.vq[2] = a.z; x.vq[3] = a.w;
+        ld_words(x.vq, T.v_q + off);
         x.vs = T.v_scale[off >> 5];
     }
 }
 
 // Ragged end of a tensor: element-wise loads, missing elements read as zero (a zero
 // element yields zero moments and therefore never raises its group's absmax).
-template <bool HAS_V>
-__device__ __forceinline__ void load_tail(LaneIO& x, const TensorDev& T, int64_t off, int cnt) {
+template <int VEC, bool HAS_V>
+__device__ __forceinline__ void load_tail(LaneIO<VEC>& x, const TensorDev& T, int64_t off, int cnt) {
     const uint16_t* p = reinterpret_cast<const uint16_t*>(T.param) + off;
     const uint16_t* g = reinterpret_cast<const uint16_t*>(T.grad) + off;
     const uint8_t* r = reinterpret_cast<const uint8_t*>(T.rho) + off;
     const uint8_t* mq = reinterpret_cast<const uint8_t*>(T.m_q) + off;
     const uint8_t* vq = T.v_q + off;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < VEC / 2; ++j) {
         uint32_t lo = (2 * j < cnt) ? p[2 * j] : 0u, hi = (2 * j + 1 < cnt) ? p[2 * j + 1] : 0u;
         x.p[j] = lo | (hi << 16);
         lo = (2 * j < cnt) ? g[2 * j] : 0u; hi = (2 * j + 1 < cnt) ? g[2 * j + 1] : 0u;
         x.g[j] = lo | (hi << 16);
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < VEC / 4; ++j) {
         uint32_t w = 0, wm = 0, wv = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -302,29 +394,28 @@ __device__ __forceinline__ void load_tail(LaneIO& x, const TensorDev& T, int64_t
     }
 }
 
-template <bool HAS_V>
-__device__ __forceinline__ void store_full(const LaneIO& y, const TensorDev& T, int64_t off, bool group_leader) {
-    uint16_t* p = reinterpret_cast<uint16_t*>(T.param) + off;
-    st128(p, y.p[0], y.p[1], y.p[2], y.p[3]);
-    st128(p + 8, y.p[4], y.p[5], y.p[6], y.p[7]);
-    st128(T.rho + off, y.r[0], y.r[1], y.r[2], y.r[3]);
-    st128(T.m_q + off, y.mq[0], y.mq[1], y.mq[2], y.mq[3]);
-    if (HAS_V) st128(T.v_q + off, y.vq[0], y.vq[1], y.vq[2], y.vq[3]);
+template <int VEC, bool HAS_V>
+__device__ __forceinline__ void store_full(const LaneIO<VEC>& y, const TensorDev& T, int64_t off,
+                                           bool group_leader) {
+    st_words(reinterpret_cast<uint16_t*>(T.param) + off, y.p);
+    st_words(T.rho + off, y.r);
+    st_words(T.m_q + off, y.mq);
+    if (HAS_V) st_words(T.v_q + off, y.vq);
     if (group_leader) {
         T.m_scale[off >> 5] = (uint16_t)y.ms;
         if (HAS_V) T.v_scale[off >> 5] = (uint16_t)y.vs;
     }
 }
 
-template <bool HAS_V>
-__device__ __forceinline__ void store_tail(const LaneIO& y, const TensorDev& T, int64_t off, int cnt,
+template <int VEC, bool HAS_V>
+__device__ __forceinline__ void store_tail(const LaneIO<VEC>& y, const TensorDev& T, int64_t off, int cnt,
                                            bool group_leader) {
     uint16_t* p = reinterpret_cast<uint16_t*>(T.param) + off;
     uint8_t* r = reinterpret_cast<uint8_t*>(T.rho) + off;
     uint8_t* mq = reinterpret_cast<uint8_t*>(T.m_q) + off;
     uint8_t* vq = T.v_q + off;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < VEC; ++i) {
         if (i < cnt) {
             p[i] = (uint16_t)(y.p[i >> 1] >> (16 * (i & 1)));
             r[i] = (uint8_t)(y.r[i >> 2] >> (8 * (i & 3)));
@@ -341,38 +432,38 @@ __device__ __forceinline__ void store_tail(const LaneIO& y, const TensorDev& T, 
 // ------------------------------------------------------- the per-lane update --
 //
 // KIND: 0 AdamW (Algorithm 4), 1 SGD (Algorithm 5), 2 Lion (Algorithm 6).
-// Operates on the 16 elements of one lane; the lane's pair partner (lane ^ 1) holds the
-// other half of the same 32-element group and must execute this function together with it.
-template <int KIND>
-__device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const DecodeTables& tab,
+// Operates on the VEC elements of one lane; the lanes holding the rest of the same 32-element
+// group (lane ^ 1, and lane ^ 2, lane ^ 3 when VEC == 8) must execute this function with it.
+template <int KIND, int VEC>
+__device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y, const DecodeTables& tab,
                                             const StepConsts& c, float lr, float wd) {
     constexpr bool HAS_V = (KIND == 0);
     const float s_m = (float)__builtin_bit_cast(_Float16, (uint16_t)x.ms);
     const float s_v = HAS_V ? (float)__builtin_bit_cast(_Float16, (uint16_t)x.vs) : 0.0f;
 
-    float mt[16];     // new momentum
-    float vt[16];     // new variance (AdamW)
-    float rh[16];     // sqrt of the bias-corrected new variance (AdamW)
+    float mt[VEC];    // new momentum
+    float vt[VEC];    // new variance (AdamW)
+    float rh[VEC];    // sqrt of the bias-corrected new variance (AdamW)
     float amax_m = 0.0f, amax_v = 0.0f;
 
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < VEC / 4; ++j) {
         // four elements at a time (one word of each byte stream)
         float th4[4], mh4[4], vh4[4];
         float tht[4];     // new master weights of this block
-        uint32_t vmin = 0xffffffffu;
+        float vmin = 3.0e38f;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int i = 4 * j + k;
             const uint32_t pw = x.p[i >> 1], gw = x.g[i >> 1];
-            const uint32_t pb = (i & 1) ? (pw >> 16) : (pw & 0xffffu);
+            const uint32_t pE = (i & 1) ? ((pw >> 23) & 0xffu) : ((pw >> 7) & 0xffu);
             const float base = (i & 1) ? u2f(pw & 0xffff0000u) : u2f(pw << 16);
             const float g = (i & 1) ? u2f(gw & 0xffff0000u) : u2f(gw << 16);
             const uint32_t rb = (x.r[j] >> (8 * k)) & 0xffu;
             const uint32_t mb = (x.mq[j] >> (8 * k)) & 0xffu;
             // prologue: reconstruct optimizer state and master weight
             const float m = tab.m[mb] * s_m;                         // Q_m^-1
-            const float th = reconstruct1(pb, base, tab.rho[rb]);    // C^-1
+            const float th = reconstruct_lds(tab, pE, base, tab.rho[rb]);    // C^-1
             float m_new;
             if (KIND == 0) {
                 const uint32_t vb = (x.vq[j] >> (8 * k)) & 0xffu;
@@ -387,7 +478,7 @@ __device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const De
                 th4[k] = th;
                 vt[i] = v_new;
                 amax_v = fmaxf(amax_v, v_new);
-                vmin = min(vmin, f2u(vhat) - 1u);    // 0 -> 0xffffffff: zero is fine for the fast root
+                vmin = fminf(vmin, vhat);
             } else if (KIND == 1) {
                 m_new = (c.beta1 * m) + g;                           // beta1 carries the momentum mu
                 tht[k] = th - (lr * (m_new + (wd * th)));
@@ -402,7 +493,8 @@ __device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const De
         }
         if (KIND == 0) {
             // sqrt(v_hat): the short sequence unless some lane holds a value below 2^-96
-            if (any_lane(vmin < kSqrtFastMinBits - 1u)) {
+            // (exact zeros take the general sequence too: one comparison covers both)
+            if (any_lane(vmin < kSqrtFastMin)) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrtf(vh4[k]);
             } else {
@@ -420,24 +512,27 @@ __device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const De
         const uint32_t w0 = bf16_pack(tht[0], tht[1]), w1 = bf16_pack(tht[2], tht[3]);
         y.p[2 * j] = w0;
         y.p[2 * j + 1] = w1;
-        y.r[j] = pack_low_bytes(rho_bits(tht[0], w0 & 0xffffu), rho_bits(tht[1], w0 >> 16),
-                                rho_bits(tht[2], w1 & 0xffffu), rho_bits(tht[3], w1 >> 16));
+        y.r[j] = pack_low_bytes(rho_bits_lds(tab, tht[0], w0 & 0xffffu, (w0 >> 7) & 0xffu),
+                                rho_bits_lds(tab, tht[1], w0 >> 16, (w0 >> 23) & 0xffu),
+                                rho_bits_lds(tab, tht[2], w1 & 0xffffu, (w1 >> 7) & 0xffu),
+                                rho_bits_lds(tab, tht[3], w1 >> 16, (w1 >> 23) & 0xffu));
     }
 
     // epilogue, part 2: group scales (one DPP swap joins the two lanes of a group).  The square root
     // is monotone, so the group maximum of sqrt(v) is the square root of the maximum of v.
-    amax_m = fmaxf(amax_m, swap_pair(amax_m));
+    amax_m = group_max<VEC>(amax_m);
     float r_m, r_v = 0.0f, kr255 = 0.0f;
-    y.ms = group_scale(amax_m, &r_m);
+    y.ms = group_scale_fast(amax_m, &r_m);
     if (HAS_V) {
-        amax_v = fmaxf(amax_v, swap_pair(amax_v));
-        y.vs = group_scale(sqrtf(amax_v), &r_v);
+        amax_v = group_max<VEC>(amax_v);
+        const float root_max = any_lane(amax_v < kSqrtFastMin) ? sqrtf(amax_v) : sqrt_rn_midrange(amax_v);
+        y.vs = group_scale_fast(root_max, &r_v);
         kr255 = (c.root_bc2 * r_v) * 255.0f;
     }
 
     // epilogue: state codes, four at a time; exact recomputation only near rounding ties
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < VEC / 4; ++j) {
         uint32_t cm[4];
         float dm = 0.0f;
 #pragma unroll
@@ -471,9 +566,10 @@ __device__ __forceinline__ void update_lane(const LaneIO& x, LaneIO& y, const De
 
 // ------------------------------------------------------------ step kernels --
 
-template <int KIND, bool DIRECT>
+template <int KIND, int VEC, bool DIRECT>
 __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     constexpr bool HAS_V = (KIND == 0);
+    constexpr int kTile = kThreads * VEC;      // elements per workgroup
     __shared__ DecodeTables tab;
     const int tid = (int)threadIdx.x;
 
@@ -487,44 +583,39 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         T = a.tensors[ck.x];
         chunk = (int64_t)ck.y;
     }
-    // one tile per workgroup: its streaming loads go out first, the decode tables are staged
-    // into LDS while they are in flight
-    static_assert(kChunkElems == kTileElems, "one tile per workgroup");
-    const int64_t off = chunk * kChunkElems + (int64_t)tid * kVec;
+    // One tile per workgroup, and no loop: a wavefront issues its stores and retires without
+    // waiting for them, and the dispatcher keeps the compute units full.  (Persistent workgroups
+    // that loop over tiles were measured 10 % slower: every iteration waits for the previous
+    // iteration's stores to be acknowledged before its loads return.)
+    // The streaming loads go out first; the decode tables are staged while they are in flight.
+    const int64_t off = chunk * kTile + (int64_t)tid * VEC;
     const int64_t left = T.numel - off;
-    const int cnt = left >= kVec ? kVec : (left > 0 ? (int)left : 0);
-    LaneIO x, y;
-    if (cnt == kVec) load_full<HAS_V>(x, T, off);
-    else load_tail<HAS_V>(x, T, off, cnt);
+    const int cnt = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+    LaneIO<VEC> x, y;
+    if (cnt == VEC) load_full<VEC, HAS_V>(x, T, off);
+    else load_tail<VEC, HAS_V>(x, T, off, cnt);
     fill_tables(tab, tid);
     __syncthreads();
-    // Both lanes of a group run the update together (the partner of a lane with cnt == 0 may
-    // hold elements); lanes past the end compute on zeros and store nothing.
-    update_lane<KIND>(x, y, tab, a.c, T.lr, T.wd);
-    const bool leader = (tid & 1) == 0;
-    if (cnt == kVec) store_full<HAS_V>(y, T, off, leader);
-    else store_tail<HAS_V>(y, T, off, cnt, leader);
+    // All lanes of a group run the update together (a lane with cnt == 0 may share its group
+    // with lanes that hold elements); lanes past the end compute on zeros and store nothing.
+    update_lane<KIND, VEC>(x, y, tab, a.c, T.lr, T.wd);
+    const bool leader = (tid & (kGroup / VEC - 1)) == 0;
+    if (cnt == VEC) store_full<VEC, HAS_V>(y, T, off, leader);
+    else store_tail<VEC, HAS_V>(y, T, off, cnt, leader);
 }
 
-template __global__ void step_kernel<0, false>(StepArgs);
-template __global__ void step_kernel<0, true>(StepArgs);
-template __global__ void step_kernel<1, false>(StepArgs);
-template __global__ void step_kernel<1, true>(StepArgs);
-template __global__ void step_kernel<2, false>(StepArgs);
-template __global__ void step_kernel<2, true>(StepArgs);
-
-void launch_step(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
+template <int KIND, int VEC>
+static hipError_t launch_kind(bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
     const dim3 grid((unsigned)n_blocks), block(kThreads);
-    if (kind == 0) {
-        if (direct) hipLaunchKernelGGL((step_kernel<0, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((step_kernel<0, false>), grid, block, 0, s, a);
-    } else if (kind == 1) {
-        if (direct) hipLaunchKernelGGL((step_kernel<1, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((step_kernel<1, false>), grid, block, 0, s, a);
-    } else {
-        if (direct) hipLaunchKernelGGL((step_kernel<2, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((step_kernel<2, false>), grid, block, 0, s, a);
-    }
+    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<KIND, VEC, false>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_step(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
+    if (kind == 0) return launch_kind<0, kVecAdamW>(direct, a, n_blocks, s);
+    if (kind == 1) return launch_kind<1, kVecSgdLion>(direct, a, n_blocks, s);
+    return launch_kind<2, kVecSgdLion>(direct, a, n_blocks, s);
 }
 
 // -------------------------------------------------------- standalone codecs --
