@@ -247,7 +247,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": ("fo::copy_kernel" if ckpt else
-                                f"fo::step_kernel<{['adamw', 'sgd', 'lion'].index(kind)}, {'true' if release else 'false'}>"),
+                                f"fo::step_kernel<{['adamw', 'sgd', 'lion'].index(kind)}, ..., {'true' if release else 'false'}>"),
                      "algorithmic_bytes_per_launch": algo_bytes if not release else None,
                      "bytes_per_param": BYTES_PER_PARAM[kind]},
     }

@@ -52,7 +52,8 @@ typedef enum flashoptim_status {
     FLASHOPTIM_ERR_MISALIGNED = -2,  /* a device pointer is not 16-byte aligned               */
     FLASHOPTIM_ERR_NUMEL_RANGE = -3, /* numel < 0 or >= 2^40                                  */
     FLASHOPTIM_ERR_HIP = -4,         /* a HIP runtime call failed (see flashoptim_last_hip_error) */
-    FLASHOPTIM_ERR_BAD_BLOB = -5     /* checkpoint blob too small, or header/table mismatch   */
+    FLASHOPTIM_ERR_BAD_BLOB = -5,    /* checkpoint blob too small, or header/table mismatch   */
+    FLASHOPTIM_ERR_SELFTEST = -6     /* flashoptim_selftest found a failing check             */
 } flashoptim_status;
 
 /* Optimizer kinds (checkpoint entry points). */
@@ -151,6 +152,19 @@ int flashoptim_checkpoint_unpack(int kind, const void* blob, int64_t blob_bytes,
  * failed HIP call on this thread (0 if none).  release_cache: frees the cached device chunk
  * tables (synchronises the device first).  version: (major << 16) | minor. */
 const char* flashoptim_strerror(int status);
+
+/* ---- device self-test ------------------------------------------------------------------
+ * The step kernels obtain some correctly rounded results (1/s of an FP16 scale, sqrt, the
+ * decision of an 8-bit code) from shorter instruction sequences that are exact provided the
+ * hardware reciprocal and square root are within 1 ulp.  This call checks those provisions on
+ * the current device against plain IEEE operations, exhaustively where the domain is small:
+ *   [0] Newton reciprocal of every positive finite FP16 value      [1] v_rcp_f32 within 1 ulp on [1, 4)
+ *   [2] short square root == sqrtf on 2^25 spread values and all of [1, 4)
+ *   [3] momentum codes (Algorithm 2) and [4] variance codes (Algorithm 3): the estimate equals the
+ *       exact code wherever the kernel's tie test does not ask for the exact evaluation.
+ * n_checked, n_failed: HOST arrays of 5 counters (one per section above).  Waits for completion.
+ * Returns FLASHOPTIM_OK, FLASHOPTIM_ERR_SELFTEST if any check failed, or another status. */
+int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream);
 int flashoptim_last_hip_error(void);
 int flashoptim_release_cache(void);
 int flashoptim_version(void);

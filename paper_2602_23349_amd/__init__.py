@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     split_weights, reconstruct_weights,
     quantize_momentum, dequantize_momentum, quantize_variance, dequantize_variance,
     checkpoint_size, checkpoint_pack, checkpoint_unpack,
-    strerror, release_cache, version, EXPORTED_SYMBOLS, KIND,
+    strerror, release_cache, version, selftest, EXPORTED_SYMBOLS, KIND,
 )

@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = [
     "flashoptim_quantize_variance", "flashoptim_dequantize_variance",
     "flashoptim_checkpoint_size", "flashoptim_checkpoint_pack", "flashoptim_checkpoint_unpack",
     "flashoptim_strerror", "flashoptim_last_hip_error", "flashoptim_release_cache", "flashoptim_version",
+    "flashoptim_selftest",
 ]
 
 
@@ -75,6 +76,7 @@ def load_library():
     L.flashoptim_checkpoint_size.restype = i64
     L.flashoptim_checkpoint_pack.argtypes = [i32, C.POINTER(_Tensor), i64, i64, vp, i64, vp]
     L.flashoptim_checkpoint_unpack.argtypes = [i32, vp, i64, C.POINTER(_Tensor), i64, C.POINTER(i64), vp]
+    L.flashoptim_selftest.argtypes = [C.POINTER(i64), C.POINTER(i64), vp]
     L.flashoptim_strerror.argtypes = [i32]
     L.flashoptim_strerror.restype = C.c_char_p
     for name in EXPORTED_SYMBOLS:
@@ -222,6 +224,16 @@ def checkpoint_unpack(kind, blob, tensors, stream=None):
                                                        tl.array, tl.n, C.byref(step), _stream(stream)),
            "flashoptim_checkpoint_unpack")
     return int(step.value)
+
+
+def selftest(stream=None):
+    """Runs the device self-test; returns (status, checked[5], failed[5])."""
+    checked = (C.c_int64 * 5)()
+    failed = (C.c_int64 * 5)()
+    status = load_library().flashoptim_selftest(checked, failed, _stream(stream))
+    if status not in (0, -6):
+        raise FlashOptimError(status, "flashoptim_selftest")
+    return status, list(checked), list(failed)
 
 
 def strerror(status):

@@ -479,6 +479,41 @@ int flashoptim_checkpoint_unpack(int kind, const void* blob, int64_t blob_bytes,
     return FLASHOPTIM_OK;
 }
 
+int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream_) {
+    if (!n_checked || !n_failed) return FLASHOPTIM_ERR_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    unsigned long long* d = nullptr;
+    FO_HIP(hipMalloc((void**)&d, fo::kSelftestCounters * sizeof(unsigned long long)));
+    hipError_t e = hipMemsetAsync(d, 0, fo::kSelftestCounters * sizeof(unsigned long long), stream);
+    StepConsts c;
+    std::memset(&c, 0, sizeof(c));
+    for (int section = 0; section < 4 && e == hipSuccess; ++section) e = fo::launch_selftest(d, section, c, 1.0f, stream);
+    // variance codes: bias corrections of steps 1, 2, 10, 1000 and "infinity", three group scales
+    const int64_t steps[5] = {1, 2, 10, 1000, 100000000};
+    const float scales[3] = {0.000244140625f /* 2^-12 */, 0.00131988525390625f, 0.03125f};
+    for (int i = 0; i < 5 && e == hipSuccess; ++i) {
+        c.rbc2 = recip_bias_correction(0.999f, steps[i]);
+        c.root_bc2 = (float)std::sqrt(1.0 / (double)c.rbc2);
+        for (int k = 0; k < 3 && e == hipSuccess; ++k) e = fo::launch_selftest(d, 4, c, 1.0f / scales[k], stream);
+    }
+    unsigned long long h[fo::kSelftestCounters] = {0};
+    if (e == hipSuccess) e = hipMemcpyAsync(h, d, sizeof(h), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    (void)hipFree(d);
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        (void)hipGetLastError();
+        return FLASHOPTIM_ERR_HIP;
+    }
+    int64_t failed = 0;
+    for (int sct = 0; sct < fo::kSelftestCounters / 2; ++sct) {
+        n_checked[sct] = (int64_t)h[2 * sct];
+        n_failed[sct] = (int64_t)h[2 * sct + 1];
+        failed += n_failed[sct];
+    }
+    return failed == 0 ? FLASHOPTIM_OK : FLASHOPTIM_ERR_SELFTEST;
+}
+
 const char* flashoptim_strerror(int status) {
     switch (status) {
         case FLASHOPTIM_OK: return "ok";
@@ -487,6 +522,7 @@ const char* flashoptim_strerror(int status) {
         case FLASHOPTIM_ERR_NUMEL_RANGE: return "numel out of range";
         case FLASHOPTIM_ERR_HIP: return "HIP runtime error";
         case FLASHOPTIM_ERR_BAD_BLOB: return "checkpoint blob too small or does not match the tensor list";
+        case FLASHOPTIM_ERR_SELFTEST: return "device self-test found a hardware operation outside its documented error bound";
         default: return "unknown status";
     }
 }

@@ -9,17 +9,25 @@
 namespace fo {
 
 constexpr int kGroup = 32;                         // quantisation group (Algorithms 2, 3)
-constexpr int kThreads = 256;                      // lanes per workgroup
+constexpr int kThreads = 256;                      // lanes per workgroup (codec and copy kernels)
+// Launch shape of the step kernels, per optimizer kind (0 AdamW, 1 SGD, 2 Lion): consecutive
+// elements per lane and lanes per workgroup.  One workgroup handles one chunk-table entry of
+// chunk_elems(kind) elements.
 #ifndef FO_VEC_ADAMW
 #define FO_VEC_ADAMW 8
 #endif
 #ifndef FO_VEC_SGD_LION
 #define FO_VEC_SGD_LION 8
 #endif
-constexpr int kVecAdamW = FO_VEC_ADAMW;            // consecutive elements per lane, AdamW kernel
-constexpr int kVecSgdLion = FO_VEC_SGD_LION;       // consecutive elements per lane, SGD / Lion kernels
-// elements per workgroup (= per chunk-table entry) for an optimizer kind
-constexpr int chunk_elems(int kind) { return kThreads * (kind == 0 ? kVecAdamW : kVecSgdLion); }
+#ifndef FO_THREADS_ADAMW
+#define FO_THREADS_ADAMW 256
+#endif
+#ifndef FO_THREADS_SGD_LION
+#define FO_THREADS_SGD_LION 512
+#endif
+constexpr int step_vec(int kind) { return kind == 0 ? FO_VEC_ADAMW : FO_VEC_SGD_LION; }
+constexpr int step_threads(int kind) { return kind == 0 ? FO_THREADS_ADAMW : FO_THREADS_SGD_LION; }
+constexpr int chunk_elems(int kind) { return step_threads(kind) * step_vec(kind); }
 constexpr int kCopyChunkBytes = 64 * 1024;         // checkpoint copy: bytes per workgroup
 
 // One tensor as the kernels see it (device pointers), 72 bytes.
@@ -64,6 +72,9 @@ void launch_reconstruct(const void* param, const int8_t* rho, float* theta, int6
 void launch_quantize(bool variance, const float* x, void* q, uint16_t* scale, int64_t n, hipStream_t s);
 void launch_dequantize(bool variance, const void* q, const uint16_t* scale, float* x, int64_t n, hipStream_t s);
 void launch_copy(const CopySegment* segs, const uint2* chunks, int64_t n_chunks, hipStream_t s);
+constexpr int kSelftestCounters = 10;   // two per section
+hipError_t launch_selftest(unsigned long long* counters, int section, const StepConsts& c, float scale_r,
+                           hipStream_t s);
 
 }  // namespace fo
 #endif

@@ -86,10 +86,10 @@ __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 template <int VEC>
 __device__ __forceinline__ float group_max(float x) {
     x = fmaxf(x, u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), 0xB1 /* quad_perm [1,0,3,2] */,
-                                                           0xf, 0xf, false)));
+                                                           0xf, 0xf, true)));
     if (VEC == 8)
         x = fmaxf(x, u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), 0x4E /* quad_perm [2,3,0,1] */,
-                                                               0xf, 0xf, false)));
+                                                               0xf, 0xf, true)));
     return x;
 }
 
@@ -265,13 +265,21 @@ constexpr DecodeTables make_decode_tables() {
 }
 __device__ const DecodeTables g_decode_tables = make_decode_tables();
 
-// Each workgroup stages the tables in LDS (one entry of each per lane; blockDim.x == 256).
+// Each workgroup stages the tables (6 KB, L2-resident) into LDS: one entry per lane per table.
+// With 512 lanes the two halves of the workgroup share the work.
+template <int THREADS>
 __device__ __forceinline__ void fill_tables(DecodeTables& t, int tid) {
-    t.rho[tid] = g_decode_tables.rho[tid];
-    t.m[tid] = g_decode_tables.m[tid];
-    t.v[tid] = g_decode_tables.v[tid];
-    t.half_ulp[tid] = g_decode_tables.half_ulp[tid];
-    t.split[tid] = g_decode_tables.split[tid];
+    static_assert(THREADS == 256 || THREADS == 512, "");
+    const int i = tid & 255;
+    if (THREADS == 256 || tid < 256) {
+        t.rho[i] = g_decode_tables.rho[i];
+        t.m[i] = g_decode_tables.m[i];
+        t.v[i] = g_decode_tables.v[i];
+    }
+    if (THREADS == 256 || tid >= 256) {
+        t.half_ulp[i] = g_decode_tables.half_ulp[i];
+        t.split[i] = g_decode_tables.split[i];
+    }
 }
 
 // In-kernel forms of C^-1 and of the rho half of C through the LDS tables.  E is the exponent
@@ -456,7 +464,8 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
         for (int k = 0; k < 4; ++k) {
             const int i = 4 * j + k;
             const uint32_t pw = x.p[i >> 1], gw = x.g[i >> 1];
-            const uint32_t pE = (i & 1) ? ((pw >> 23) & 0xffu) : ((pw >> 7) & 0xffu);
+            // (pair << 1) puts the two exponent fields on byte boundaries (bytes 1 and 3)
+            const uint32_t pE = (i & 1) ? ((pw << 1) >> 24) : (((pw << 1) >> 8) & 0xffu);
             const float base = (i & 1) ? u2f(pw & 0xffff0000u) : u2f(pw << 16);
             const float g = (i & 1) ? u2f(gw & 0xffff0000u) : u2f(gw << 16);
             const uint32_t rb = (x.r[j] >> (8 * k)) & 0xffu;
@@ -512,10 +521,11 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
         const uint32_t w0 = bf16_pack(tht[0], tht[1]), w1 = bf16_pack(tht[2], tht[3]);
         y.p[2 * j] = w0;
         y.p[2 * j + 1] = w1;
-        y.r[j] = pack_low_bytes(rho_bits_lds(tab, tht[0], w0 & 0xffffu, (w0 >> 7) & 0xffu),
-                                rho_bits_lds(tab, tht[1], w0 >> 16, (w0 >> 23) & 0xffu),
-                                rho_bits_lds(tab, tht[2], w1 & 0xffffu, (w1 >> 7) & 0xffu),
-                                rho_bits_lds(tab, tht[3], w1 >> 16, (w1 >> 23) & 0xffu));
+        const uint32_t e0 = w0 << 1, e1 = w1 << 1;     // exponent fields on byte boundaries
+        y.r[j] = pack_low_bytes(rho_bits_lds(tab, tht[0], w0 & 0xffffu, (e0 >> 8) & 0xffu),
+                                rho_bits_lds(tab, tht[1], w0 >> 16, e0 >> 24),
+                                rho_bits_lds(tab, tht[2], w1 & 0xffffu, (e1 >> 8) & 0xffu),
+                                rho_bits_lds(tab, tht[3], w1 >> 16, e1 >> 24));
     }
 
     // epilogue, part 2: group scales (one DPP swap joins the two lanes of a group).  The square root
@@ -566,10 +576,10 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
 
 // ------------------------------------------------------------ step kernels --
 
-template <int KIND, int VEC, bool DIRECT>
-__global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
+template <int KIND, int VEC, int THREADS, bool DIRECT>
+__global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
     constexpr bool HAS_V = (KIND == 0);
-    constexpr int kTile = kThreads * VEC;      // elements per workgroup
+    constexpr int kTile = THREADS * VEC;       // elements per workgroup
     __shared__ DecodeTables tab;
     const int tid = (int)threadIdx.x;
 
@@ -594,7 +604,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     LaneIO<VEC> x, y;
     if (cnt == VEC) load_full<VEC, HAS_V>(x, T, off);
     else load_tail<VEC, HAS_V>(x, T, off, cnt);
-    fill_tables(tab, tid);
+    fill_tables<THREADS>(tab, tid);
     __syncthreads();
     // All lanes of a group run the update together (a lane with cnt == 0 may share its group
     // with lanes that hold elements); lanes past the end compute on zeros and store nothing.
@@ -604,18 +614,19 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     else store_tail<VEC, HAS_V>(y, T, off, cnt, leader);
 }
 
-template <int KIND, int VEC>
+template <int KIND>
 static hipError_t launch_kind(bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
-    const dim3 grid((unsigned)n_blocks), block(kThreads);
-    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<KIND, VEC, false>), grid, block, 0, s, a);
+    constexpr int VEC = step_vec(KIND), THREADS = step_threads(KIND);
+    const dim3 grid((unsigned)n_blocks), block(THREADS);
+    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, false>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_step(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
-    if (kind == 0) return launch_kind<0, kVecAdamW>(direct, a, n_blocks, s);
-    if (kind == 1) return launch_kind<1, kVecSgdLion>(direct, a, n_blocks, s);
-    return launch_kind<2, kVecSgdLion>(direct, a, n_blocks, s);
+    if (kind == 0) return launch_kind<0>(direct, a, n_blocks, s);
+    if (kind == 1) return launch_kind<1>(direct, a, n_blocks, s);
+    return launch_kind<2>(direct, a, n_blocks, s);
 }
 
 // -------------------------------------------------------- standalone codecs --
@@ -697,6 +708,104 @@ void launch_dequantize(bool variance, const void* q, const uint16_t* scale, floa
                                      (const uint8_t*)q, scale, x, n);
     else hipLaunchKernelGGL((dequantize_kernel<false>), dim3(blocks_for(n)), dim3(kThreads), 0, s,
                             (const uint8_t*)q, scale, x, n);
+}
+
+// ------------------------------------------------------------------ self-test --
+//
+// The step kernels replace some exactly rounded operations by shorter sequences that give
+// the same bits provided the hardware behaves as documented (v_rcp_f32 and v_sqrt_f32 within
+// 1 ulp).  This kernel checks those provisions on the device it runs on, against the plain
+// IEEE operations:
+//   section 0: recip_of_fp16(s) == 1.0f / s for every positive finite FP16 value s;
+//   section 1: v_rcp_f32(d) within 1 ulp of 1.0f / d for every d in [1, 4);
+//   section 2: sqrt_rn_midrange(x) == sqrtf(x) on 2^25 values spread over [2^-96, 2^128) and on
+//              every value of the two binades [1, 4);
+//   section 3: momentum codes: wherever the tie test does not fire, m_code_fast == m_code_exact,
+//              for every m' in [2^-13, 2) of either sign;
+//   section 4: variance codes: same for v_code_fast against v_code_exact, over every FP32 value of
+//              four binades of v, several bias-correction pairs and several group scales.
+// counters[2 * section] counts checks, counters[2 * section + 1] failures.
+
+constexpr int kSelftestSections = 5;
+
+__device__ __forceinline__ void selftest_tally(unsigned long long* counters, int section, bool checked, bool failed) {
+    const unsigned long long c = __popcll(__builtin_amdgcn_ballot_w64(checked));
+    const unsigned long long f = __popcll(__builtin_amdgcn_ballot_w64(checked && failed));
+    if ((threadIdx.x & 63) == 0) {
+        if (c) atomicAdd(&counters[2 * section], c);
+        if (f) atomicAdd(&counters[2 * section + 1], f);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void selftest_kernel(unsigned long long* counters, int section,
+                                                            StepConsts c, float scale_r) {
+    const uint64_t gid = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    bool checked = false, failed = false;
+    if (section == 0) {
+        if (gid >= 1 && gid <= 0x7bffu) {
+            const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)gid);
+            checked = true;
+            failed = f2u(recip_of_fp16(s)) != f2u(1.0f / s);
+        }
+    } else if (section == 1) {
+        if (gid < (1ull << 24)) {
+            const float d = u2f(0x3f800000u + (uint32_t)gid);            // [1, 4)
+            const int32_t diff = (int32_t)f2u(__builtin_amdgcn_rcpf(d)) - (int32_t)f2u(1.0f / d);
+            checked = true;
+            failed = diff > 1 || diff < -1;
+        }
+    } else if (section == 2) {
+        if (gid < (1ull << 25) + (1ull << 24)) {
+            uint32_t bits;
+            if (gid < (1ull << 25)) bits = 0x0f800000u + (uint32_t)(gid * 55u);   // 2^-96 ... just below 2^128
+            else bits = 0x3f800000u + (uint32_t)(gid - (1ull << 25));             // [1, 4)
+            if (bits < 0x7f800000u) {
+                const float x = u2f(bits);
+                checked = true;
+                failed = f2u(sqrt_rn_midrange(x)) != f2u(sqrtf(x));
+            }
+        }
+    } else if (section == 3) {
+        if (gid < 2ull * 14 * (1ull << 23)) {
+            const uint32_t sign = (uint32_t)(gid & 1) << 31;
+            const uint32_t mag = 0x39000000u + (uint32_t)(gid >> 1);     // 2^-13 ... 2
+            const float m1 = u2f(sign | mag);
+            float resid;
+            const uint32_t fast = m_code_fast(m1, 1.0f, &resid) & 0xffu;
+            const uint32_t exact = m_code_exact(m1, 1.0f) & 0xffu;
+            checked = !(resid > 0.5f - kTieWindowM);
+            failed = fast != exact;
+        }
+    } else {
+        if (gid < 4ull * (1ull << 23)) {
+            // four binades of v starting at 2^-30, 2^-29, 2^-11, 2^-10 (odd and even exponents; with the
+            // scales used by the host the codes land in 6..64 and in 180..255 and beyond)
+            const uint32_t k = (uint32_t)(gid >> 23), mant = (uint32_t)gid & 0x7fffffu;
+            const uint32_t ebits = (k == 0 ? 97u : k == 1 ? 98u : k == 2 ? 116u : 117u) << 23;
+            const float v = u2f(ebits | mant);
+            const float root_hat = sqrtf(v * c.rbc2);
+            const float kr255 = (c.root_bc2 * scale_r) * 255.0f;
+            float resid;
+            const uint32_t fast = v_code_fast(root_hat, kr255, &resid) & 0xffu;
+            const uint32_t exact = v_code_exact(v, scale_r) & 0xffu;
+            checked = !(resid > 0.5f - kTieWindowV);
+            failed = fast != exact;
+        }
+    }
+    selftest_tally(counters, section, checked, failed);
+}
+
+hipError_t launch_selftest(unsigned long long* counters, int section, const StepConsts& c, float scale_r,
+                           hipStream_t s) {
+    uint64_t n = 0;
+    if (section == 0) n = 0x7c00;
+    else if (section == 1) n = 1ull << 24;
+    else if (section == 2) n = (1ull << 25) + (1ull << 24);
+    else if (section == 3) n = 2ull * 14 * (1ull << 23);
+    else n = 4ull * (1ull << 23);
+    hipLaunchKernelGGL(selftest_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s,
+                       counters, section, c, scale_r);
+    return hipGetLastError();
 }
 
 // ----------------------------------------------------------- checkpoint copy --
