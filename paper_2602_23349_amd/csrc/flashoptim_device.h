@@ -11,8 +11,8 @@ namespace fo {
 constexpr int kGroup = 32;                         // quantisation group (Algorithms 2, 3)
 constexpr int kThreads = 256;                      // lanes per workgroup (codec and copy kernels)
 // Launch shape of the step kernels, per optimizer kind (0 AdamW, 1 SGD, 2 Lion): consecutive
-// elements per lane and lanes per workgroup.  One workgroup handles one chunk-table entry of
-// chunk_elems(kind) elements.
+// elements per lane, lanes per workgroup, and tiles (passes) per workgroup.  One workgroup handles
+// one chunk-table entry of chunk_elems(kind) elements.
 #ifndef FO_VEC_ADAMW
 #define FO_VEC_ADAMW 8
 #endif
@@ -25,9 +25,16 @@ constexpr int kThreads = 256;                      // lanes per workgroup (codec
 #ifndef FO_THREADS_SGD_LION
 #define FO_THREADS_SGD_LION 512
 #endif
+#ifndef FO_TILES_ADAMW
+#define FO_TILES_ADAMW 1
+#endif
+#ifndef FO_TILES_SGD_LION
+#define FO_TILES_SGD_LION 1
+#endif
 constexpr int step_vec(int kind) { return kind == 0 ? FO_VEC_ADAMW : FO_VEC_SGD_LION; }
 constexpr int step_threads(int kind) { return kind == 0 ? FO_THREADS_ADAMW : FO_THREADS_SGD_LION; }
-constexpr int chunk_elems(int kind) { return step_threads(kind) * step_vec(kind); }
+constexpr int step_tiles(int kind) { return kind == 0 ? FO_TILES_ADAMW : FO_TILES_SGD_LION; }
+constexpr int chunk_elems(int kind) { return step_threads(kind) * step_vec(kind) * step_tiles(kind); }
 constexpr int kCopyChunkBytes = 64 * 1024;         // checkpoint copy: bytes per workgroup
 
 // One tensor as the kernels see it (device pointers), 72 bytes.

@@ -576,10 +576,10 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
 
 // ------------------------------------------------------------ step kernels --
 
-template <int KIND, int VEC, int THREADS, bool DIRECT>
+template <int KIND, int VEC, int THREADS, int TILES, bool DIRECT>
 __global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
     constexpr bool HAS_V = (KIND == 0);
-    constexpr int kTile = THREADS * VEC;       // elements per workgroup
+    constexpr int kTile = THREADS * VEC;       // elements per pass of the workgroup
     __shared__ DecodeTables tab;
     const int tid = (int)threadIdx.x;
 
@@ -593,33 +593,46 @@ __global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
         T = a.tensors[ck.x];
         chunk = (int64_t)ck.y;
     }
-    // One tile per workgroup, and no loop: a wavefront issues its stores and retires without
-    // waiting for them, and the dispatcher keeps the compute units full.  (Persistent workgroups
-    // that loop over tiles were measured 10 % slower: every iteration waits for the previous
-    // iteration's stores to be acknowledged before its loads return.)
-    // The streaming loads go out first; the decode tables are staged while they are in flight.
-    const int64_t off = chunk * kTile + (int64_t)tid * VEC;
-    const int64_t left = T.numel - off;
-    const int cnt = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+    // A workgroup handles TILES consecutive tiles of one tensor and then retires (persistent
+    // workgroups that loop over many tiles were measured 10 % slower: an iteration's loads then
+    // wait behind the previous iteration's stores).  The first tile's streaming loads go out
+    // before the decode tables are staged, so the staging hides behind them; the loads of tile
+    // k+1 are issued BEFORE the stores of tile k, so that waiting for them does not wait for
+    // those stores.
+    const bool leader = (tid & (kGroup / VEC - 1)) == 0;
+    int64_t off = chunk * (int64_t)(kTile * TILES) + (int64_t)tid * VEC;
+    int64_t left = T.numel - off;
+    int cnt = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
     LaneIO<VEC> x, y;
     if (cnt == VEC) load_full<VEC, HAS_V>(x, T, off);
     else load_tail<VEC, HAS_V>(x, T, off, cnt);
     fill_tables<THREADS>(tab, tid);
     __syncthreads();
-    // All lanes of a group run the update together (a lane with cnt == 0 may share its group
-    // with lanes that hold elements); lanes past the end compute on zeros and store nothing.
-    update_lane<KIND, VEC>(x, y, tab, a.c, T.lr, T.wd);
-    const bool leader = (tid & (kGroup / VEC - 1)) == 0;
-    if (cnt == VEC) store_full<VEC, HAS_V>(y, T, off, leader);
-    else store_tail<VEC, HAS_V>(y, T, off, cnt, leader);
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) {
+        // All lanes of a group run the update together (a lane with cnt == 0 may share its group
+        // with lanes that hold elements); lanes past the end compute on zeros and store nothing.
+        update_lane<KIND, VEC>(x, y, tab, a.c, T.lr, T.wd);
+        const int64_t off_done = off;
+        const int cnt_done = cnt;
+        if (t + 1 < TILES) {
+            off += kTile;
+            left = T.numel - off;
+            cnt = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+            if (cnt == VEC) load_full<VEC, HAS_V>(x, T, off);
+            else load_tail<VEC, HAS_V>(x, T, off, cnt);
+        }
+        if (cnt_done == VEC) store_full<VEC, HAS_V>(y, T, off_done, leader);
+        else store_tail<VEC, HAS_V>(y, T, off_done, cnt_done, leader);
+    }
 }
 
 template <int KIND>
 static hipError_t launch_kind(bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
-    constexpr int VEC = step_vec(KIND), THREADS = step_threads(KIND);
+    constexpr int VEC = step_vec(KIND), THREADS = step_threads(KIND), TILES = step_tiles(KIND);
     const dim3 grid((unsigned)n_blocks), block(THREADS);
-    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, false>), grid, block, 0, s, a);
+    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, TILES, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, TILES, false>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
