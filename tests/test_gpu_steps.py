@@ -199,3 +199,117 @@ def test_checkpoint_pack_unpack_small_lists():
         blob2 = blob.clone(); blob2[0] = 0
         with pytest.raises(fo.FlashOptimError):
             fo.checkpoint_unpack(kind, blob2, fresh)
+
+
+def test_hyperparameters_and_gradient_buffers_may_change_between_steps():
+    # lr follows a schedule, weight decay toggles, and gradients arrive in different buffers: the cached
+    # device table of the list must follow (it is re-uploaded in stream order when its content changes)
+    specs = W.odd_sizes()[8:20]
+    states = [oracle.TensorState(W.theta0(sp, i, seed=11).numpy(), "adamw") for i, sp in enumerate(specs)]
+    bufs = [upload_state(s) for s in states]
+    alt = [torch.empty_like(b.grad) for b in bufs]
+    tl = fo.TensorList(bufs)
+    for t in range(1, 8):
+        lr = 1e-3 * (0.5 + 0.1 * t)
+        grads = grads_for(specs, t, seed=11, scale=1e-3)
+        for i, (b, g, sp) in enumerate(zip(bufs, grads, specs)):
+            wd = 0.01 if (sp.role == "matrix" and t % 2) else 0.0
+            dst = b.grad if t % 3 else alt[i]
+            dst.copy_(g.cuda())
+            tl.set_grad(i, dst)
+            tl.set_hyper(i, lr=lr, weight_decay=wd)
+            oracle.adamw_step(states[i], _g_bits(g), lr, wd, 0.9, 0.999, 1e-8, t)
+        fo.adamw_step(tl, 0.9, 0.999, 1e-8, t)
+        # no synchronisation between steps: uploads and kernels are ordered on the stream
+    for i, s in enumerate(states):
+        rep = compare_state(download(bufs[i]), s, where=f"schedule {specs[i].name}")
+        assert sum(r[1] for r in rep) == 0
+
+
+def test_non_default_stream_and_two_lists_interleaved():
+    specs = W.odd_sizes()[10:16]
+    st_a = [oracle.TensorState(W.theta0(sp, i, seed=12).numpy(), "sgd") for i, sp in enumerate(specs)]
+    st_b = [oracle.TensorState(W.theta0(sp, i, seed=13).numpy(), "lion") for i, sp in enumerate(specs)]
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    ba = [upload_state(s) for s in st_a]
+    bb = [upload_state(s) for s in st_b]
+    for b in ba:
+        b.lr, b.weight_decay = SGD["lr"], SGD["wd"]
+    for b in bb:
+        b.lr, b.weight_decay = LION["lr"], LION["wd"]
+    tla, tlb = fo.TensorList(ba), fo.TensorList(bb)
+    torch.cuda.synchronize()
+    for t in (1, 2, 3):
+        ga = grads_for(specs, t, seed=12)
+        gb = grads_for(specs, t, seed=13)
+        with torch.cuda.stream(s1):
+            for b, g in zip(ba, ga):
+                b.grad.copy_(g.cuda(), non_blocking=True)
+            fo.sgd_step(tla, SGD["momentum"], stream=s1)
+        with torch.cuda.stream(s2):
+            for b, g in zip(bb, gb):
+                b.grad.copy_(g.cuda(), non_blocking=True)
+            fo.lion_step(tlb, LION["beta1"], LION["beta2"], stream=s2)
+        for s, g in zip(st_a, ga):
+            oracle.sgd_step(s, _g_bits(g), SGD["lr"], SGD["wd"], SGD["momentum"])
+        for s, g in zip(st_b, gb):
+            oracle.lion_step(s, _g_bits(g), LION["lr"], LION["wd"], LION["beta1"], LION["beta2"])
+    s1.synchronize(); s2.synchronize()
+    for b, s in zip(ba + bb, st_a + st_b):
+        rep = compare_state(download(b), s, where="streams")
+        assert sum(r[1] for r in rep) == 0
+
+
+def test_many_distinct_lists_evict_cached_tables():
+    # more distinct lists than the library keeps cached tables for; every call must still be right
+    spec = W.ParamSpec("w", (3000,), "matrix")
+    results = []
+    for k in range(70):
+        sts = [oracle.TensorState(W.theta0(spec, 100 * k + j, seed=14).numpy(), "sgd") for j in range(2)]
+        bufs = [upload_state(s) for s in sts]
+        for b in bufs:
+            b.lr, b.weight_decay = SGD["lr"], SGD["wd"]
+        gs = [W.grad_bf16(spec, 100 * k + j, 1, seed=14) for j in range(2)]
+        for b, g in zip(bufs, gs):
+            b.grad.copy_(g.cuda())
+        fo.sgd_step(bufs, SGD["momentum"])
+        for s, g in zip(sts, gs):
+            oracle.sgd_step(s, _g_bits(g), SGD["lr"], SGD["wd"], SGD["momentum"])
+        results.append((bufs, sts))
+    torch.cuda.synchronize()
+    for bufs, sts in results:
+        for b, s in zip(bufs, sts):
+            rep = compare_state(download(b), s, where="evict")
+            assert sum(r[1] for r in rep) == 0
+    fo.release_cache()
+
+
+def test_single_tensor_beyond_2_to_31_elements():
+    # 64-bit element offsets: one tensor of 2^31 + 2^20 + 77 elements (15.3 GB of AdamW state),
+    # oracle on sampled groups at the start, around element 2^31, and at the ragged end
+    n = (1 << 31) + (1 << 20) + 77
+    spec = W.ParamSpec("huge", (n,), "matrix")
+    ng = (n + 31) // 32
+    groups = np.array(sorted({0, 1, ng - 1, ng - 2, (1 << 31) // 32 - 1, (1 << 31) // 32, (1 << 31) // 32 + 1,
+                              (1 << 30) // 32, 3 * (1 << 29) // 32 + 5, ng // 3}), dtype=np.int64)
+    idx = (torch.from_numpy(groups).cuda()[:, None] * 32 + torch.arange(32, device="cuda")[None, :]).reshape(-1)
+    idx = idx[idx < n]
+    gidx = torch.from_numpy(groups).cuda()
+    b = fo.ParamBuffers(n, "adamw")
+    th = W.theta0(spec, 0, seed=15, device="cuda")
+    fo.split_weights(th, b.param, b.rho)
+    st = oracle.TensorState(th[idx].cpu().numpy(), "adamw")
+    del th
+    b.lr, b.weight_decay = ADAMW["lr"], ADAMW["wd"]
+    tl = fo.TensorList([b])
+    for t in (1, 2):
+        b.grad.copy_(W.grad_bf16(spec, 0, t, seed=15, device="cuda", scale=1e-3))
+        g = b.grad[idx].view(torch.int16).cpu().numpy().view(np.uint16)
+        fo.adamw_step(tl, 0.9, 0.999, 1e-8, t)
+        oracle.adamw_step(st, g, ADAMW["lr"], ADAMW["wd"], 0.9, 0.999, 1e-8, t)
+    got = dict(thp=bits16(b.param[idx]), rho=b.rho[idx].cpu().numpy(), mq=b.m_q[idx].cpu().numpy(),
+               ms=bits16(b.m_scale[gidx]), vq=b.v_q[idx].cpu().numpy(), vs=bits16(b.v_scale[gidx]))
+    rep = compare_state(got, st, where="huge tensor")
+    assert sum(r[1] for r in rep) == 0
+    del b, tl
+    torch.cuda.empty_cache()
