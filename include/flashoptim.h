@@ -113,6 +113,23 @@ int flashoptim_split_weights(const float* theta, void* param_bf16, int8_t* rho, 
 int flashoptim_reconstruct_weights(const void* param_bf16, const int8_t* rho, float* theta, int64_t n,
                                    void* stream);
 
+/* ---- 16-bit correction and the exhaustive reconstruction experiment (Section 4.4) ------
+ * Algorithm 1 with N = 32767: rho is an INT16 (theta' + rho = 32 bits, near-lossless).  Same
+ * conventions as the INT8 entry points above.  The fused steps use the INT8 form only.
+ * reconstruction_sweep: pushes the FP32 bit patterns first, first + stride, ... (< 2^32; stride 1
+ *   and first 0 = every FP32 value) through split then reconstruct with an 8- or 16-bit correction
+ *   and returns error statistics in `stats`, a HOST array of 520 doubles:
+ *   [0] values measured  [1] skipped (non-finite theta or theta')  [2] values with |theta - theta'| >
+ *   ULP(theta')/2  [3] max |theta_hat - theta| / (ULP(theta')/(4N))  [4] max relative error over normal
+ *   theta  [5] bit-exact reconstructions  [6] rho outside [-N, N]  [7] unused  [8 + E] sum and
+ *   [264 + E] count of the relative errors of the normal values with FP32 exponent field E (their ratio
+ *   is the mean relative error per exponent that Figure 3 plots).  Waits for completion. */
+int flashoptim_split_weights_i16(const float* theta, void* param_bf16, int16_t* rho, int64_t n, void* stream);
+int flashoptim_reconstruct_weights_i16(const void* param_bf16, const int16_t* rho, float* theta, int64_t n,
+                                       void* stream);
+int flashoptim_reconstruction_sweep(int correction_bits, uint64_t first, uint64_t stride, double* stats,
+                                    void* stream);
+
 /* ---- companded 8-bit state codecs (Section 3.2, Algorithms 2 and 3) -----------------
  * quantize_momentum:   per group s = FP16(max|m|), code = Round(127 * 2m'/(1+|m'|)), m' = m/s
  * dequantize_momentum: m = (z / (2 - |z|)) * s, z = code/127

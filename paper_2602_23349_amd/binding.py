@@ -22,7 +22,8 @@ EXPORTED_SYMBOLS = [
     "flashoptim_quantize_variance", "flashoptim_dequantize_variance",
     "flashoptim_checkpoint_size", "flashoptim_checkpoint_pack", "flashoptim_checkpoint_unpack",
     "flashoptim_strerror", "flashoptim_last_hip_error", "flashoptim_release_cache", "flashoptim_version",
-    "flashoptim_selftest",
+    "flashoptim_selftest", "flashoptim_split_weights_i16", "flashoptim_reconstruct_weights_i16",
+    "flashoptim_reconstruction_sweep",
 ]
 
 
@@ -69,7 +70,9 @@ def load_library():
     L.flashoptim_adamw_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_AdamWHp), vp]
     L.flashoptim_sgd_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_SgdHp), vp]
     L.flashoptim_lion_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_LionHp), vp]
-    for name in ("flashoptim_split_weights", "flashoptim_reconstruct_weights", "flashoptim_quantize_momentum",
+    L.flashoptim_reconstruction_sweep.argtypes = [i32, C.c_uint64, C.c_uint64, C.POINTER(C.c_double), vp]
+    for name in ("flashoptim_split_weights", "flashoptim_reconstruct_weights", "flashoptim_split_weights_i16",
+                 "flashoptim_reconstruct_weights_i16", "flashoptim_quantize_momentum",
                  "flashoptim_dequantize_momentum", "flashoptim_quantize_variance", "flashoptim_dequantize_variance"):
         getattr(L, name).argtypes = [vp, vp, vp, i64, vp]
     L.flashoptim_checkpoint_size.argtypes = [i32, C.POINTER(i64), i64]
@@ -180,6 +183,25 @@ def reconstruct_weights(param_bf16, rho, theta, stream=None):
     n = param_bf16.numel()
     _check(load_library().flashoptim_reconstruct_weights(_ptr(param_bf16), _ptr(rho), _ptr(theta), n, _stream(stream)),
            "flashoptim_reconstruct_weights")
+
+
+def split_weights_i16(theta, param_bf16, rho, stream=None):
+    _check(load_library().flashoptim_split_weights_i16(_ptr(theta), _ptr(param_bf16), _ptr(rho), theta.numel(),
+                                                       _stream(stream)), "flashoptim_split_weights_i16")
+
+
+def reconstruct_weights_i16(param_bf16, rho, theta, stream=None):
+    _check(load_library().flashoptim_reconstruct_weights_i16(_ptr(param_bf16), _ptr(rho), _ptr(theta),
+                                                             param_bf16.numel(), _stream(stream)),
+           "flashoptim_reconstruct_weights_i16")
+
+
+def reconstruction_sweep(correction_bits, first=0, stride=1, stream=None):
+    """Returns the 520 statistics of flashoptim_reconstruction_sweep as a list of floats."""
+    stats = (C.c_double * 520)()
+    _check(load_library().flashoptim_reconstruction_sweep(int(correction_bits), int(first), int(stride), stats,
+                                                          _stream(stream)), "flashoptim_reconstruction_sweep")
+    return list(stats)
 
 
 def quantize_momentum(m, q, scale, stream=None):

@@ -373,7 +373,7 @@ int flashoptim_lion_step(const flashoptim_tensor* tensors, int64_t n_tensors, co
 int flashoptim_split_weights(const float* theta, void* param_bf16, int8_t* rho, int64_t n, void* stream) {
     int rc = check_elementwise(theta, param_bf16, rho, n);
     if (rc != FLASHOPTIM_OK || n == 0) return rc;
-    fo::launch_split(theta, param_bf16, rho, n, static_cast<hipStream_t>(stream));
+    fo::launch_split(8, theta, param_bf16, rho, n, static_cast<hipStream_t>(stream));
     FO_HIP(hipGetLastError());
     return FLASHOPTIM_OK;
 }
@@ -381,8 +381,48 @@ int flashoptim_split_weights(const float* theta, void* param_bf16, int8_t* rho, 
 int flashoptim_reconstruct_weights(const void* param_bf16, const int8_t* rho, float* theta, int64_t n, void* stream) {
     int rc = check_elementwise(param_bf16, rho, theta, n);
     if (rc != FLASHOPTIM_OK || n == 0) return rc;
-    fo::launch_reconstruct(param_bf16, rho, theta, n, static_cast<hipStream_t>(stream));
+    fo::launch_reconstruct(8, param_bf16, rho, theta, n, static_cast<hipStream_t>(stream));
     FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_split_weights_i16(const float* theta, void* param_bf16, int16_t* rho, int64_t n, void* stream) {
+    int rc = check_elementwise(theta, param_bf16, rho, n);
+    if (rc != FLASHOPTIM_OK || n == 0) return rc;
+    fo::launch_split(16, theta, param_bf16, rho, n, static_cast<hipStream_t>(stream));
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_reconstruct_weights_i16(const void* param_bf16, const int16_t* rho, float* theta, int64_t n,
+                                       void* stream) {
+    int rc = check_elementwise(param_bf16, rho, theta, n);
+    if (rc != FLASHOPTIM_OK || n == 0) return rc;
+    fo::launch_reconstruct(16, param_bf16, rho, theta, n, static_cast<hipStream_t>(stream));
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_reconstruction_sweep(int correction_bits, uint64_t first, uint64_t stride, double* stats,
+                                    void* stream_) {
+    if ((correction_bits != 8 && correction_bits != 16) || stride == 0 || !stats) return FLASHOPTIM_ERR_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const uint64_t limit = 1ull << 32;
+    const uint64_t count = first < limit ? (limit - first + stride - 1) / stride : 0;
+    for (int i = 0; i < fo::kSweepStats; ++i) stats[i] = 0.0;
+    if (count == 0) return FLASHOPTIM_OK;
+    double* d = nullptr;
+    FO_HIP(hipMalloc((void**)&d, fo::kSweepStats * sizeof(double)));
+    hipError_t e = hipMemsetAsync(d, 0, fo::kSweepStats * sizeof(double), stream);
+    if (e == hipSuccess) e = fo::launch_sweep(correction_bits, first, stride, count, d, stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(stats, d, fo::kSweepStats * sizeof(double), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    (void)hipFree(d);
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        (void)hipGetLastError();
+        return FLASHOPTIM_ERR_HIP;
+    }
     return FLASHOPTIM_OK;
 }
 

@@ -74,8 +74,10 @@ struct CopySegment {
 };
 
 hipError_t launch_step(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s);
-void launch_split(const float* theta, void* param, int8_t* rho, int64_t n, hipStream_t s);
-void launch_reconstruct(const void* param, const int8_t* rho, float* theta, int64_t n, hipStream_t s);
+void launch_split(int bits, const float* theta, void* param, void* rho, int64_t n, hipStream_t s);
+void launch_reconstruct(int bits, const void* param, const void* rho, float* theta, int64_t n, hipStream_t s);
+constexpr int kSweepStats = 8 + 2 * 256;
+hipError_t launch_sweep(int bits, uint64_t first, uint64_t stride, uint64_t count, double* stats, hipStream_t s);
 void launch_quantize(bool variance, const float* x, void* q, uint16_t* scale, int64_t n, hipStream_t s);
 void launch_dequantize(bool variance, const void* q, const uint16_t* scale, float* x, int64_t n, hipStream_t s);
 void launch_copy(const CopySegment* segs, const uint2* chunks, int64_t n_chunks, hipStream_t s);

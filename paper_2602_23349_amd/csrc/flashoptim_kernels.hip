@@ -105,24 +105,6 @@ __device__ __forceinline__ int half_ulp_log2(uint32_t b) {
     return E - 135;
 }
 
-// C^-1: theta' (bits in the low 16 of b, value `base`) and q = rho/127 -> theta_hat (Eq. 2).
-__device__ __forceinline__ float reconstruct1(uint32_t b, float base, float q) {
-    return base + ldexpf(q, half_ulp_log2(b));
-}
-
-// Second half of C for one element whose BF16 rounding `b` (low 16 bits) is known:
-// rho = Round(Clamp(e * 2^-l, -1, 1) * 127) (Eq. 1); the result's low byte is the code.
-// For a finite theta' round-to-nearest guarantees |e| <= 2^l, so the clamp is the identity.
-// For theta' = +-inf, e is -+inf or NaN, and the low mantissa byte of (+-inf or NaN) + 1.5*2^23
-// is 0: the correction of a non-finite weight is 0 without a separate test.
-__device__ __forceinline__ uint32_t rho_bits(float theta, uint32_t b) {
-    const float base = u2f(b << 16);
-    const float e = theta - base;
-    const int E = (int)((b >> 7) & 0xffu);
-    const float en = ldexpf(e, 135 - (E < 1 ? 1 : E));
-    return round_to_int_bits(en * 127.0f);
-}
-
 // BF16 round-to-nearest-even of two floats: a in the low half, b in the high half.
 __device__ __forceinline__ uint32_t bf16_pack(float a, float b) {
     floatx2_t f = {a, b};
@@ -647,23 +629,110 @@ hipError_t launch_step(int kind, bool direct, const StepArgs& a, int64_t n_block
 // Not on the per-step path (used at initialisation, for inspection and by tests):
 // one lane per element / per group, plain global accesses.
 
-__global__ __launch_bounds__(kThreads) void split_kernel(const float* theta, uint16_t* param, int8_t* rho,
-                                                         int64_t n) {
+// C and C^-1 for a correction of N = 127 (INT8) or N = 32767 (INT16) levels per side,
+// written out plainly (Algorithm 1; the fused kernels use table-driven forms of the N = 127 case).
+template <int N>
+__device__ __forceinline__ int split_rho(float theta, uint32_t b) {
+    const int E = (int)((b >> 7) & 0xffu);
+    if (E == 255) return 0;                                   // non-finite theta': no correction
+    const float e = theta - u2f(b << 16);
+    const float en = ldexpf(e, 135 - (E < 1 ? 1 : E));        // e * 2^-l, exact
+    const float c = __builtin_amdgcn_fmed3f(en, -1.0f, 1.0f);
+    return (int)rintf(c * (float)N);
+}
+template <int N>
+__device__ __forceinline__ float reconstruct_n(uint32_t b, int rho) {
+    const float base = u2f(b << 16);
+    if (((b >> 7) & 0xffu) == 255u) return base;
+    const float q = (float)rho / (float)N;
+    return base + ldexpf(q, half_ulp_log2(b));
+}
+
+template <int N, typename RHO>
+__global__ __launch_bounds__(kThreads) void split_kernel(const float* theta, uint16_t* param, RHO* rho, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= n) return;
     const float t = theta[i];
     const uint32_t b = bf16_pack(t, 0.0f) & 0xffffu;
     param[i] = (uint16_t)b;
-    rho[i] = (int8_t)(rho_bits(t, b) & 0xffu);
+    rho[i] = (RHO)split_rho<N>(t, b);
 }
 
-__global__ __launch_bounds__(kThreads) void reconstruct_kernel(const uint16_t* param, const int8_t* rho,
-                                                               float* theta, int64_t n) {
+template <int N, typename RHO>
+__global__ __launch_bounds__(kThreads) void reconstruct_kernel(const uint16_t* param, const RHO* rho, float* theta,
+                                                               int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= n) return;
-    const uint32_t b = param[i];
-    const float q = (float)(int)rho[i] / 127.0f;
-    theta[i] = reconstruct1(b, u2f(b << 16), q);
+    theta[i] = reconstruct_n<N>(param[i], (int)rho[i]);
+}
+
+// The data-independent experiment of Section 4.4: FP32 bit patterns first, first + stride, ...
+// (below 2^32) go through C then C^-1; errors are measured in double.  Statistics layout
+// (doubles): [0] values measured, [1] skipped (non-finite theta or theta'), [2] values with
+// |theta - theta'| > ULP(theta')/2, [3] max |theta_hat - theta| / (ULP(theta')/(4N)),
+// [4] max relative error over normal theta, [5] bit-exact reconstructions, [6] rho outside
+// [-N, N], [7] unused, [8 + E] sum of relative errors and [264 + E] count of the normal values
+// with FP32 exponent field E.  [3] and [4] are accumulated as the bit patterns of non-negative
+// doubles with an integer maximum.
+constexpr int kSweepPerLane = 256;
+
+template <int N>
+__global__ __launch_bounds__(kThreads) void sweep_kernel(uint64_t first, uint64_t stride, uint64_t count,
+                                                         double* st) {
+    __shared__ double bin_sum[256];
+    __shared__ double bin_cnt[256];
+    bin_sum[threadIdx.x] = 0.0;
+    bin_cnt[threadIdx.x] = 0.0;
+    __syncthreads();
+    const uint64_t j0 = ((uint64_t)blockIdx.x * kThreads + threadIdx.x) * kSweepPerLane;
+    double measured = 0, skipped = 0, viol = 0, exact = 0, range_bad = 0, max_ratio = 0, max_rel = 0;
+    double run_sum = 0, run_cnt = 0;
+    int run_exp = -1;
+    for (int k = 0; k < kSweepPerLane; ++k) {
+        const uint64_t j = j0 + (uint64_t)k;
+        if (j >= count) break;
+        const uint32_t bits = (uint32_t)(first + j * stride);
+        const float theta = u2f(bits);
+        const uint32_t Ef = (bits >> 23) & 0xffu;
+        if (Ef == 255u) { skipped += 1; continue; }
+        const uint32_t b = bf16_pack(theta, 0.0f) & 0xffffu;
+        if (((b >> 7) & 0xffu) == 255u) { skipped += 1; continue; }
+        const int rho = split_rho<N>(theta, b);
+        const float hat = reconstruct_n<N>(b, rho);
+        measured += 1;
+        const double th = (double)theta, tp = (double)u2f(b << 16);
+        int E = (int)((b >> 7) & 0xffu);
+        E = E < 1 ? 1 : E;
+        const double u = ldexp(1.0, E - 134);
+        if (fabs(th - tp) > 0.5 * u) viol += 1;
+        const double err = fabs((double)hat - th);
+        const double ratio = err / (u / (4.0 * N));
+        max_ratio = ratio > max_ratio ? ratio : max_ratio;
+        if (hat == theta) exact += 1;
+        if (rho < -N || rho > N) range_bad += 1;
+        if (Ef >= 1u) {
+            const double rel = err / fabs(th);
+            max_rel = rel > max_rel ? rel : max_rel;
+            if ((int)Ef != run_exp) {
+                if (run_cnt > 0) { atomicAdd(&bin_sum[run_exp], run_sum); atomicAdd(&bin_cnt[run_exp], run_cnt); }
+                run_exp = (int)Ef; run_sum = 0; run_cnt = 0;
+            }
+            run_sum += rel; run_cnt += 1;
+        }
+    }
+    if (run_cnt > 0) { atomicAdd(&bin_sum[run_exp], run_sum); atomicAdd(&bin_cnt[run_exp], run_cnt); }
+    if (measured > 0) atomicAdd(&st[0], measured);
+    if (skipped > 0) atomicAdd(&st[1], skipped);
+    if (viol > 0) atomicAdd(&st[2], viol);
+    if (exact > 0) atomicAdd(&st[5], exact);
+    if (range_bad > 0) atomicAdd(&st[6], range_bad);
+    atomicMax(reinterpret_cast<unsigned long long*>(&st[3]), (unsigned long long)__double_as_longlong(max_ratio));
+    atomicMax(reinterpret_cast<unsigned long long*>(&st[4]), (unsigned long long)__double_as_longlong(max_rel));
+    __syncthreads();
+    if (bin_cnt[threadIdx.x] > 0) {
+        atomicAdd(&st[8 + threadIdx.x], bin_sum[threadIdx.x]);
+        atomicAdd(&st[264 + threadIdx.x], bin_cnt[threadIdx.x]);
+    }
 }
 
 // One lane per group of 32.
@@ -702,12 +771,24 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* q, 
 
 static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads); }
 
-void launch_split(const float* theta, void* param, int8_t* rho, int64_t n, hipStream_t s) {
-    hipLaunchKernelGGL(split_kernel, dim3(blocks_for(n)), dim3(kThreads), 0, s, theta, (uint16_t*)param, rho, n);
+void launch_split(int bits, const float* theta, void* param, void* rho, int64_t n, hipStream_t s) {
+    if (bits == 8) hipLaunchKernelGGL((split_kernel<127, int8_t>), dim3(blocks_for(n)), dim3(kThreads), 0, s, theta,
+                                      (uint16_t*)param, (int8_t*)rho, n);
+    else hipLaunchKernelGGL((split_kernel<32767, int16_t>), dim3(blocks_for(n)), dim3(kThreads), 0, s, theta,
+                            (uint16_t*)param, (int16_t*)rho, n);
 }
-void launch_reconstruct(const void* param, const int8_t* rho, float* theta, int64_t n, hipStream_t s) {
-    hipLaunchKernelGGL(reconstruct_kernel, dim3(blocks_for(n)), dim3(kThreads), 0, s, (const uint16_t*)param, rho,
-                       theta, n);
+void launch_reconstruct(int bits, const void* param, const void* rho, float* theta, int64_t n, hipStream_t s) {
+    if (bits == 8) hipLaunchKernelGGL((reconstruct_kernel<127, int8_t>), dim3(blocks_for(n)), dim3(kThreads), 0, s,
+                                      (const uint16_t*)param, (const int8_t*)rho, theta, n);
+    else hipLaunchKernelGGL((reconstruct_kernel<32767, int16_t>), dim3(blocks_for(n)), dim3(kThreads), 0, s,
+                            (const uint16_t*)param, (const int16_t*)rho, theta, n);
+}
+hipError_t launch_sweep(int bits, uint64_t first, uint64_t stride, uint64_t count, double* stats, hipStream_t s) {
+    const uint64_t lanes = (count + kSweepPerLane - 1) / kSweepPerLane;
+    const unsigned grid = (unsigned)((lanes + kThreads - 1) / kThreads);
+    if (bits == 8) hipLaunchKernelGGL((sweep_kernel<127>), dim3(grid), dim3(kThreads), 0, s, first, stride, count, stats);
+    else hipLaunchKernelGGL((sweep_kernel<32767>), dim3(grid), dim3(kThreads), 0, s, first, stride, count, stats);
+    return hipGetLastError();
 }
 void launch_quantize(bool variance, const float* x, void* q, uint16_t* scale, int64_t n, hipStream_t s) {
     const int64_t groups = (n + kGroup - 1) / kGroup;
