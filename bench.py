@@ -50,19 +50,40 @@ def parse_args():
                     help="fused: one multi-tensor launch per step; grad_release: one call per tensor in "
                          "reverse list order with a single reused gradient buffer; ckpt_pack / ckpt_unpack: "
                          "a 'step' is one checkpoint gather / scatter of the whole list (a plain copy)")
+    ap.add_argument("--variant", default="flash", choices=["flash", "wsplit", "oquant", "ref"],
+                    help="flash: both techniques on (the product path); wsplit: split weights + FP32 states; "
+                         "oquant: FP32 weights + 8-bit states; ref: plain FP32 optimizer (BF16 gradients). "
+                         "The last three are the ablation entry points (fused mode only).")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
 
-def build_state(fo, W, torch, specs, kind, hp, dist, scale, seed, with_grads):
+VARIANT_FLAGS = {"flash": (True, True), "wsplit": (True, False), "oquant": (False, True), "ref": (False, False)}
+
+
+def variant_bytes(kind, variant):
+    """Algorithmic bytes read + written per parameter."""
+    split, quant = VARIANT_FLAGS[variant]
+    nstate = 2 if kind == "adamw" else 1
+    w = (2 + 1) * 2 if split else 4 * 2                       # weights (+ correction), in and out
+    st = (1 + 2 / 32) * 2 * nstate if quant else 4 * 2 * nstate
+    return w + st + 2                                         # + BF16 gradient, read once
+
+
+def build_state(fo, W, torch, specs, kind, hp, dist, scale, seed, with_grads, variant="flash"):
     """Device buffers for the whole list: theta_0 is drawn per tensor in FP32 on the device and split by
     the library; gradients are drawn in BF16 on the device."""
+    split, quant = VARIANT_FLAGS[variant]
     bufs = []
     for i, sp in enumerate(specs):
-        b = fo.ParamBuffers(sp.numel, kind, device="cuda", with_grad=with_grads)
+        b = fo.ParamBuffers(sp.numel, kind, device="cuda", with_grad=with_grads, split_weights=split,
+                            quantize_states=quant)
         th = W.theta0(sp, i, seed=seed, device="cuda")
-        fo.split_weights(th, b.param, b.rho)
+        if split:
+            fo.split_weights(th, b.param, b.rho)
+        else:
+            b.theta.copy_(th)
         del th
         if with_grads:
             sc = W.tensor_sigma(i, seed) if scale is None else scale
@@ -74,7 +95,14 @@ def build_state(fo, W, torch, specs, kind, hp, dist, scale, seed, with_grads):
 
 
 def step_call(fo, kind, tl, hp, t):
-    if kind == "adamw":
+    if isinstance(tl, fo.TensorListEx):
+        if kind == "adamw":
+            fo.adamw_step_ex(tl, hp["beta1"], hp["beta2"], hp["eps"], t)
+        elif kind == "sgd":
+            fo.sgd_step_ex(tl, hp["momentum"])
+        else:
+            fo.lion_step_ex(tl, hp["beta1"], hp["beta2"])
+    elif kind == "adamw":
         fo.adamw_step(tl, hp["beta1"], hp["beta2"], hp["eps"], t)
     elif kind == "sgd":
         fo.sgd_step(tl, hp["momentum"])
@@ -175,8 +203,12 @@ def main():
     release = args.mode == "grad_release"
     ckpt = args.mode.startswith("ckpt")
 
-    bufs = build_state(fo, W, torch, specs, kind, hp, dist, scale, seed, with_grads=not (release or ckpt))
-    tl = fo.TensorList(bufs)
+    if args.variant != "flash" and args.mode != "fused":
+        print("bench.py: --variant other than flash is available in fused mode only", file=sys.stderr)
+        sys.exit(2)
+    bufs = build_state(fo, W, torch, specs, kind, hp, dist, scale, seed, with_grads=not (release or ckpt),
+                       variant=args.variant)
+    tl = fo.TensorList(bufs) if args.variant == "flash" else fo.TensorListEx(bufs)
     stream = torch.cuda.current_stream()
 
     if ckpt:
@@ -227,20 +259,22 @@ def main():
     value = n_params * args.steps / (total_ms * 1e-3)
 
     launches = len(specs) if release else 1
-    algo_bytes = BYTES_PER_PARAM[kind] * n_params           # per step = per launch in fused mode
+    bytes_per_param = variant_bytes(kind, args.variant)
+    assert args.variant != "flash" or bytes_per_param == BYTES_PER_PARAM[kind]
+    algo_bytes = bytes_per_param * n_params                 # per step = per launch in fused mode
     if ckpt:
         payload = sum(2 * s.numel + s.numel * (3 if kind == "adamw" else 2)
                       + 2 * ((s.numel + 31) // 32) * (2 if kind == "adamw" else 1) for s in specs)
         algo_bytes = 2.0 * payload                          # every payload byte is read once and written once
     achieved = algo_bytes / (ms_per_step * 1e-3) / 1e9
-    traffic = None if (release or ckpt) else read_traffic(kind, args.workload)
+    traffic = None if (release or ckpt or args.variant != "flash") else read_traffic(kind, args.workload)
     out = {
         "metric": "optimizer_step_params_per_sec", "value": value, "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "optimizer": kind, "tensors": len(specs), "params": n_params,
-                   "mode": args.mode, "launches_per_step": launches,
+                   "mode": args.mode, "variant": args.variant, "launches_per_step": launches,
                    "resident_bytes_per_param": (7.125 if kind == "adamw" else 6.0625) - (2 if release else 0),
                    "min_ms_step": min(per_step_ms), "max_ms_step": max(per_step_ms),
                    "wall_ms_per_step": wall * 1e3 / args.steps},
@@ -249,9 +283,9 @@ def main():
                      "kernel": ("fo::copy_kernel" if ckpt else
                                 f"fo::step_kernel<{['adamw', 'sgd', 'lion'].index(kind)}, ..., {'true' if release else 'false'}>"),
                      "algorithmic_bytes_per_launch": algo_bytes if not release else None,
-                     "bytes_per_param": BYTES_PER_PARAM[kind]},
+                     "bytes_per_param": bytes_per_param},
     }
-    if not args.no_cpu_baseline and not ckpt:
+    if not args.no_cpu_baseline and not ckpt and args.variant == "flash":
         del bufs, tl
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(W, specs, kind, hp, dist, scale, seed, args.cpu_seconds)

@@ -104,6 +104,33 @@ int flashoptim_sgd_step(const flashoptim_tensor* tensors, int64_t n_tensors,
 int flashoptim_lion_step(const flashoptim_tensor* tensors, int64_t n_tensors,
                          const flashoptim_lion_hp* hp, void* stream);
 
+/* ---- ablation and reference variants of the steps (Section 4.3) -----------------------
+ * The paper isolates its two techniques: "Weight Split" (split weights, FP32 states) and
+ * "Opt. Quant." (FP32 master weights, 8-bit states); with both off the step is the plain FP32
+ * optimizer (Algorithms 4-6 without their highlighted lines), here still fed BF16 gradients.
+ * flags: FLASHOPTIM_SPLIT_WEIGHTS | FLASHOPTIM_QUANTIZE_STATES selects which technique is ON; both on
+ * is identical to the plain entry points above.
+ * With splitting off, `theta` ([numel] FP32, in/out) is the master weight and t.param / t.rho are
+ * ignored; with state quantisation off, `m` (and `v` for AdamW; [numel] FP32, in/out) hold the
+ * states and t.m_q / t.m_scale / t.v_q / t.v_scale are ignored.  Ignored pointers may be NULL.
+ * Bytes moved per parameter (AdamW): 12.25 both on; 24 weight split only; 14.25 state quantisation
+ * only; 26 both off. */
+enum { FLASHOPTIM_SPLIT_WEIGHTS = 1, FLASHOPTIM_QUANTIZE_STATES = 2 };
+
+typedef struct flashoptim_tensor_ex {
+    flashoptim_tensor t;  /* compressed buffers, grad, numel, lr, weight_decay                   */
+    float* theta;         /* [numel] FP32 master weight, used when weights are not split         */
+    float* m;             /* [numel] FP32 momentum, used when states are not quantized           */
+    float* v;             /* [numel] FP32 variance (AdamW), used when states are not quantized   */
+} flashoptim_tensor_ex;
+
+int flashoptim_adamw_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tensors,
+                             const flashoptim_adamw_hp* hp, unsigned flags, void* stream);
+int flashoptim_sgd_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tensors,
+                           const flashoptim_sgd_hp* hp, unsigned flags, void* stream);
+int flashoptim_lion_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tensors,
+                            const flashoptim_lion_hp* hp, unsigned flags, void* stream);
+
 /* ---- weight splitting (Section 3.1, Algorithm 1, N = 127) --------------------------
  * split:       theta (FP32) -> theta' = BF16 round-to-nearest-even, rho = Round(e / (ULP(theta')/2) * 127)
  *              Used once at the start of training (Algorithm 4, line 3).

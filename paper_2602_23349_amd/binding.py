@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = [
     "flashoptim_strerror", "flashoptim_last_hip_error", "flashoptim_release_cache", "flashoptim_version",
     "flashoptim_selftest", "flashoptim_split_weights_i16", "flashoptim_reconstruct_weights_i16",
     "flashoptim_reconstruction_sweep",
+    "flashoptim_adamw_step_ex", "flashoptim_sgd_step_ex", "flashoptim_lion_step_ex",
 ]
 
 
@@ -40,6 +41,13 @@ class _Tensor(C.Structure):
     _fields_ = [("param", C.c_void_p), ("rho", C.c_void_p), ("grad", C.c_void_p),
                 ("m_q", C.c_void_p), ("m_scale", C.c_void_p), ("v_q", C.c_void_p), ("v_scale", C.c_void_p),
                 ("numel", C.c_int64), ("lr", C.c_float), ("weight_decay", C.c_float)]
+
+
+class _TensorEx(C.Structure):
+    _fields_ = [("t", _Tensor), ("theta", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p)]
+
+
+SPLIT_WEIGHTS, QUANTIZE_STATES = 1, 2
 
 
 class _AdamWHp(C.Structure):
@@ -70,6 +78,9 @@ def load_library():
     L.flashoptim_adamw_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_AdamWHp), vp]
     L.flashoptim_sgd_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_SgdHp), vp]
     L.flashoptim_lion_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_LionHp), vp]
+    L.flashoptim_adamw_step_ex.argtypes = [C.POINTER(_TensorEx), i64, C.POINTER(_AdamWHp), C.c_uint, vp]
+    L.flashoptim_sgd_step_ex.argtypes = [C.POINTER(_TensorEx), i64, C.POINTER(_SgdHp), C.c_uint, vp]
+    L.flashoptim_lion_step_ex.argtypes = [C.POINTER(_TensorEx), i64, C.POINTER(_LionHp), C.c_uint, vp]
     L.flashoptim_reconstruction_sweep.argtypes = [i32, C.c_uint64, C.c_uint64, C.POINTER(C.c_double), vp]
     for name in ("flashoptim_split_weights", "flashoptim_reconstruct_weights", "flashoptim_split_weights_i16",
                  "flashoptim_reconstruct_weights_i16", "flashoptim_quantize_momentum",
@@ -105,19 +116,30 @@ def _check(status, where):
 
 
 class ParamBuffers:
-    """Device buffers of one parameter in the compressed layout (allocation only)."""
+    """Device buffers of one parameter (allocation only).  split_weights / quantize_states choose the
+    compressed layout (default) or the FP32 arrays of the ablation variants for each half."""
 
-    def __init__(self, numel, kind, device="cuda", with_grad=True):
+    def __init__(self, numel, kind, device="cuda", with_grad=True, split_weights=True, quantize_states=True):
         ng = (numel + 31) // 32
+        has_v = kind == "adamw"
         self.numel, self.kind = int(numel), kind
-        self.param = torch.zeros(numel, dtype=torch.bfloat16, device=device)
-        self.rho = torch.zeros(numel, dtype=torch.int8, device=device)
-        self.grad = torch.zeros(numel, dtype=torch.bfloat16, device=device) if with_grad else None
-        self.m_q = torch.zeros(numel, dtype=torch.int8, device=device)
-        self.m_scale = torch.zeros(ng, dtype=torch.float16, device=device)
-        self.v_q = torch.zeros(numel, dtype=torch.uint8, device=device) if kind == "adamw" else None
-        self.v_scale = torch.zeros(ng, dtype=torch.float16, device=device) if kind == "adamw" else None
+        self.split_weights, self.quantize_states = split_weights, quantize_states
+        z = lambda n, dt: torch.zeros(n, dtype=dt, device=device)
+        self.param = z(numel, torch.bfloat16) if split_weights else None
+        self.rho = z(numel, torch.int8) if split_weights else None
+        self.theta = None if split_weights else z(numel, torch.float32)
+        self.grad = z(numel, torch.bfloat16) if with_grad else None
+        self.m_q = z(numel, torch.int8) if quantize_states else None
+        self.m_scale = z(ng, torch.float16) if quantize_states else None
+        self.v_q = z(numel, torch.uint8) if (quantize_states and has_v) else None
+        self.v_scale = z(ng, torch.float16) if (quantize_states and has_v) else None
+        self.m = None if quantize_states else z(numel, torch.float32)
+        self.v = z(numel, torch.float32) if (not quantize_states and has_v) else None
         self.lr, self.weight_decay = 0.0, 0.0
+
+    @property
+    def flags(self):
+        return (SPLIT_WEIGHTS if self.split_weights else 0) | (QUANTIZE_STATES if self.quantize_states else 0)
 
 
 class TensorList:
@@ -149,6 +171,48 @@ class TensorList:
         out.array = (_Tensor * 1)()
         C.memmove(out.array, C.byref(self.array[i]), C.sizeof(_Tensor))
         return out
+
+
+class TensorListEx:
+    """Host array of flashoptim_tensor_ex descriptors for the ablation entry points."""
+
+    def __init__(self, buffers):
+        self.buffers = list(buffers)
+        self.n = len(self.buffers)
+        self.flags = self.buffers[0].flags if self.buffers else 3
+        assert all(b.flags == self.flags for b in self.buffers)
+        self.array = (_TensorEx * max(self.n, 1))()
+        for i, b in enumerate(self.buffers):
+            d = self.array[i]
+            d.t.param, d.t.rho, d.t.grad = _ptr(b.param), _ptr(b.rho), _ptr(b.grad)
+            d.t.m_q, d.t.m_scale, d.t.v_q, d.t.v_scale = _ptr(b.m_q), _ptr(b.m_scale), _ptr(b.v_q), _ptr(b.v_scale)
+            d.t.numel, d.t.lr, d.t.weight_decay = b.numel, b.lr, b.weight_decay
+            d.theta, d.m, d.v = _ptr(b.theta), _ptr(b.m), _ptr(b.v)
+
+
+def _as_list_ex(tensors):
+    return tensors if isinstance(tensors, TensorListEx) else TensorListEx(tensors)
+
+
+def adamw_step_ex(tensors, beta1, beta2, eps, step, flags=None, stream=None):
+    tl = _as_list_ex(tensors)
+    hp = _AdamWHp(beta1, beta2, eps, int(step))
+    _check(load_library().flashoptim_adamw_step_ex(tl.array, tl.n, C.byref(hp), tl.flags if flags is None else flags,
+                                                   _stream(stream)), "flashoptim_adamw_step_ex")
+
+
+def sgd_step_ex(tensors, momentum, flags=None, stream=None):
+    tl = _as_list_ex(tensors)
+    hp = _SgdHp(momentum)
+    _check(load_library().flashoptim_sgd_step_ex(tl.array, tl.n, C.byref(hp), tl.flags if flags is None else flags,
+                                                 _stream(stream)), "flashoptim_sgd_step_ex")
+
+
+def lion_step_ex(tensors, beta1, beta2, flags=None, stream=None):
+    tl = _as_list_ex(tensors)
+    hp = _LionHp(beta1, beta2)
+    _check(load_library().flashoptim_lion_step_ex(tl.array, tl.n, C.byref(hp), tl.flags if flags is None else flags,
+                                                  _stream(stream)), "flashoptim_lion_step_ex")
 
 
 def _as_list(tensors):

@@ -166,10 +166,105 @@ int validate_tensors(const flashoptim_tensor* t, int64_t n, bool has_v) {
 
 TensorDev to_dev(const flashoptim_tensor& x, bool has_v) {
     TensorDev d;
+    std::memset(&d, 0, sizeof(d));
     d.param = x.param; d.rho = x.rho; d.grad = x.grad; d.m_q = x.m_q; d.m_scale = x.m_scale;
     d.v_q = has_v ? x.v_q : nullptr; d.v_scale = has_v ? x.v_scale : nullptr;
     d.numel = x.numel; d.lr = x.lr; d.wd = x.weight_decay;
     return d;
+}
+
+// Validation and conversion of the extended descriptors of the ablation entry points: only the
+// buffers that the chosen variant uses are required (and passed on).
+int to_dev_ex(const flashoptim_tensor_ex* t, int64_t n, bool has_v, bool split, bool quant,
+              std::vector<TensorDev>& live) {
+    if (n < 0 || (n > 0 && t == nullptr)) return FLASHOPTIM_ERR_INVALID_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        const flashoptim_tensor_ex& x = t[i];
+        if (x.t.numel < 0 || x.t.numel >= kMaxNumel) return FLASHOPTIM_ERR_NUMEL_RANGE;
+        if (x.t.numel == 0) continue;
+        const void* need[8];
+        int k = 0;
+        need[k++] = x.t.grad;
+        if (split) { need[k++] = x.t.param; need[k++] = x.t.rho; } else need[k++] = x.theta;
+        if (quant) {
+            need[k++] = x.t.m_q; need[k++] = x.t.m_scale;
+            if (has_v) { need[k++] = x.t.v_q; need[k++] = x.t.v_scale; }
+        } else {
+            need[k++] = x.m;
+            if (has_v) need[k++] = x.v;
+        }
+        for (int j = 0; j < k; ++j) if (!need[j]) return FLASHOPTIM_ERR_INVALID_ARG;
+        for (int j = 0; j < k; ++j) if (!aligned16(need[j])) return FLASHOPTIM_ERR_MISALIGNED;
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        const flashoptim_tensor_ex& x = t[i];
+        if (x.t.numel == 0) continue;
+        TensorDev d;
+        std::memset(&d, 0, sizeof(d));
+        d.grad = x.t.grad; d.numel = x.t.numel; d.lr = x.t.lr; d.wd = x.t.weight_decay;
+        if (split) { d.param = x.t.param; d.rho = x.t.rho; } else d.theta32 = x.theta;
+        if (quant) {
+            d.m_q = x.t.m_q; d.m_scale = x.t.m_scale;
+            if (has_v) { d.v_q = x.t.v_q; d.v_scale = x.t.v_scale; }
+        } else {
+            d.m32 = x.m;
+            if (has_v) d.v32 = x.v;
+        }
+        live.push_back(d);
+    }
+    return FLASHOPTIM_OK;
+}
+
+// Launches one step over the live tensors (already validated and converted).
+int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, const StepConsts& c,
+                hipStream_t stream) {
+    if (live.empty()) return FLASHOPTIM_OK;
+    StepArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.c = c;
+    const int64_t ce = fo::chunk_elems(kind);
+
+    if (live.size() == 1) {
+        // gradient-release call: no table, no allocation, no lock
+        a.single = live[0];
+        const int64_t blocks = (live[0].numel + ce - 1) / ce;
+        FO_HIP(fo::launch_step(kind, true, split, quant, a, blocks, stream));
+        return FLASHOPTIM_OK;
+    }
+
+    int device = 0;
+    FO_HIP(hipGetDevice(&device));
+    std::string key;
+    key.reserve(16 + live.size() * 80);
+    const int32_t tag[4] = {kind, device, (int32_t)split, (int32_t)quant};
+    append(key, tag, sizeof(tag));
+    for (const TensorDev& d : live) {
+        const void* ids[9] = {d.param, d.rho, d.m_q, d.m_scale, d.v_q, d.v_scale, d.theta32, d.m32, d.v32};
+        append(key, ids, sizeof(ids));
+        append(key, &d.numel, sizeof(d.numel));
+    }
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    Plan* plan = nullptr;
+    std::vector<uint2> chunks;
+    if (g_index.find(key) == g_index.end()) {
+        for (size_t ti = 0; ti < live.size(); ++ti) {
+            const int64_t nc = (live[ti].numel + ce - 1) / ce;
+            for (int64_t ci = 0; ci < nc; ++ci) chunks.push_back(make_uint2((unsigned)ti, (unsigned)ci));
+        }
+    }
+    int rc = get_plan(key, live.size() * sizeof(TensorDev), chunks, &plan);
+    if (rc != FLASHOPTIM_OK) return rc;
+
+    const size_t bytes = live.size() * sizeof(TensorDev);
+    if (plan->uploaded.size() != bytes || std::memcmp(plan->uploaded.data(), live.data(), bytes) != 0) {
+        rc = upload_table(*plan, live.data(), bytes, stream);
+        if (rc != FLASHOPTIM_OK) return rc;
+    }
+    a.tensors = static_cast<const TensorDev*>(plan->d_table);
+    a.chunks = plan->d_chunks;
+    FO_HIP(fo::launch_step(kind, false, split, quant, a, plan->n_chunks, stream));
+    return FLASHOPTIM_OK;
 }
 
 int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, const StepConsts& c, void* stream_) {
@@ -181,62 +276,21 @@ int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, cons
         if (!tensors[i].grad) return FLASHOPTIM_ERR_INVALID_ARG;
         if (!aligned16(tensors[i].grad)) return FLASHOPTIM_ERR_MISALIGNED;
     }
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
-
-    // live tensors only
     std::vector<TensorDev> live;
     live.reserve((size_t)n_tensors);
     for (int64_t i = 0; i < n_tensors; ++i)
         if (tensors[i].numel > 0) live.push_back(to_dev(tensors[i], has_v));
-    if (live.empty()) return FLASHOPTIM_OK;
+    return launch_live(kind, true, true, live, c, static_cast<hipStream_t>(stream_));
+}
 
-    StepArgs a;
-    std::memset(&a, 0, sizeof(a));
-    a.c = c;
-
-    if (live.size() == 1) {
-        // gradient-release call: no table, no allocation, no lock
-        a.single = live[0];
-        const int64_t ce = fo::chunk_elems(kind);
-        const int64_t blocks = (live[0].numel + ce - 1) / ce;
-        FO_HIP(fo::launch_step(kind, true, a, blocks, stream));
-        return FLASHOPTIM_OK;
-    }
-
-    int device = 0;
-    FO_HIP(hipGetDevice(&device));
-    std::string key;
-    key.reserve(16 + live.size() * 56);
-    const int32_t tag[2] = {kind, device};
-    append(key, tag, sizeof(tag));
-    for (const TensorDev& d : live) {
-        const void* ids[6] = {d.param, d.rho, d.m_q, d.m_scale, d.v_q, d.v_scale};
-        append(key, ids, sizeof(ids));
-        append(key, &d.numel, sizeof(d.numel));
-    }
-
-    std::lock_guard<std::mutex> lock(g_mu);
-    Plan* plan = nullptr;
-    std::vector<uint2> chunks;
-    if (g_index.find(key) == g_index.end()) {
-        for (size_t ti = 0; ti < live.size(); ++ti) {
-            const int64_t ce = fo::chunk_elems(kind);
-            const int64_t nc = (live[ti].numel + ce - 1) / ce;
-            for (int64_t ci = 0; ci < nc; ++ci) chunks.push_back(make_uint2((unsigned)ti, (unsigned)ci));
-        }
-    }
-    rc = get_plan(key, live.size() * sizeof(TensorDev), chunks, &plan);
+int run_step_ex(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors, const StepConsts& c,
+                unsigned flags, void* stream_) {
+    if (flags & ~(unsigned)(FLASHOPTIM_SPLIT_WEIGHTS | FLASHOPTIM_QUANTIZE_STATES)) return FLASHOPTIM_ERR_INVALID_ARG;
+    const bool split = (flags & FLASHOPTIM_SPLIT_WEIGHTS) != 0, quant = (flags & FLASHOPTIM_QUANTIZE_STATES) != 0;
+    std::vector<TensorDev> live;
+    int rc = to_dev_ex(tensors, n_tensors, kind == FLASHOPTIM_ADAMW, split, quant, live);
     if (rc != FLASHOPTIM_OK) return rc;
-
-    const size_t bytes = live.size() * sizeof(TensorDev);
-    if (plan->uploaded.size() != bytes || std::memcmp(plan->uploaded.data(), live.data(), bytes) != 0) {
-        rc = upload_table(*plan, live.data(), bytes, stream);
-        if (rc != FLASHOPTIM_OK) return rc;
-    }
-    a.tensors = static_cast<const TensorDev*>(plan->d_table);
-    a.chunks = plan->d_chunks;
-    FO_HIP(fo::launch_step(kind, false, a, plan->n_chunks, stream));
-    return FLASHOPTIM_OK;
+    return launch_live(kind, split, quant, live, c, static_cast<hipStream_t>(stream_));
 }
 
 // 1 / (float)(1 - beta^t): the bias correction is formed in double and rounded to FP32
@@ -337,10 +391,8 @@ int check_elementwise(const void* a, const void* b, const void* c, int64_t n) {
 
 extern "C" {
 
-int flashoptim_adamw_step(const flashoptim_tensor* tensors, int64_t n_tensors, const flashoptim_adamw_hp* hp,
-                          void* stream) {
-    if (!hp || hp->step < 1) return FLASHOPTIM_ERR_INVALID_ARG;
-    StepConsts c;
+static bool adamw_consts(const flashoptim_adamw_hp* hp, StepConsts& c) {
+    if (!hp || hp->step < 1) return false;
     std::memset(&c, 0, sizeof(c));
     c.beta1 = hp->beta1; c.beta2 = hp->beta2;
     c.omb1 = 1.0f - hp->beta1; c.omb2 = 1.0f - hp->beta2;
@@ -348,26 +400,62 @@ int flashoptim_adamw_step(const flashoptim_tensor* tensors, int64_t n_tensors, c
     c.rbc2 = recip_bias_correction(hp->beta2, hp->step);
     c.eps = hp->eps;
     c.root_bc2 = (float)std::sqrt(1.0 / (double)c.rbc2);
+    return true;
+}
+static bool sgd_consts(const flashoptim_sgd_hp* hp, StepConsts& c) {
+    if (!hp) return false;
+    std::memset(&c, 0, sizeof(c));
+    c.beta1 = hp->momentum;
+    return true;
+}
+static bool lion_consts(const flashoptim_lion_hp* hp, StepConsts& c) {
+    if (!hp) return false;
+    std::memset(&c, 0, sizeof(c));
+    c.beta1 = hp->beta1; c.beta2 = hp->beta2;
+    c.omb1 = 1.0f - hp->beta1; c.omb2 = 1.0f - hp->beta2;
+    return true;
+}
+
+int flashoptim_adamw_step(const flashoptim_tensor* tensors, int64_t n_tensors, const flashoptim_adamw_hp* hp,
+                          void* stream) {
+    StepConsts c;
+    if (!adamw_consts(hp, c)) return FLASHOPTIM_ERR_INVALID_ARG;
     return run_step(FLASHOPTIM_ADAMW, tensors, n_tensors, c, stream);
 }
 
 int flashoptim_sgd_step(const flashoptim_tensor* tensors, int64_t n_tensors, const flashoptim_sgd_hp* hp,
                         void* stream) {
-    if (!hp) return FLASHOPTIM_ERR_INVALID_ARG;
     StepConsts c;
-    std::memset(&c, 0, sizeof(c));
-    c.beta1 = hp->momentum;
+    if (!sgd_consts(hp, c)) return FLASHOPTIM_ERR_INVALID_ARG;
     return run_step(FLASHOPTIM_SGD, tensors, n_tensors, c, stream);
 }
 
 int flashoptim_lion_step(const flashoptim_tensor* tensors, int64_t n_tensors, const flashoptim_lion_hp* hp,
                          void* stream) {
-    if (!hp) return FLASHOPTIM_ERR_INVALID_ARG;
     StepConsts c;
-    std::memset(&c, 0, sizeof(c));
-    c.beta1 = hp->beta1; c.beta2 = hp->beta2;
-    c.omb1 = 1.0f - hp->beta1; c.omb2 = 1.0f - hp->beta2;
+    if (!lion_consts(hp, c)) return FLASHOPTIM_ERR_INVALID_ARG;
     return run_step(FLASHOPTIM_LION, tensors, n_tensors, c, stream);
+}
+
+int flashoptim_adamw_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tensors, const flashoptim_adamw_hp* hp,
+                             unsigned flags, void* stream) {
+    StepConsts c;
+    if (!adamw_consts(hp, c)) return FLASHOPTIM_ERR_INVALID_ARG;
+    return run_step_ex(FLASHOPTIM_ADAMW, tensors, n_tensors, c, flags, stream);
+}
+
+int flashoptim_sgd_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tensors, const flashoptim_sgd_hp* hp,
+                           unsigned flags, void* stream) {
+    StepConsts c;
+    if (!sgd_consts(hp, c)) return FLASHOPTIM_ERR_INVALID_ARG;
+    return run_step_ex(FLASHOPTIM_SGD, tensors, n_tensors, c, flags, stream);
+}
+
+int flashoptim_lion_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tensors, const flashoptim_lion_hp* hp,
+                            unsigned flags, void* stream) {
+    StepConsts c;
+    if (!lion_consts(hp, c)) return FLASHOPTIM_ERR_INVALID_ARG;
+    return run_step_ex(FLASHOPTIM_LION, tensors, n_tensors, c, flags, stream);
 }
 
 int flashoptim_split_weights(const float* theta, void* param_bf16, int8_t* rho, int64_t n, void* stream) {

@@ -37,7 +37,7 @@ constexpr int step_tiles(int kind) { return kind == 0 ? FO_TILES_ADAMW : FO_TILE
 constexpr int chunk_elems(int kind) { return step_threads(kind) * step_vec(kind) * step_tiles(kind); }
 constexpr int kCopyChunkBytes = 64 * 1024;         // checkpoint copy: bytes per workgroup
 
-// One tensor as the kernels see it (device pointers), 72 bytes.
+// One tensor as the kernels see it (device pointers), 96 bytes.
 struct TensorDev {
     void* param;
     int8_t* rho;
@@ -46,6 +46,9 @@ struct TensorDev {
     uint16_t* m_scale;
     uint8_t* v_q;
     uint16_t* v_scale;
+    float* theta32;   // ablation variants: FP32 master weight (weights not split)
+    float* m32;       // ablation variants: FP32 momentum (states not quantized)
+    float* v32;       // ablation variants: FP32 variance
     int64_t numel;
     float lr, wd;
 };
@@ -73,7 +76,8 @@ struct CopySegment {
     int64_t pad_bytes;   // >= bytes; [bytes, pad_bytes) of dst is zero-filled
 };
 
-hipError_t launch_step(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s);
+hipError_t launch_step(int kind, bool direct, bool split, bool quant, const StepArgs& a, int64_t n_blocks,
+                       hipStream_t s);
 void launch_split(int bits, const float* theta, void* param, void* rho, int64_t n, hipStream_t s);
 void launch_reconstruct(int bits, const void* param, const void* rho, float* theta, int64_t n, hipStream_t s);
 constexpr int kSweepStats = 8 + 2 * 256;

@@ -297,7 +297,26 @@ struct LaneIO {
     uint32_t mq[VEC / 4];   // VEC INT8 momentum codes
     uint32_t vq[VEC / 4];   // VEC UINT8 variance codes
     uint32_t ms, vs;        // FP16 scale bits of the lane's group
+    // uncompressed halves (ablation variants only; dead otherwise)
+    float th32[VEC];        // FP32 master weights when weights are not split
+    float m32[VEC];         // FP32 momentum when states are not quantized
+    float v32[VEC];         // FP32 variance when states are not quantized
 };
+
+// VEC floats from / to a 16-byte aligned address
+template <int VEC>
+__device__ __forceinline__ void ld_floats(float (&f)[VEC], const float* p) {
+#pragma unroll
+    for (int k = 0; k < VEC / 4; ++k) {
+        const uint4 a = ld128(p + 4 * k);
+        f[4 * k] = u2f(a.x); f[4 * k + 1] = u2f(a.y); f[4 * k + 2] = u2f(a.z); f[4 * k + 3] = u2f(a.w);
+    }
+}
+template <int VEC>
+__device__ __forceinline__ void st_floats(float* p, const float (&f)[VEC]) {
+#pragma unroll
+    for (int k = 0; k < VEC / 4; ++k) st128(p + 4 * k, f2u(f[4 * k]), f2u(f[4 * k + 1]), f2u(f[4 * k + 2]), f2u(f[4 * k + 3]));
+}
 
 // 4 * N bytes from / to a 4N-byte aligned address
 template <int N>
@@ -335,22 +354,31 @@ __device__ __forceinline__ void st_words(void* p, const uint32_t (&w)[N]) {
     }
 }
 
-template <int VEC, bool HAS_V>
+template <int VEC, bool HAS_V, bool SPLIT, bool QUANT>
 __device__ __forceinline__ void load_full(LaneIO<VEC>& x, const TensorDev& T, int64_t off) {
-    ld_words(x.p, reinterpret_cast<const uint16_t*>(T.param) + off);
+    if (SPLIT) {
+        ld_words(x.p, reinterpret_cast<const uint16_t*>(T.param) + off);
+        ld_words(x.r, T.rho + off);
+    } else {
+        ld_floats(x.th32, T.theta32 + off);
+    }
     ld_words(x.g, reinterpret_cast<const uint16_t*>(T.grad) + off);
-    ld_words(x.r, T.rho + off);
-    ld_words(x.mq, T.m_q + off);
-    x.ms = T.m_scale[off >> 5];
-    if (HAS_V) {
-        ld_words(x.vq, T.v_q + off);
-        x.vs = T.v_scale[off >> 5];
+    if (QUANT) {
+        ld_words(x.mq, T.m_q + off);
+        x.ms = T.m_scale[off >> 5];
+        if (HAS_V) {
+            ld_words(x.vq, T.v_q + off);
+            x.vs = T.v_scale[off >> 5];
+        }
+    } else {
+        ld_floats(x.m32, T.m32 + off);
+        if (HAS_V) ld_floats(x.v32, T.v32 + off);
     }
 }
 
 // Ragged end of a tensor: element-wise loads, missing elements read as zero (a zero
 // element yields zero moments and therefore never raises its group's absmax).
-template <int VEC, bool HAS_V>
+template <int VEC, bool HAS_V, bool SPLIT, bool QUANT>
 __device__ __forceinline__ void load_tail(LaneIO<VEC>& x, const TensorDev& T, int64_t off, int cnt) {
     const uint16_t* p = reinterpret_cast<const uint16_t*>(T.param) + off;
     const uint16_t* g = reinterpret_cast<const uint16_t*>(T.grad) + off;
@@ -359,10 +387,12 @@ __device__ __forceinline__ void load_tail(LaneIO<VEC>& x, const TensorDev& T, in
     const uint8_t* vq = T.v_q + off;
 #pragma unroll
     for (int j = 0; j < VEC / 2; ++j) {
-        uint32_t lo = (2 * j < cnt) ? p[2 * j] : 0u, hi = (2 * j + 1 < cnt) ? p[2 * j + 1] : 0u;
-        x.p[j] = lo | (hi << 16);
-        lo = (2 * j < cnt) ? g[2 * j] : 0u; hi = (2 * j + 1 < cnt) ? g[2 * j + 1] : 0u;
+        uint32_t lo = (2 * j < cnt) ? g[2 * j] : 0u, hi = (2 * j + 1 < cnt) ? g[2 * j + 1] : 0u;
         x.g[j] = lo | (hi << 16);
+        if (SPLIT) {
+            lo = (2 * j < cnt) ? p[2 * j] : 0u; hi = (2 * j + 1 < cnt) ? p[2 * j + 1] : 0u;
+            x.p[j] = lo | (hi << 16);
+        }
     }
 #pragma unroll
     for (int j = 0; j < VEC / 4; ++j) {
@@ -370,34 +400,49 @@ __device__ __forceinline__ void load_tail(LaneIO<VEC>& x, const TensorDev& T, in
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             if (4 * j + k < cnt) {
-                w |= (uint32_t)r[4 * j + k] << (8 * k);
-                wm |= (uint32_t)mq[4 * j + k] << (8 * k);
-                if (HAS_V) wv |= (uint32_t)vq[4 * j + k] << (8 * k);
+                if (SPLIT) w |= (uint32_t)r[4 * j + k] << (8 * k);
+                if (QUANT) wm |= (uint32_t)mq[4 * j + k] << (8 * k);
+                if (QUANT && HAS_V) wv |= (uint32_t)vq[4 * j + k] << (8 * k);
             }
         }
         x.r[j] = w; x.mq[j] = wm; x.vq[j] = wv;
     }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        if (!SPLIT) x.th32[i] = (i < cnt) ? T.theta32[off + i] : 0.0f;
+        if (!QUANT) x.m32[i] = (i < cnt) ? T.m32[off + i] : 0.0f;
+        if (!QUANT && HAS_V) x.v32[i] = (i < cnt) ? T.v32[off + i] : 0.0f;
+    }
     x.ms = 0; x.vs = 0;
-    if (cnt > 0) {
+    if (QUANT && cnt > 0) {
         x.ms = T.m_scale[off >> 5];
         if (HAS_V) x.vs = T.v_scale[off >> 5];
     }
 }
 
-template <int VEC, bool HAS_V>
+template <int VEC, bool HAS_V, bool SPLIT, bool QUANT>
 __device__ __forceinline__ void store_full(const LaneIO<VEC>& y, const TensorDev& T, int64_t off,
                                            bool group_leader) {
-    st_words(reinterpret_cast<uint16_t*>(T.param) + off, y.p);
-    st_words(T.rho + off, y.r);
-    st_words(T.m_q + off, y.mq);
-    if (HAS_V) st_words(T.v_q + off, y.vq);
-    if (group_leader) {
-        T.m_scale[off >> 5] = (uint16_t)y.ms;
-        if (HAS_V) T.v_scale[off >> 5] = (uint16_t)y.vs;
+    if (SPLIT) {
+        st_words(reinterpret_cast<uint16_t*>(T.param) + off, y.p);
+        st_words(T.rho + off, y.r);
+    } else {
+        st_floats(T.theta32 + off, y.th32);
+    }
+    if (QUANT) {
+        st_words(T.m_q + off, y.mq);
+        if (HAS_V) st_words(T.v_q + off, y.vq);
+        if (group_leader) {
+            T.m_scale[off >> 5] = (uint16_t)y.ms;
+            if (HAS_V) T.v_scale[off >> 5] = (uint16_t)y.vs;
+        }
+    } else {
+        st_floats(T.m32 + off, y.m32);
+        if (HAS_V) st_floats(T.v32 + off, y.v32);
     }
 }
 
-template <int VEC, bool HAS_V>
+template <int VEC, bool HAS_V, bool SPLIT, bool QUANT>
 __device__ __forceinline__ void store_tail(const LaneIO<VEC>& y, const TensorDev& T, int64_t off, int cnt,
                                            bool group_leader) {
     uint16_t* p = reinterpret_cast<uint16_t*>(T.param) + off;
@@ -407,13 +452,22 @@ __device__ __forceinline__ void store_tail(const LaneIO<VEC>& y, const TensorDev
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
         if (i < cnt) {
-            p[i] = (uint16_t)(y.p[i >> 1] >> (16 * (i & 1)));
-            r[i] = (uint8_t)(y.r[i >> 2] >> (8 * (i & 3)));
-            mq[i] = (uint8_t)(y.mq[i >> 2] >> (8 * (i & 3)));
-            if (HAS_V) vq[i] = (uint8_t)(y.vq[i >> 2] >> (8 * (i & 3)));
+            if (SPLIT) {
+                p[i] = (uint16_t)(y.p[i >> 1] >> (16 * (i & 1)));
+                r[i] = (uint8_t)(y.r[i >> 2] >> (8 * (i & 3)));
+            } else {
+                T.theta32[off + i] = y.th32[i];
+            }
+            if (QUANT) {
+                mq[i] = (uint8_t)(y.mq[i >> 2] >> (8 * (i & 3)));
+                if (HAS_V) vq[i] = (uint8_t)(y.vq[i >> 2] >> (8 * (i & 3)));
+            } else {
+                T.m32[off + i] = y.m32[i];
+                if (HAS_V) T.v32[off + i] = y.v32[i];
+            }
         }
     }
-    if (group_leader && cnt > 0) {
+    if (QUANT && group_leader && cnt > 0) {
         T.m_scale[off >> 5] = (uint16_t)y.ms;
         if (HAS_V) T.v_scale[off >> 5] = (uint16_t)y.vs;
     }
@@ -424,12 +478,14 @@ __device__ __forceinline__ void store_tail(const LaneIO<VEC>& y, const TensorDev
 // KIND: 0 AdamW (Algorithm 4), 1 SGD (Algorithm 5), 2 Lion (Algorithm 6).
 // Operates on the VEC elements of one lane; the lanes holding the rest of the same 32-element
 // group (lane ^ 1, and lane ^ 2, lane ^ 3 when VEC == 8) must execute this function with it.
-template <int KIND, int VEC>
+// SPLIT / QUANT: the paper's ablations (Section 4.3).  SPLIT = false keeps the master weight in
+// FP32 (x.th32 -> y.th32); QUANT = false keeps the states in FP32 (x.m32, x.v32 -> y.m32, y.v32).
+template <int KIND, int VEC, bool SPLIT, bool QUANT>
 __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y, const DecodeTables& tab,
                                             const StepConsts& c, float lr, float wd) {
     constexpr bool HAS_V = (KIND == 0);
-    const float s_m = (float)__builtin_bit_cast(_Float16, (uint16_t)x.ms);
-    const float s_v = HAS_V ? (float)__builtin_bit_cast(_Float16, (uint16_t)x.vs) : 0.0f;
+    const float s_m = QUANT ? (float)__builtin_bit_cast(_Float16, (uint16_t)x.ms) : 0.0f;
+    const float s_v = (QUANT && HAS_V) ? (float)__builtin_bit_cast(_Float16, (uint16_t)x.vs) : 0.0f;
 
     float mt[VEC];    // new momentum
     float vt[VEC];    // new variance (AdamW)
@@ -445,21 +501,36 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int i = 4 * j + k;
-            const uint32_t pw = x.p[i >> 1], gw = x.g[i >> 1];
-            // (pair << 1) puts the two exponent fields on byte boundaries (bytes 1 and 3)
-            const uint32_t pE = (i & 1) ? ((pw << 1) >> 24) : (((pw << 1) >> 8) & 0xffu);
-            const float base = (i & 1) ? u2f(pw & 0xffff0000u) : u2f(pw << 16);
+            const uint32_t gw = x.g[i >> 1];
             const float g = (i & 1) ? u2f(gw & 0xffff0000u) : u2f(gw << 16);
-            const uint32_t rb = (x.r[j] >> (8 * k)) & 0xffu;
-            const uint32_t mb = (x.mq[j] >> (8 * k)) & 0xffu;
             // prologue: reconstruct optimizer state and master weight
-            const float m = tab.m[mb] * s_m;                         // Q_m^-1
-            const float th = reconstruct_lds(tab, pE, base, tab.rho[rb]);    // C^-1
+            float m, th;
+            if (QUANT) {
+                const uint32_t mb = (x.mq[j] >> (8 * k)) & 0xffu;
+                m = tab.m[mb] * s_m;                                 // Q_m^-1
+            } else {
+                m = x.m32[i];
+            }
+            if (SPLIT) {
+                const uint32_t pw = x.p[i >> 1];
+                // (pair << 1) puts the two exponent fields on byte boundaries (bytes 1 and 3)
+                const uint32_t pE = (i & 1) ? ((pw << 1) >> 24) : (((pw << 1) >> 8) & 0xffu);
+                const float base = (i & 1) ? u2f(pw & 0xffff0000u) : u2f(pw << 16);
+                const uint32_t rb = (x.r[j] >> (8 * k)) & 0xffu;
+                th = reconstruct_lds(tab, pE, base, tab.rho[rb]);    // C^-1
+            } else {
+                th = x.th32[i];
+            }
             float m_new;
             if (KIND == 0) {
-                const uint32_t vb = (x.vq[j] >> (8 * k)) & 0xffu;
-                const float v1 = tab.v[vb] * s_v;                    // Q_v^-1
-                const float v = v1 * v1;
+                float v;
+                if (QUANT) {
+                    const uint32_t vb = (x.vq[j] >> (8 * k)) & 0xffu;
+                    const float v1 = tab.v[vb] * s_v;                // Q_v^-1
+                    v = v1 * v1;
+                } else {
+                    v = x.v32[i];
+                }
                 m_new = (c.beta1 * m) + (c.omb1 * g);
                 const float gg = g * g;
                 const float v_new = (c.beta2 * v) + (c.omb2 * gg);
@@ -500,14 +571,27 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
             }
         }
         // epilogue, part 1: split the new master weights of this block
-        const uint32_t w0 = bf16_pack(tht[0], tht[1]), w1 = bf16_pack(tht[2], tht[3]);
-        y.p[2 * j] = w0;
-        y.p[2 * j + 1] = w1;
-        const uint32_t e0 = w0 << 1, e1 = w1 << 1;     // exponent fields on byte boundaries
-        y.r[j] = pack_low_bytes(rho_bits_lds(tab, tht[0], w0 & 0xffffu, (e0 >> 8) & 0xffu),
-                                rho_bits_lds(tab, tht[1], w0 >> 16, e0 >> 24),
-                                rho_bits_lds(tab, tht[2], w1 & 0xffffu, (e1 >> 8) & 0xffu),
-                                rho_bits_lds(tab, tht[3], w1 >> 16, e1 >> 24));
+        if (SPLIT) {
+            const uint32_t w0 = bf16_pack(tht[0], tht[1]), w1 = bf16_pack(tht[2], tht[3]);
+            y.p[2 * j] = w0;
+            y.p[2 * j + 1] = w1;
+            const uint32_t e0 = w0 << 1, e1 = w1 << 1;     // exponent fields on byte boundaries
+            y.r[j] = pack_low_bytes(rho_bits_lds(tab, tht[0], w0 & 0xffffu, (e0 >> 8) & 0xffu),
+                                    rho_bits_lds(tab, tht[1], w0 >> 16, e0 >> 24),
+                                    rho_bits_lds(tab, tht[2], w1 & 0xffffu, (e1 >> 8) & 0xffu),
+                                    rho_bits_lds(tab, tht[3], w1 >> 16, e1 >> 24));
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) y.th32[4 * j + k] = tht[k];
+        }
+    }
+    if (!QUANT) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            y.m32[i] = mt[i];
+            if (HAS_V) y.v32[i] = vt[i];
+        }
+        return;
     }
 
     // epilogue, part 2: group scales (one DPP swap joins the two lanes of a group).  The square root
@@ -558,7 +642,7 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
 
 // ------------------------------------------------------------ step kernels --
 
-template <int KIND, int VEC, int THREADS, int TILES, bool DIRECT>
+template <int KIND, int VEC, int THREADS, int TILES, bool DIRECT, bool SPLIT, bool QUANT>
 __global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
     constexpr bool HAS_V = (KIND == 0);
     constexpr int kTile = THREADS * VEC;       // elements per pass of the workgroup
@@ -586,42 +670,52 @@ __global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
     int64_t left = T.numel - off;
     int cnt = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
     LaneIO<VEC> x, y;
-    if (cnt == VEC) load_full<VEC, HAS_V>(x, T, off);
-    else load_tail<VEC, HAS_V>(x, T, off, cnt);
+    if (cnt == VEC) load_full<VEC, HAS_V, SPLIT, QUANT>(x, T, off);
+    else load_tail<VEC, HAS_V, SPLIT, QUANT>(x, T, off, cnt);
     fill_tables<THREADS>(tab, tid);
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < TILES; ++t) {
         // All lanes of a group run the update together (a lane with cnt == 0 may share its group
         // with lanes that hold elements); lanes past the end compute on zeros and store nothing.
-        update_lane<KIND, VEC>(x, y, tab, a.c, T.lr, T.wd);
+        update_lane<KIND, VEC, SPLIT, QUANT>(x, y, tab, a.c, T.lr, T.wd);
         const int64_t off_done = off;
         const int cnt_done = cnt;
         if (t + 1 < TILES) {
             off += kTile;
             left = T.numel - off;
             cnt = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
-            if (cnt == VEC) load_full<VEC, HAS_V>(x, T, off);
-            else load_tail<VEC, HAS_V>(x, T, off, cnt);
+            if (cnt == VEC) load_full<VEC, HAS_V, SPLIT, QUANT>(x, T, off);
+            else load_tail<VEC, HAS_V, SPLIT, QUANT>(x, T, off, cnt);
         }
-        if (cnt_done == VEC) store_full<VEC, HAS_V>(y, T, off_done, leader);
-        else store_tail<VEC, HAS_V>(y, T, off_done, cnt_done, leader);
+        if (cnt_done == VEC) store_full<VEC, HAS_V, SPLIT, QUANT>(y, T, off_done, leader);
+        else store_tail<VEC, HAS_V, SPLIT, QUANT>(y, T, off_done, cnt_done, leader);
     }
 }
 
-template <int KIND>
-static hipError_t launch_kind(bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
+template <int KIND, bool SPLIT, bool QUANT>
+static hipError_t launch_variant(bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
     constexpr int VEC = step_vec(KIND), THREADS = step_threads(KIND), TILES = step_tiles(KIND);
     const dim3 grid((unsigned)n_blocks), block(THREADS);
-    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, TILES, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, TILES, false>), grid, block, 0, s, a);
+    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, TILES, true, SPLIT, QUANT>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, TILES, false, SPLIT, QUANT>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
-hipError_t launch_step(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
-    if (kind == 0) return launch_kind<0>(direct, a, n_blocks, s);
-    if (kind == 1) return launch_kind<1>(direct, a, n_blocks, s);
-    return launch_kind<2>(direct, a, n_blocks, s);
+template <int KIND>
+static hipError_t launch_kind(bool direct, bool split, bool quant, const StepArgs& a, int64_t n_blocks,
+                              hipStream_t s) {
+    if (split && quant) return launch_variant<KIND, true, true>(direct, a, n_blocks, s);
+    if (split) return launch_variant<KIND, true, false>(direct, a, n_blocks, s);
+    if (quant) return launch_variant<KIND, false, true>(direct, a, n_blocks, s);
+    return launch_variant<KIND, false, false>(direct, a, n_blocks, s);
+}
+
+hipError_t launch_step(int kind, bool direct, bool split, bool quant, const StepArgs& a, int64_t n_blocks,
+                       hipStream_t s) {
+    if (kind == 0) return launch_kind<0>(direct, split, quant, a, n_blocks, s);
+    if (kind == 1) return launch_kind<1>(direct, split, quant, a, n_blocks, s);
+    return launch_kind<2>(direct, split, quant, a, n_blocks, s);
 }
 
 // -------------------------------------------------------- standalone codecs --
