@@ -20,7 +20,7 @@
  *    elements [32k, 32k+32) of that sequence, the last group may be short, and groups
  *    never span tensors.  A scale array holds ceil(numel/32) FP16 bit patterns.
  *  - All-zero m_q/m_scale/v_q/v_scale buffers are the initial state Q_m(0), Q_v(0)
- *    (Algorithm 4, lines 1-2): a zero scale decodes to exactly zero.
+ *    (the initialisation of Algorithm 4): a zero scale decodes to exactly zero.
  *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
  *    stream) and the call returns without waiting.  Buffers may be reused or freed
  *    by the caller in stream order.
@@ -91,10 +91,10 @@ typedef struct flashoptim_lion_hp { float beta1, beta2; } flashoptim_lion_hp;
  * needs no table and no device allocation.  The grad pointers are not part of the
  * cached identity of a list, so gradients may live in different buffers each step.
  *
- * flashoptim_adamw_step: Algorithm 4, lines 9-22 (reconstruct m, v, theta; AdamW
+ * flashoptim_adamw_step: Algorithm 4, the body of the loop after the gradient (reconstruct m, v, theta; AdamW
  *   update with bias correction and decoupled weight decay; quantize m, v; split theta).
- * flashoptim_sgd_step:   Algorithm 5, lines 8-13 (m <- mu m + g; theta <- theta - eta (m + lambda theta)).
- * flashoptim_lion_step:  Algorithm 6, lines 8-14 (u = sign(b1 m + (1-b1) g); m <- b2 m + (1-b2) g;
+ * flashoptim_sgd_step:   Algorithm 5, loop body (m <- mu m + g; theta <- theta - eta (m + lambda theta)).
+ * flashoptim_lion_step:  Algorithm 6, loop body (u = sign(b1 m + (1-b1) g); m <- b2 m + (1-b2) g;
  *   theta <- theta - eta (u + lambda theta)); sign(0) = 0.
  * tensors: host array of n_tensors descriptors (n_tensors >= 0). */
 int flashoptim_adamw_step(const flashoptim_tensor* tensors, int64_t n_tensors,
@@ -133,7 +133,7 @@ int flashoptim_lion_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tenso
 
 /* ---- weight splitting (Section 3.1, Algorithm 1, N = 127) --------------------------
  * split:       theta (FP32) -> theta' = BF16 round-to-nearest-even, rho = Round(e / (ULP(theta')/2) * 127)
- *              Used once at the start of training (Algorithm 4, line 3).
+ *              Used once at the start of training (initialisation of Algorithm 4).
  * reconstruct: theta_hat = theta' + (rho/127) * ULP(theta')/2   (Eq. 2)
  * n >= 0 elements; all pointers device memory. */
 int flashoptim_split_weights(const float* theta, void* param_bf16, int8_t* rho, int64_t n, void* stream);

@@ -155,7 +155,7 @@ __device__ __forceinline__ float sqrt_rn_midrange(float x) {
 }
 
 // Exact Q_m code (low byte of the result) of one element given the reciprocal group scale
-// (Algorithm 2, lines 4-6).
+// (Algorithm 2, encoder).
 __device__ __forceinline__ uint32_t m_code_exact(float m, float r) {
     const float m1 = m * r;
     const float num = 2.0f * m1;
@@ -180,7 +180,7 @@ __device__ __forceinline__ uint32_t m_code_fast(float m, float r, float* resid) 
     return f2u(t);
 }
 
-// Exact Q_v code of one element from v and the reciprocal group scale (Algorithm 3, lines 2, 5).
+// Exact Q_v code of one element from v and the reciprocal group scale (Algorithm 3, encoder).
 __device__ __forceinline__ uint32_t v_code_exact(float v, float r) {
     const float y = __builtin_amdgcn_fmed3f((sqrtf(v) * r) * 255.0f, 0.0f, 255.0f);
     return round_to_int_bits(y);
@@ -214,7 +214,7 @@ struct DecodeTables {
     float m[256];      // phi_m^-1((float)(int8)i / 127)
     float v[256];      // (float)i / 255
     float half_ulp[256];   // 2^l, l = max(E,1) - 135: half the BF16 ULP of a value with exponent field E
-    float2 split[256];     // {2^h, 127 * 2^(-l-h)}, h = floor(-l/2): the two scalings of Algorithm 1, line 5
+    float2 split[256];     // {2^h, 127 * 2^(-l-h)}, h = floor(-l/2): the two scalings of Algorithm 1's encoder
 };
 
 constexpr float pow2_const(int k) {     // 2^k, exact for -149 <= k <= 127
@@ -226,8 +226,8 @@ constexpr float pow2_const(int k) {     // 2^k, exact for -149 <= k <= 127
 
 // All tables are compile-time constants.  The compiler evaluates constant expressions in
 // IEEE binary32 with round-to-nearest-even, so every entry is the result of the same single
-// divisions the definitions prescribe (Algorithm 1 line 11; Algorithm 2 lines 10-11;
-// Algorithm 3 line 10); the powers of two are exact.
+// divisions the definitions prescribe (the decoders of Algorithms 1, 2 and 3); the powers of two
+// are exact.
 constexpr DecodeTables make_decode_tables() {
     DecodeTables t{};
     for (int i = 0; i < 256; ++i) {
@@ -267,7 +267,7 @@ __device__ __forceinline__ void fill_tables(DecodeTables& t, int tid) {
 // In-kernel forms of C^-1 and of the rho half of C through the LDS tables.  E is the exponent
 // field of theta' (bits 7..14 of its BF16 pattern).
 //   C^-1: theta_hat = theta' + q * 2^l.  The product is exact, or rounds once when it is
-//         subnormal - exactly what the two-factor form of Algorithm 1 (line 11) does.
+//         subnormal - exactly what the two-factor form in Algorithm 1's decoder does.
 //   C:    rho = Round(((e * 2^h) * (127 * 2^(-l-h)))): both products are exact (e has at most
 //         16 significant bits below theta'), so this is Round(e_norm * 127).  For a finite
 //         theta' the clamp of Algorithm 1 is the identity (|e| <= 2^l under round-to-nearest);

@@ -1,7 +1,7 @@
 """Shared plumbing of the GPU parity tests: moving state between the oracle's numpy arrays and
 the library's device buffers, and the comparison bar.
 
-Bar (BASELINE the benchmark spec): 8-bit codes, correction bytes and FP16 scales bit-exact, with at most
+Bar: 8-bit codes, correction bytes and FP16 scales bit-exact, with at most
 a 1-LSB difference on at most 1e-5 of the elements (reported); BF16 weights and reconstructed
 master weights within 1e-6 relative.
 """
