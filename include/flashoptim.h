@@ -23,7 +23,11 @@
  *    (the initialisation of Algorithm 4): a zero scale decodes to exactly zero.
  *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
  *    stream) and the call returns without waiting.  Buffers may be reused or freed
- *    by the caller in stream order.
+ *    by the caller in stream order.  Calls that touch the same tensors from different
+ *    streams must be ordered by the caller, as for any other kernel; calls on disjoint
+ *    lists may run concurrently (the library is thread-safe).
+ *  - One call covers at most 2^31 - 1 workgroups (2048 elements each for AdamW, 4096 for
+ *    SGD / Lion): more returns FLASHOPTIM_ERR_NUMEL_RANGE.
  *  - Return value: FLASHOPTIM_OK (0) or a negative flashoptim_status.  Arguments are
  *    validated before anything is enqueued: when an error is returned no buffer has
  *    been modified.  Nothing throws or aborts.

@@ -223,6 +223,10 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
     std::memset(&a, 0, sizeof(a));
     a.c = c;
     const int64_t ce = fo::chunk_elems(kind);
+    // one workgroup per chunk: the launch grid is a 31-bit count
+    int64_t total_chunks = 0;
+    for (const TensorDev& d : live) total_chunks += (d.numel + ce - 1) / ce;
+    if (total_chunks > (int64_t)0x7fffffff) return FLASHOPTIM_ERR_NUMEL_RANGE;
 
     if (live.size() == 1) {
         // gradient-release call: no table, no allocation, no lock

@@ -1,0 +1,60 @@
+"""Randomised GPU parity: random hyper-parameters (incl. extreme betas, step counts, learning rates),
+random tensor sizes, and states drawn directly as codes over the whole code range, so that the
+estimate-then-certify code paths see every region of their domain."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_23349_amd as fo
+import workloads as W
+from helpers import bits16, compare_state, download, upload_state
+
+pytestmark = pytest.mark.gpu
+
+
+def _random_state(kind, n, idx, seed):
+    rs = W.random_state(n, idx, seed=seed, with_variance=(kind == "adamw"))
+    st = oracle.TensorState(np.zeros(n, np.float32), kind)
+    st.thp = bits16(rs["thp"]); st.rho = rs["rho"].numpy().copy(); st.mq = rs["mq"].numpy().copy()
+    st.ms = bits16(rs["ms"])
+    if kind == "adamw":
+        st.vq = rs["vq"].numpy().copy(); st.vs = bits16(rs["vs"])
+    return st
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_random_hyperparameters_and_states(case):
+    rng = np.random.default_rng(1000 + case)
+    kind = ("adamw", "adamw", "sgd", "lion")[case % 4]
+    n = int(rng.integers(1, 300000))
+    f = lambda v: float(np.float32(v))
+    lr = f(10.0 ** rng.uniform(-6, -0.5))
+    wd = f(rng.choice([0.0, 10.0 ** rng.uniform(-4, -0.3)]))
+    b1 = f(rng.choice([0.0, 0.5, 0.9, 0.99, rng.uniform(0, 0.999)]))
+    b2 = f(rng.choice([0.0, 0.9, 0.95, 0.999, 0.9999, rng.uniform(0.5, 0.9999)]))
+    eps = f(10.0 ** rng.uniform(-12, -3))
+    t0 = int(rng.choice([1, 2, 7, 100, 12345, 10 ** 6]))
+    gscale = 10.0 ** rng.uniform(-7, -1)
+    st = _random_state(kind, n, case, seed=77)
+    buf = upload_state(st)
+    buf.lr, buf.weight_decay = lr, wd
+    spec = W.ParamSpec("r", (n,), "matrix")
+    tl = fo.TensorList([buf])
+    report = []
+    for t in range(t0, t0 + 3):
+        g = W.grad_bf16(spec, case, t, seed=77, dist=("student3" if case % 3 == 0 else "normal"), scale=gscale)
+        buf.grad.copy_(g.cuda())
+        gb = g.view(torch.int16).numpy().view(np.uint16)
+        if kind == "adamw":
+            fo.adamw_step(tl, b1, b2, eps, t)
+            oracle.adamw_step(st, gb, lr, wd, b1, b2, eps, t)
+        elif kind == "sgd":
+            fo.sgd_step(tl, b1)
+            oracle.sgd_step(st, gb, lr, wd, b1)
+        else:
+            fo.lion_step(tl, b1, b2)
+            oracle.lion_step(st, gb, lr, wd, b1, b2)
+        compare_state(download(buf), st, where=f"case {case} {kind} n={n} t={t}", report=report)
+    bad = [r for r in report if r[2]]
+    assert not bad, (kind, n, lr, wd, b1, b2, eps, t0, gscale, bad)
