@@ -172,6 +172,21 @@ int flashoptim_dequantize_momentum(const int8_t* q, const uint16_t* scale, float
 int flashoptim_quantize_variance(const float* v, uint8_t* q, uint16_t* scale, int64_t n, void* stream);
 int flashoptim_dequantize_variance(const uint8_t* q, const uint16_t* scale, float* v, int64_t n, void* stream);
 
+/* ---- linear baseline and quantisation error (Section 4.5) ------------------------------
+ * The paper validates its companders against "standard scaled integer quantization": the same
+ * group-wise FP16 absmax scale, no compander (momentum code = Round(127 m / s); variance code =
+ * Round(255 v / s) with s the group maximum of v itself).
+ * quantize_state / dequantize_state: state 0 = momentum (INT8 codes), 1 = variance (UINT8 codes);
+ *   linear 0 = companded (identical to the four entry points above), 1 = the linear baseline.
+ * quantization_nmse: quantizes and dequantizes x on the fly and returns in `sums` (HOST, 2 doubles)
+ *   sum (x_hat - x)^2 and sum x^2, whose ratio is the normalised MSE the paper plots.  Waits for
+ *   completion. */
+int flashoptim_quantize_state(int state, int linear, const float* x, void* q, uint16_t* scale, int64_t n,
+                              void* stream);
+int flashoptim_dequantize_state(int state, int linear, const void* q, const uint16_t* scale, float* x, int64_t n,
+                                void* stream);
+int flashoptim_quantization_nmse(int state, int linear, const float* x, int64_t n, double* sums, void* stream);
+
 /* ---- checkpoint (Section 3.4, "Checkpoint size": 2 + 1 + 1 + 1 bytes per parameter) --
  * The paper fixes the content, not a container.  Blob layout, little-endian:
  *   header (64 B): "FOPTCKPT" | u32 version = 1 | u32 kind | i64 step | i64 n_tensors |

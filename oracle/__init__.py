@@ -47,7 +47,9 @@ def _declare(L):
     L.fo_oracle_reconstruct.restype = None
     L.fo_oracle_reconstruct.argtypes = [vp, vp, vp, i64, i32]
     for name in ("fo_oracle_quantize_momentum", "fo_oracle_dequantize_momentum",
-                 "fo_oracle_quantize_variance", "fo_oracle_dequantize_variance"):
+                 "fo_oracle_quantize_variance", "fo_oracle_dequantize_variance",
+                 "fo_oracle_quantize_momentum_linear", "fo_oracle_dequantize_momentum_linear",
+                 "fo_oracle_quantize_variance_linear", "fo_oracle_dequantize_variance_linear"):
         getattr(L, name).restype = None
         getattr(L, name).argtypes = [vp, vp, vp, i64]
     L.fo_oracle_adamw_step.restype = None
@@ -139,38 +141,50 @@ def reconstruct(thp, rho, N=127):
     return out
 
 
-def quantize_momentum(m):
+def _suffix(linear):
+    return "_linear" if linear else ""
+
+
+def quantize_momentum(m, linear=False):
+    """Q_m (companded; linear=True: plain absmax quantisation without the compander)."""
     m = _c(m, np.float32).ravel()
     q = np.empty(m.size, np.int8)
     s = np.empty(n_groups(m.size), np.uint16)
-    lib().fo_oracle_quantize_momentum(_p(m), _p(q), _p(s), m.size)
+    getattr(lib(), "fo_oracle_quantize_momentum" + _suffix(linear))(_p(m), _p(q), _p(s), m.size)
     return q, s
 
 
-def dequantize_momentum(q, s):
+def dequantize_momentum(q, s, linear=False):
     q = _c(q, np.int8).ravel()
     s = _c(s, np.uint16).ravel()
     assert s.size == n_groups(q.size)
     out = np.empty(q.size, np.float32)
-    lib().fo_oracle_dequantize_momentum(_p(q), _p(s), _p(out), q.size)
+    getattr(lib(), "fo_oracle_dequantize_momentum" + _suffix(linear))(_p(q), _p(s), _p(out), q.size)
     return out
 
 
-def quantize_variance(v):
+def quantize_variance(v, linear=False):
     v = _c(v, np.float32).ravel()
     q = np.empty(v.size, np.uint8)
     s = np.empty(n_groups(v.size), np.uint16)
-    lib().fo_oracle_quantize_variance(_p(v), _p(q), _p(s), v.size)
+    getattr(lib(), "fo_oracle_quantize_variance" + _suffix(linear))(_p(v), _p(q), _p(s), v.size)
     return q, s
 
 
-def dequantize_variance(q, s):
+def dequantize_variance(q, s, linear=False):
     q = _c(q, np.uint8).ravel()
     s = _c(s, np.uint16).ravel()
     assert s.size == n_groups(q.size)
     out = np.empty(q.size, np.float32)
-    lib().fo_oracle_dequantize_variance(_p(q), _p(s), _p(out), q.size)
+    getattr(lib(), "fo_oracle_dequantize_variance" + _suffix(linear))(_p(q), _p(s), _p(out), q.size)
     return out
+
+
+def nmse(x, x_hat):
+    """Normalised mean squared error sum((x_hat - x)^2) / sum(x^2), in double (Section 4.5)."""
+    x = np.asarray(x, np.float64).ravel()
+    d = np.asarray(x_hat, np.float64).ravel() - x
+    return float(np.dot(d, d) / np.dot(x, x))
 
 
 # -------------------------------------------------------------------- state --

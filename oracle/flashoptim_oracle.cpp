@@ -220,6 +220,43 @@ inline float dequant_v_one(uint8_t q, float s) {
     return v1 * v1;                                        // v  <- v'^2
 }
 
+// Linear (no companding) group quantizers: the "standard scaled integer quantization" that
+// Section 4.5 compares against.  Same scale rule [R-Q2] [R-Q3] and rounding [R-Q4]; the compander
+// is dropped: momentum code = Round(127 m / s); variance code = Round(255 v / s) with s = max v.
+void quant_m_linear_group(const float* m, int cnt, int8_t* q, uint16_t* scale_out) {
+    float a = 0.0f;
+    for (int i = 0; i < cnt; ++i) { float t = std::fabs(m[i]); if (t > a) a = t; }
+    uint16_t hs = group_scale(a);
+    *scale_out = hs;
+    float s = fp16_to_f32(hs);
+    if (s == 0.0f) { for (int i = 0; i < cnt; ++i) q[i] = 0; return; }
+    float r = 1.0f / s;
+    for (int i = 0; i < cnt; ++i) {
+        float y = std::rint((m[i] * r) * 127.0f);
+        if (y > 127.0f) y = 127.0f;
+        if (y < -127.0f) y = -127.0f;
+        q[i] = (int8_t)(int)y;
+    }
+}
+inline float dequant_m_linear_one(int8_t q, float s) { return ((float)q / 127.0f) * s; }
+
+void quant_v_linear_group(const float* v, int cnt, uint8_t* q, uint16_t* scale_out) {
+    float a = 0.0f;
+    for (int i = 0; i < cnt; ++i) if (v[i] > a) a = v[i];
+    uint16_t hs = group_scale(a);
+    *scale_out = hs;
+    float s = fp16_to_f32(hs);
+    if (s == 0.0f) { for (int i = 0; i < cnt; ++i) q[i] = 0; return; }
+    float r = 1.0f / s;
+    for (int i = 0; i < cnt; ++i) {
+        float y = std::rint((v[i] * r) * 255.0f);
+        if (y > 255.0f) y = 255.0f;
+        if (y < 0.0f) y = 0.0f;
+        q[i] = (uint8_t)(int)y;
+    }
+}
+inline float dequant_v_linear_one(uint8_t q, float s) { return ((float)q / 255.0f) * s; }
+
 // Reciprocal of a bias correction 1 - beta^t.  [R-Q6]
 inline float recip_bias_correction(float beta, int64_t t) {
     float bc = (float)(1.0 - std::pow((double)beta, (double)t));
@@ -293,6 +330,25 @@ void fo_oracle_quantize_variance(const float* v, uint8_t* q, uint16_t* scale, in
 
 void fo_oracle_dequantize_variance(const uint8_t* q, const uint16_t* scale, float* v, int64_t n) {
     for (int64_t i = 0; i < n; ++i) v[i] = dequant_v_one(q[i], fp16_to_f32(scale[i / kGroup]));
+}
+
+void fo_oracle_quantize_momentum_linear(const float* m, int8_t* q, uint16_t* scale, int64_t n) {
+    for (int64_t g = 0; g < n_groups(n); ++g) {
+        int64_t o = g * kGroup; int cnt = (int)((n - o < kGroup) ? n - o : kGroup);
+        quant_m_linear_group(m + o, cnt, q + o, scale + g);
+    }
+}
+void fo_oracle_dequantize_momentum_linear(const int8_t* q, const uint16_t* scale, float* m, int64_t n) {
+    for (int64_t i = 0; i < n; ++i) m[i] = dequant_m_linear_one(q[i], fp16_to_f32(scale[i / kGroup]));
+}
+void fo_oracle_quantize_variance_linear(const float* v, uint8_t* q, uint16_t* scale, int64_t n) {
+    for (int64_t g = 0; g < n_groups(n); ++g) {
+        int64_t o = g * kGroup; int cnt = (int)((n - o < kGroup) ? n - o : kGroup);
+        quant_v_linear_group(v + o, cnt, q + o, scale + g);
+    }
+}
+void fo_oracle_dequantize_variance_linear(const uint8_t* q, const uint16_t* scale, float* v, int64_t n) {
+    for (int64_t i = 0; i < n; ++i) v[i] = dequant_v_linear_one(q[i], fp16_to_f32(scale[i / kGroup]));
 }
 
 // ------------------------------------------------------------------- steps --

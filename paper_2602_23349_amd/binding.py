@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = [
     "flashoptim_selftest", "flashoptim_split_weights_i16", "flashoptim_reconstruct_weights_i16",
     "flashoptim_reconstruction_sweep",
     "flashoptim_adamw_step_ex", "flashoptim_sgd_step_ex", "flashoptim_lion_step_ex",
+    "flashoptim_quantize_state", "flashoptim_dequantize_state", "flashoptim_quantization_nmse",
 ]
 
 
@@ -86,6 +87,9 @@ def load_library():
                  "flashoptim_reconstruct_weights_i16", "flashoptim_quantize_momentum",
                  "flashoptim_dequantize_momentum", "flashoptim_quantize_variance", "flashoptim_dequantize_variance"):
         getattr(L, name).argtypes = [vp, vp, vp, i64, vp]
+    L.flashoptim_quantize_state.argtypes = [i32, i32, vp, vp, vp, i64, vp]
+    L.flashoptim_dequantize_state.argtypes = [i32, i32, vp, vp, vp, i64, vp]
+    L.flashoptim_quantization_nmse.argtypes = [i32, i32, vp, i64, C.POINTER(C.c_double), vp]
     L.flashoptim_checkpoint_size.argtypes = [i32, C.POINTER(i64), i64]
     L.flashoptim_checkpoint_size.restype = i64
     L.flashoptim_checkpoint_pack.argtypes = [i32, C.POINTER(_Tensor), i64, i64, vp, i64, vp]
@@ -286,6 +290,27 @@ def quantize_variance(v, q, scale, stream=None):
 def dequantize_variance(q, scale, v, stream=None):
     _check(load_library().flashoptim_dequantize_variance(_ptr(q), _ptr(scale), _ptr(v), q.numel(), _stream(stream)),
            "flashoptim_dequantize_variance")
+
+
+_STATE = {"momentum": 0, "variance": 1}
+
+
+def quantize_state(state, linear, x, q, scale, stream=None):
+    _check(load_library().flashoptim_quantize_state(_STATE[state], int(bool(linear)), _ptr(x), _ptr(q), _ptr(scale),
+                                                    x.numel(), _stream(stream)), "flashoptim_quantize_state")
+
+
+def dequantize_state(state, linear, q, scale, x, stream=None):
+    _check(load_library().flashoptim_dequantize_state(_STATE[state], int(bool(linear)), _ptr(q), _ptr(scale), _ptr(x),
+                                                      q.numel(), _stream(stream)), "flashoptim_dequantize_state")
+
+
+def quantization_nmse(state, linear, x, stream=None):
+    """Returns (sum of squared errors, sum of squares) of quantize -> dequantize over x."""
+    sums = (C.c_double * 2)()
+    _check(load_library().flashoptim_quantization_nmse(_STATE[state], int(bool(linear)), _ptr(x), x.numel(), sums,
+                                                       _stream(stream)), "flashoptim_quantization_nmse")
+    return float(sums[0]), float(sums[1])
 
 
 def checkpoint_size(kind, numels):

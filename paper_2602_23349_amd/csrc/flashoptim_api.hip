@@ -521,7 +521,7 @@ int flashoptim_reconstruction_sweep(int correction_bits, uint64_t first, uint64_
 int flashoptim_quantize_momentum(const float* m, int8_t* q, uint16_t* scale, int64_t n, void* stream) {
     int rc = check_elementwise(m, q, scale, n);
     if (rc != FLASHOPTIM_OK || n == 0) return rc;
-    fo::launch_quantize(false, m, q, scale, n, static_cast<hipStream_t>(stream));
+    fo::launch_quantize(false, false, m, q, scale, n, static_cast<hipStream_t>(stream));
     FO_HIP(hipGetLastError());
     return FLASHOPTIM_OK;
 }
@@ -529,7 +529,7 @@ int flashoptim_quantize_momentum(const float* m, int8_t* q, uint16_t* scale, int
 int flashoptim_dequantize_momentum(const int8_t* q, const uint16_t* scale, float* m, int64_t n, void* stream) {
     int rc = check_elementwise(q, scale, m, n);
     if (rc != FLASHOPTIM_OK || n == 0) return rc;
-    fo::launch_dequantize(false, q, scale, m, n, static_cast<hipStream_t>(stream));
+    fo::launch_dequantize(false, false, q, scale, m, n, static_cast<hipStream_t>(stream));
     FO_HIP(hipGetLastError());
     return FLASHOPTIM_OK;
 }
@@ -537,7 +537,7 @@ int flashoptim_dequantize_momentum(const int8_t* q, const uint16_t* scale, float
 int flashoptim_quantize_variance(const float* v, uint8_t* q, uint16_t* scale, int64_t n, void* stream) {
     int rc = check_elementwise(v, q, scale, n);
     if (rc != FLASHOPTIM_OK || n == 0) return rc;
-    fo::launch_quantize(true, v, q, scale, n, static_cast<hipStream_t>(stream));
+    fo::launch_quantize(true, false, v, q, scale, n, static_cast<hipStream_t>(stream));
     FO_HIP(hipGetLastError());
     return FLASHOPTIM_OK;
 }
@@ -545,8 +545,51 @@ int flashoptim_quantize_variance(const float* v, uint8_t* q, uint16_t* scale, in
 int flashoptim_dequantize_variance(const uint8_t* q, const uint16_t* scale, float* v, int64_t n, void* stream) {
     int rc = check_elementwise(q, scale, v, n);
     if (rc != FLASHOPTIM_OK || n == 0) return rc;
-    fo::launch_dequantize(true, q, scale, v, n, static_cast<hipStream_t>(stream));
+    fo::launch_dequantize(true, false, q, scale, v, n, static_cast<hipStream_t>(stream));
     FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_quantize_state(int state, int linear, const float* x, void* q, uint16_t* scale, int64_t n,
+                              void* stream) {
+    if (state < 0 || state > 1 || linear < 0 || linear > 1) return FLASHOPTIM_ERR_INVALID_ARG;
+    int rc = check_elementwise(x, q, scale, n);
+    if (rc != FLASHOPTIM_OK || n == 0) return rc;
+    fo::launch_quantize(state == 1, linear == 1, x, q, scale, n, static_cast<hipStream_t>(stream));
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_dequantize_state(int state, int linear, const void* q, const uint16_t* scale, float* x, int64_t n,
+                                void* stream) {
+    if (state < 0 || state > 1 || linear < 0 || linear > 1) return FLASHOPTIM_ERR_INVALID_ARG;
+    int rc = check_elementwise(q, scale, x, n);
+    if (rc != FLASHOPTIM_OK || n == 0) return rc;
+    fo::launch_dequantize(state == 1, linear == 1, q, scale, x, n, static_cast<hipStream_t>(stream));
+    FO_HIP(hipGetLastError());
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_quantization_nmse(int state, int linear, const float* x, int64_t n, double* sums, void* stream_) {
+    if (state < 0 || state > 1 || linear < 0 || linear > 1 || !sums) return FLASHOPTIM_ERR_INVALID_ARG;
+    if (n < 0 || n >= kMaxNumel) return FLASHOPTIM_ERR_NUMEL_RANGE;
+    sums[0] = sums[1] = 0.0;
+    if (n == 0) return FLASHOPTIM_OK;
+    if (!x) return FLASHOPTIM_ERR_INVALID_ARG;
+    if (!aligned16(x)) return FLASHOPTIM_ERR_MISALIGNED;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    double* d = nullptr;
+    FO_HIP(hipMalloc((void**)&d, 2 * sizeof(double)));
+    hipError_t e = hipMemsetAsync(d, 0, 2 * sizeof(double), stream);
+    if (e == hipSuccess) { fo::launch_nmse(state == 1, linear == 1, x, n, d, stream); e = hipGetLastError(); }
+    if (e == hipSuccess) e = hipMemcpyAsync(sums, d, 2 * sizeof(double), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    (void)hipFree(d);
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        (void)hipGetLastError();
+        return FLASHOPTIM_ERR_HIP;
+    }
     return FLASHOPTIM_OK;
 }
 

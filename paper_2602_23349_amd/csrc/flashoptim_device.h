@@ -82,8 +82,10 @@ void launch_split(int bits, const float* theta, void* param, void* rho, int64_t 
 void launch_reconstruct(int bits, const void* param, const void* rho, float* theta, int64_t n, hipStream_t s);
 constexpr int kSweepStats = 8 + 2 * 256;
 hipError_t launch_sweep(int bits, uint64_t first, uint64_t stride, uint64_t count, double* stats, hipStream_t s);
-void launch_quantize(bool variance, const float* x, void* q, uint16_t* scale, int64_t n, hipStream_t s);
-void launch_dequantize(bool variance, const void* q, const uint16_t* scale, float* x, int64_t n, hipStream_t s);
+void launch_quantize(bool variance, bool linear, const float* x, void* q, uint16_t* scale, int64_t n, hipStream_t s);
+void launch_dequantize(bool variance, bool linear, const void* q, const uint16_t* scale, float* x, int64_t n,
+                       hipStream_t s);
+void launch_nmse(bool variance, bool linear, const float* x, int64_t n, double* sums, hipStream_t s);
 void launch_copy(const CopySegment* segs, const uint2* chunks, int64_t n_chunks, hipStream_t s);
 constexpr int kSelftestCounters = 10;   // two per section
 hipError_t launch_selftest(unsigned long long* counters, int section, const StepConsts& c, float scale_r,

@@ -829,37 +829,86 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(uint64_t first, uint64_
     }
 }
 
-// One lane per group of 32.
-template <bool VARIANCE>
+// Group quantizers written out plainly, one lane per group of 32.  LINEAR drops the compander
+// (the "standard scaled integer quantization" baseline of Section 4.5): momentum code =
+// Round(127 m / s), variance code = Round(255 v / s) with s the group maximum of v itself.
+template <bool VARIANCE, bool LINEAR>
+__device__ __forceinline__ uint32_t quantize_group(const float* x, int cnt, uint8_t* codes) {
+    float a = 0.0f;
+    for (int i = 0; i < cnt; ++i) {
+        const float t = VARIANCE ? (LINEAR ? x[i] : sqrtf(x[i])) : fabsf(x[i]);
+        a = fmaxf(a, t);
+    }
+    float r;
+    const uint32_t sbits = group_scale(a, &r);
+    for (int i = 0; i < cnt; ++i) {
+        uint32_t c;
+        if (!LINEAR) {
+            c = VARIANCE ? v_code_exact(x[i], r) : m_code_exact(x[i], r);
+        } else if (VARIANCE) {
+            c = round_to_int_bits(__builtin_amdgcn_fmed3f((x[i] * r) * 255.0f, 0.0f, 255.0f));
+        } else {
+            c = round_to_int_bits(__builtin_amdgcn_fmed3f((x[i] * r) * 127.0f, -127.0f, 127.0f));
+        }
+        codes[i] = (uint8_t)(c & 0xffu);
+    }
+    return sbits;
+}
+
+template <bool VARIANCE, bool LINEAR>
+__device__ __forceinline__ float dequantize_one(uint8_t q, float s) {
+    if (VARIANCE) {
+        const float v1 = ((float)q / 255.0f) * s;
+        return LINEAR ? v1 : v1 * v1;
+    }
+    const float z = (float)(int)(int8_t)q / 127.0f;
+    return LINEAR ? z * s : (z / (2.0f - fabsf(z))) * s;
+}
+
+template <bool VARIANCE, bool LINEAR>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const float* x, uint8_t* q, uint16_t* scale,
                                                             int64_t n) {
     const int64_t grp = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const int64_t o = grp * kGroup;
     if (o >= n) return;
     const int cnt = (n - o < kGroup) ? (int)(n - o) : kGroup;
-    float a = 0.0f;
-    for (int i = 0; i < cnt; ++i) {
-        const float t = VARIANCE ? sqrtf(x[o + i]) : fabsf(x[o + i]);
-        a = fmaxf(a, t);
-    }
-    float r;
-    scale[grp] = (uint16_t)group_scale(a, &r);
-    for (int i = 0; i < cnt; ++i)
-        q[o + i] = (uint8_t)((VARIANCE ? v_code_exact(x[o + i], r) : m_code_exact(x[o + i], r)) & 0xffu);
+    scale[grp] = (uint16_t)quantize_group<VARIANCE, LINEAR>(x + o, cnt, q + o);
 }
 
-template <bool VARIANCE>
+template <bool VARIANCE, bool LINEAR>
 __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* q, const uint16_t* scale, float* x,
                                                               int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= n) return;
-    const float s = (float)__builtin_bit_cast(_Float16, scale[i >> 5]);
-    if (VARIANCE) {
-        const float v1 = ((float)q[i] / 255.0f) * s;
-        x[i] = v1 * v1;
-    } else {
-        const float z = (float)(int)(int8_t)q[i] / 127.0f;
-        x[i] = (z / (2.0f - fabsf(z))) * s;
+    x[i] = dequantize_one<VARIANCE, LINEAR>(q[i], (float)__builtin_bit_cast(_Float16, scale[i >> 5]));
+}
+
+// Quantisation error of a buffer (Section 4.5): sums[0] += sum (Q^-1(Q(x)) - x)^2 and
+// sums[1] += sum x^2, in double; one lane per group, wavefront reduction, one atomic per wavefront.
+template <bool VARIANCE, bool LINEAR>
+__global__ __launch_bounds__(kThreads) void nmse_kernel(const float* x, int64_t n, double* sums) {
+    const int64_t grp = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t o = grp * kGroup;
+    double err = 0.0, ref = 0.0;
+    if (o < n) {
+        const int cnt = (n - o < kGroup) ? (int)(n - o) : kGroup;
+        uint8_t codes[kGroup];
+        const uint32_t sbits = quantize_group<VARIANCE, LINEAR>(x + o, cnt, codes);
+        const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)sbits);
+        for (int i = 0; i < cnt; ++i) {
+            const double xi = (double)x[o + i];
+            const double d = (double)dequantize_one<VARIANCE, LINEAR>(codes[i], s) - xi;
+            err += d * d;
+            ref += xi * xi;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        err += __shfl_down(err, off);
+        ref += __shfl_down(ref, off);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        atomicAdd(&sums[0], err);
+        atomicAdd(&sums[1], ref);
     }
 }
 
@@ -884,18 +933,36 @@ hipError_t launch_sweep(int bits, uint64_t first, uint64_t stride, uint64_t coun
     else hipLaunchKernelGGL((sweep_kernel<32767>), dim3(grid), dim3(kThreads), 0, s, first, stride, count, stats);
     return hipGetLastError();
 }
-void launch_quantize(bool variance, const float* x, void* q, uint16_t* scale, int64_t n, hipStream_t s) {
+template <bool VARIANCE, bool LINEAR>
+static void launch_codec(int op, const void* in, const uint16_t* scale_in, void* out, uint16_t* scale_out, int64_t n,
+                         double* sums, hipStream_t s) {
     const int64_t groups = (n + kGroup - 1) / kGroup;
-    if (variance) hipLaunchKernelGGL((quantize_kernel<true>), dim3(blocks_for(groups)), dim3(kThreads), 0, s, x,
-                                     (uint8_t*)q, scale, n);
-    else hipLaunchKernelGGL((quantize_kernel<false>), dim3(blocks_for(groups)), dim3(kThreads), 0, s, x,
-                            (uint8_t*)q, scale, n);
+    if (op == 0) hipLaunchKernelGGL((quantize_kernel<VARIANCE, LINEAR>), dim3(blocks_for(groups)), dim3(kThreads), 0, s,
+                                    (const float*)in, (uint8_t*)out, scale_out, n);
+    else if (op == 1) hipLaunchKernelGGL((dequantize_kernel<VARIANCE, LINEAR>), dim3(blocks_for(n)), dim3(kThreads), 0, s,
+                                         (const uint8_t*)in, scale_in, (float*)out, n);
+    else hipLaunchKernelGGL((nmse_kernel<VARIANCE, LINEAR>), dim3(blocks_for(groups)), dim3(kThreads), 0, s,
+                            (const float*)in, n, sums);
 }
-void launch_dequantize(bool variance, const void* q, const uint16_t* scale, float* x, int64_t n, hipStream_t s) {
-    if (variance) hipLaunchKernelGGL((dequantize_kernel<true>), dim3(blocks_for(n)), dim3(kThreads), 0, s,
-                                     (const uint8_t*)q, scale, x, n);
-    else hipLaunchKernelGGL((dequantize_kernel<false>), dim3(blocks_for(n)), dim3(kThreads), 0, s,
-                            (const uint8_t*)q, scale, x, n);
+static void dispatch_codec(bool variance, bool linear, int op, const void* in, const uint16_t* scale_in, void* out,
+                           uint16_t* scale_out, int64_t n, double* sums, hipStream_t s) {
+    if (variance) {
+        if (linear) launch_codec<true, true>(op, in, scale_in, out, scale_out, n, sums, s);
+        else launch_codec<true, false>(op, in, scale_in, out, scale_out, n, sums, s);
+    } else {
+        if (linear) launch_codec<false, true>(op, in, scale_in, out, scale_out, n, sums, s);
+        else launch_codec<false, false>(op, in, scale_in, out, scale_out, n, sums, s);
+    }
+}
+void launch_quantize(bool variance, bool linear, const float* x, void* q, uint16_t* scale, int64_t n, hipStream_t s) {
+    dispatch_codec(variance, linear, 0, x, nullptr, q, scale, n, nullptr, s);
+}
+void launch_dequantize(bool variance, bool linear, const void* q, const uint16_t* scale, float* x, int64_t n,
+                       hipStream_t s) {
+    dispatch_codec(variance, linear, 1, q, scale, x, nullptr, n, nullptr, s);
+}
+void launch_nmse(bool variance, bool linear, const float* x, int64_t n, double* sums, hipStream_t s) {
+    dispatch_codec(variance, linear, 2, x, nullptr, nullptr, nullptr, n, sums, s);
 }
 
 // ------------------------------------------------------------------ self-test --

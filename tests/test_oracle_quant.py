@@ -228,3 +228,53 @@ def test_companders_are_inverse_pairs():
     z = 2 * x / (1 + np.abs(x))
     assert np.allclose(z / (2 - np.abs(z)), x, atol=1e-15)
     assert np.abs(z).max() <= 1.0 and np.all(np.diff(z) > 0)
+
+
+# ------------------------------------------------ linear (no compander) baseline --
+
+def test_linear_quantizers_are_textbook_absmax_quantisation():
+    # Section 3.2 / 4.5: the baseline is group-wise absmax scaling to INT8 / UINT8.  Without the
+    # compander the code is round(127 m / s) (round(255 v / s)), so |m_hat - m| <= s/254 (s/510).
+    rng = np.random.default_rng(30)
+    m = _groups(rng, 5000, -6, 1)
+    q, s_bits = oracle.quantize_momentum(m.ravel(), linear=True)
+    s = oracle.fp16_to_f32(s_bits).astype(np.float64)[:, None]
+    a = np.abs(m.astype(np.float64)).max(axis=1, keepdims=True)
+    assert np.array_equal(s_bits, _f16(np.minimum(a[:, 0], 65504)).view(np.uint16))
+    ok = s[:, 0] > 0
+    c = 127.0 * m[ok].astype(np.float64) / s[ok]
+    safe = np.abs(np.abs(c - np.floor(c)) - 0.5) > 1e-4
+    assert np.array_equal(q.reshape(m.shape)[ok][safe], np.clip(np.rint(c), -127, 127)[safe].astype(np.int8))
+    back = oracle.dequantize_momentum(q, s_bits, linear=True).reshape(m.shape).astype(np.float64)
+    slack = np.maximum(a - s, 0) + s * 2.0 ** -20 + 1e-30
+    assert np.all(np.abs(back - m) <= s / 254 * (1 + 1e-3) + slack)
+    v = (_groups(rng, 5000, -8, 1, heavy=True) ** 2).astype(np.float32)
+    q, s_bits = oracle.quantize_variance(v.ravel(), linear=True)
+    s = oracle.fp16_to_f32(s_bits).astype(np.float64)[:, None]
+    a = v.astype(np.float64).max(axis=1, keepdims=True)
+    back = oracle.dequantize_variance(q, s_bits, linear=True).reshape(v.shape).astype(np.float64)
+    slack = np.maximum(a - s, 0) + s * 2.0 ** -20 + 1e-30
+    assert np.all(np.abs(back - v) <= s / 510 * (1 + 1e-3) + slack)
+    ok = s[:, 0] > 0
+    c = 255.0 * v[ok].astype(np.float64) / s[ok]
+    safe = np.abs(np.abs(c - np.floor(c)) - 0.5) > 1e-4
+    assert np.array_equal(q.reshape(v.shape)[ok][safe], np.clip(np.rint(c), 0, 255)[safe].astype(np.uint8))
+
+
+def test_companding_lowers_variance_quantisation_error():
+    # Section 4.5: companding gives a large NMSE improvement for variance buffers (heavy-tailed,
+    # large dynamic range), measured as sum((x_hat - x)^2) / sum(x^2).  Synthetic stand-in for the
+    # paper's training trajectories: v = EMA of squared heavy-tailed gradients.  Linear codes flush
+    # everything below 1/510 of the group maximum, which the relative (per-element) error shows.
+    rng = np.random.default_rng(31)
+    g = rng.standard_t(3, size=(4000, G)) * 1e-3
+    v = (0.001 * g * g).astype(np.float32)
+    cq, cs = oracle.quantize_variance(v.ravel())
+    lq, ls = oracle.quantize_variance(v.ravel(), linear=True)
+    cb = oracle.dequantize_variance(cq, cs).astype(np.float64)
+    lb = oracle.dequantize_variance(lq, ls, linear=True).astype(np.float64)
+    vv = v.ravel().astype(np.float64)
+    rel_c = np.abs(cb - vv) / vv
+    rel_l = np.abs(lb - vv) / vv
+    assert np.median(rel_c) < 0.25 * np.median(rel_l)
+    assert (lq == 0).mean() > 3 * (cq == 0).mean()       # linear codes lose far more entries entirely
