@@ -225,7 +225,8 @@ const char* flashoptim_strerror(int status);
  *   [2] short square root == sqrtf on 2^25 spread values and all of [1, 4)
  *   [3] momentum codes (Algorithm 2) and [4] variance codes (Algorithm 3): the estimate equals the
  *       exact code wherever the kernel's tie test does not ask for the exact evaluation.
- * n_checked, n_failed: HOST arrays of 5 counters (one per section above).  Waits for completion.
+ *   [5] short division == IEEE division on 2^26 + 2^24 operand pairs inside its range.
+ * n_checked, n_failed: HOST arrays of 6 counters (one per section above).  Waits for completion.
  * Returns FLASHOPTIM_OK, FLASHOPTIM_ERR_SELFTEST if any check failed, or another status. */
 int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream);
 int flashoptim_last_hip_error(void);

@@ -338,9 +338,9 @@ def checkpoint_unpack(kind, blob, tensors, stream=None):
 
 
 def selftest(stream=None):
-    """Runs the device self-test; returns (status, checked[5], failed[5])."""
-    checked = (C.c_int64 * 5)()
-    failed = (C.c_int64 * 5)()
+    """Runs the device self-test; returns (status, checked[6], failed[6])."""
+    checked = (C.c_int64 * 6)()
+    failed = (C.c_int64 * 6)()
     status = load_library().flashoptim_selftest(checked, failed, _stream(stream))
     if status not in (0, -6):
         raise FlashOptimError(status, "flashoptim_selftest")

@@ -663,6 +663,7 @@ int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream_) {
     StepConsts c;
     std::memset(&c, 0, sizeof(c));
     for (int section = 0; section < 4 && e == hipSuccess; ++section) e = fo::launch_selftest(d, section, c, 1.0f, stream);
+    if (e == hipSuccess) e = fo::launch_selftest(d, 5, c, 1.0f, stream);
     // variance codes: bias corrections of steps 1, 2, 10, 1000 and "infinity", three group scales
     const int64_t steps[5] = {1, 2, 10, 1000, 100000000};
     const float scales[3] = {0.000244140625f /* 2^-12 */, 0.00131988525390625f, 0.03125f};

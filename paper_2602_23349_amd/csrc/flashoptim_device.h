@@ -87,7 +87,7 @@ void launch_dequantize(bool variance, bool linear, const void* q, const uint16_t
                        hipStream_t s);
 void launch_nmse(bool variance, bool linear, const float* x, int64_t n, double* sums, hipStream_t s);
 void launch_copy(const CopySegment* segs, const uint2* chunks, int64_t n_chunks, hipStream_t s);
-constexpr int kSelftestCounters = 10;   // two per section
+constexpr int kSelftestCounters = 12;   // two per section
 hipError_t launch_selftest(unsigned long long* counters, int section, const StepConsts& c, float scale_r,
                            hipStream_t s);
 

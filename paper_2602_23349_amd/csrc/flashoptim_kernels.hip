@@ -154,6 +154,23 @@ __device__ __forceinline__ float sqrt_rn_midrange(float x) {
     return s;
 }
 
+// Correctly rounded n / d for operands well inside the normal range: 2^-60 <= |n|, d <= 2^60.
+// This is the usual refinement of the 1-ulp hardware reciprocal (one Newton step on the
+// reciprocal, two residual corrections of the quotient, every step one FMA); with the operands
+// in that range no intermediate result leaves the normal range, so the range scaling and the
+// special-case fix-up of the general division are not needed.  Callers check the range.
+constexpr float kDivFastLo = 8.673617379884035e-19f;    // 2^-60
+constexpr float kDivFastHi = 1.152921504606847e18f;     // 2^60
+__device__ __forceinline__ float div_rn_midrange(float n, float d) {
+    float r = __builtin_amdgcn_rcpf(d);
+    const float e = fmaf(-d, r, 1.0f);
+    r = fmaf(e, r, r);
+    float q = n * r;
+    q = fmaf(fmaf(-d, q, n), r, q);
+    q = fmaf(fmaf(-d, q, n), r, q);
+    return q;
+}
+
 // Exact Q_m code (low byte of the result) of one element given the reciprocal group scale
 // (Algorithm 2, encoder).
 __device__ __forceinline__ uint32_t m_code_exact(float m, float r) {
@@ -497,7 +514,7 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
         // four elements at a time (one word of each byte stream)
         float th4[4], mh4[4], vh4[4];
         float tht[4];     // new master weights of this block
-        float vmin = 3.0e38f;
+        float vmin = 3.0e38f, vmax = 0.0f, nmin = 3.0e38f, nmax = 0.0f;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int i = 4 * j + k;
@@ -535,7 +552,10 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
                 const float gg = g * g;
                 const float v_new = (c.beta2 * v) + (c.omb2 * gg);
                 mh4[k] = m_new * c.rbc1;
+                nmin = fminf(nmin, fabsf(mh4[k]));
+                nmax = fmaxf(nmax, fabsf(mh4[k]));
                 const float vhat = v_new * c.rbc2;
+                vmax = fmaxf(vmax, vhat);
                 vh4[k] = vhat;
                 th4[k] = th;
                 vt[i] = v_new;
@@ -563,10 +583,21 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
 #pragma unroll
                 for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrt_rn_midrange(vh4[k]);
             }
+            // m_hat / (sqrt(v_hat) + eps): the short division when every operand of the block is well
+            // inside the normal range (eps <= den <= sqrt(v_hat max) + eps), else the general one
+            const bool div_fast = (c.eps >= kDivFastLo) && (c.eps <= 1.0f) &&
+                                  !any_lane(!(nmin >= kDivFastLo && nmax <= kDivFastHi && vmax <= kDivFastHi));
+            float quo[4];
+            if (div_fast) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) quo[k] = div_rn_midrange(mh4[k], rh[4 * j + k] + c.eps);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) quo[k] = mh4[k] / (rh[4 * j + k] + c.eps);
+            }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const float den = rh[4 * j + k] + c.eps;
-                const float upd = (mh4[k] / den) + (wd * th4[k]);
+                const float upd = quo[k] + (wd * th4[k]);
                 tht[k] = th4[k] - (lr * upd);
             }
         }
@@ -979,9 +1010,16 @@ void launch_nmse(bool variance, bool linear, const float* x, int64_t n, double* 
 //              for every m' in [2^-13, 2) of either sign;
 //   section 4: variance codes: same for v_code_fast against v_code_exact, over every FP32 value of
 //              four binades of v, several bias-correction pairs and several group scales.
+//   section 5: div_rn_midrange(n, d) == n / d on 2^26 pseudo-random operand pairs with magnitudes
+//              in [2^-60, 2^60] (n of either sign), plus pairs that share d across all mantissas of n.
 // counters[2 * section] counts checks, counters[2 * section + 1] failures.
 
-constexpr int kSelftestSections = 5;
+constexpr int kSelftestSections = 6;
+
+__device__ __forceinline__ uint32_t selftest_hash(uint64_t x) {
+    x ^= x >> 33; x *= 0xff51afd7ed558ccdull; x ^= x >> 33; x *= 0xc4ceb9fe1a85ec53ull; x ^= x >> 33;
+    return (uint32_t)x;
+}
 
 __device__ __forceinline__ void selftest_tally(unsigned long long* counters, int section, bool checked, bool failed) {
     const unsigned long long c = __popcll(__builtin_amdgcn_ballot_w64(checked));
@@ -1031,6 +1069,23 @@ __global__ __launch_bounds__(kThreads) void selftest_kernel(unsigned long long* 
             checked = !(resid > 0.5f - kTieWindowM);
             failed = fast != exact;
         }
+    } else if (section == 5) {
+        if (gid < (1ull << 26) + (1ull << 24)) {
+            uint32_t nb, db;
+            if (gid < (1ull << 26)) {
+                const uint32_t h1 = selftest_hash(2 * gid + 1), h2 = selftest_hash(2 * gid + 2);
+                // exponent fields 67..187 = 2^-60 .. 2^60
+                nb = (h1 & 0x807fffffu) | ((67u + (h1 >> 23) % 121u) << 23);
+                db = (h2 & 0x007fffffu) | ((67u + (h2 >> 23) % 121u) << 23);
+            } else {
+                const uint32_t k = (uint32_t)(gid - (1ull << 26));
+                nb = 0x3a000000u + (k & 0x7fffffu) + ((k >> 23) << 31);      // all mantissas, both signs
+                db = 0x38d1b717u + (k >> 23) * 0x00345678u;                   // a typical denominator ~1e-4
+            }
+            const float n = u2f(nb), d = u2f(db);
+            checked = true;
+            failed = f2u(div_rn_midrange(n, d)) != f2u(n / d);
+        }
     } else {
         if (gid < 4ull * (1ull << 23)) {
             // four binades of v starting at 2^-30, 2^-29, 2^-11, 2^-10 (odd and even exponents; with the
@@ -1057,6 +1112,7 @@ hipError_t launch_selftest(unsigned long long* counters, int section, const Step
     else if (section == 1) n = 1ull << 24;
     else if (section == 2) n = (1ull << 25) + (1ull << 24);
     else if (section == 3) n = 2ull * 14 * (1ull << 23);
+    else if (section == 5) n = (1ull << 26) + (1ull << 24);
     else n = 4ull * (1ull << 23);
     hipLaunchKernelGGL(selftest_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s,
                        counters, section, c, scale_r);

@@ -16,3 +16,4 @@ def test_device_selftest_passes():
     # code sections: all candidates minus the few inside the tie window
     assert checked[3] > 0.99 * 2 * 14 * (1 << 23)
     assert checked[4] > 0.95 * 15 * 4 * (1 << 23)
+    assert checked[5] == (1 << 26) + (1 << 24)       # short division against IEEE division
