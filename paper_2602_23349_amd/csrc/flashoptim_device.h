@@ -35,7 +35,10 @@ constexpr int step_vec(int kind) { return kind == 0 ? FO_VEC_ADAMW : FO_VEC_SGD_
 constexpr int step_threads(int kind) { return kind == 0 ? FO_THREADS_ADAMW : FO_THREADS_SGD_LION; }
 constexpr int step_tiles(int kind) { return kind == 0 ? FO_TILES_ADAMW : FO_TILES_SGD_LION; }
 constexpr int chunk_elems(int kind) { return step_threads(kind) * step_vec(kind) * step_tiles(kind); }
-constexpr int kCopyChunkBytes = 64 * 1024;         // checkpoint copy: bytes per workgroup
+#ifndef FO_COPY_CHUNK_KB
+#define FO_COPY_CHUNK_KB 64
+#endif
+constexpr int kCopyChunkBytes = FO_COPY_CHUNK_KB * 1024;   // checkpoint copy: bytes per workgroup
 
 // One tensor as the kernels see it (device pointers), 96 bytes.
 struct TensorDev {

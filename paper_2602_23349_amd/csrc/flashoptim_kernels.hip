@@ -1135,7 +1135,8 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const CopySegment* segs,
     uint8_t* dst = sg.dst;
     for (int64_t o = begin + (int64_t)threadIdx.x * 16; o < end; o += (int64_t)kThreads * 16) {
         if (o + 16 <= sg.bytes) {
-            *reinterpret_cast<uint4*>(dst + o) = *reinterpret_cast<const uint4*>(src + o);
+            const uint4 v = ld128(src + o);
+            st128(dst + o, v.x, v.y, v.z, v.w);
         } else {
             for (int k = 0; k < 16 && o + k < end; ++k) dst[o + k] = (o + k < sg.bytes) ? src[o + k] : (uint8_t)0;
         }
