@@ -135,6 +135,16 @@ int flashoptim_sgd_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tensor
 int flashoptim_lion_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tensors,
                             const flashoptim_lion_hp* hp, unsigned flags, void* stream);
 
+/* ---- migration between a standard FP32 optimizer state and the compressed layout --------
+ * compress_state:   theta', rho <- C(theta);  m_q, m_scale <- Q_m(m);  v_q, v_scale <- Q_v(v)
+ *                   (Algorithms 1-3; the initialisation of Algorithm 4 when m = v = 0, and the way to
+ *                   adopt the compressed layout from an existing 12 B/param FP32 state).
+ * decompress_state: theta <- C^-1(theta', rho);  m <- Q_m^-1;  v <- Q_v^-1  (export).
+ * One launch over the list.  Both layouts' buffers of every tensor are required (v, v_q, v_scale for
+ * kind = FLASHOPTIM_ADAMW only); t.grad, t.lr, t.weight_decay are ignored. */
+int flashoptim_compress_state(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors, void* stream);
+int flashoptim_decompress_state(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors, void* stream);
+
 /* ---- weight splitting (Section 3.1, Algorithm 1, N = 127) --------------------------
  * split:       theta (FP32) -> theta' = BF16 round-to-nearest-even, rho = Round(e / (ULP(theta')/2) * 127)
  *              Used once at the start of training (initialisation of Algorithm 4).

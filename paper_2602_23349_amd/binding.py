@@ -26,6 +26,7 @@ EXPORTED_SYMBOLS = [
     "flashoptim_reconstruction_sweep",
     "flashoptim_adamw_step_ex", "flashoptim_sgd_step_ex", "flashoptim_lion_step_ex",
     "flashoptim_quantize_state", "flashoptim_dequantize_state", "flashoptim_quantization_nmse",
+    "flashoptim_compress_state", "flashoptim_decompress_state",
 ]
 
 
@@ -87,6 +88,8 @@ def load_library():
                  "flashoptim_reconstruct_weights_i16", "flashoptim_quantize_momentum",
                  "flashoptim_dequantize_momentum", "flashoptim_quantize_variance", "flashoptim_dequantize_variance"):
         getattr(L, name).argtypes = [vp, vp, vp, i64, vp]
+    L.flashoptim_compress_state.argtypes = [i32, C.POINTER(_TensorEx), i64, vp]
+    L.flashoptim_decompress_state.argtypes = [i32, C.POINTER(_TensorEx), i64, vp]
     L.flashoptim_quantize_state.argtypes = [i32, i32, vp, vp, vp, i64, vp]
     L.flashoptim_dequantize_state.argtypes = [i32, i32, vp, vp, vp, i64, vp]
     L.flashoptim_quantization_nmse.argtypes = [i32, i32, vp, i64, C.POINTER(C.c_double), vp]
@@ -178,13 +181,13 @@ class TensorList:
 
 
 class TensorListEx:
-    """Host array of flashoptim_tensor_ex descriptors for the ablation entry points."""
+    """Host array of flashoptim_tensor_ex descriptors (ablation and conversion entry points)."""
 
-    def __init__(self, buffers):
+    def __init__(self, buffers, check_flags=True):
         self.buffers = list(buffers)
         self.n = len(self.buffers)
         self.flags = self.buffers[0].flags if self.buffers else 3
-        assert all(b.flags == self.flags for b in self.buffers)
+        assert not check_flags or all(b.flags == self.flags for b in self.buffers)
         self.array = (_TensorEx * max(self.n, 1))()
         for i, b in enumerate(self.buffers):
             d = self.array[i]
@@ -217,6 +220,18 @@ def lion_step_ex(tensors, beta1, beta2, flags=None, stream=None):
     hp = _LionHp(beta1, beta2)
     _check(load_library().flashoptim_lion_step_ex(tl.array, tl.n, C.byref(hp), tl.flags if flags is None else flags,
                                                   _stream(stream)), "flashoptim_lion_step_ex")
+
+
+def compress_state(kind, tensors, stream=None):
+    tl = tensors if isinstance(tensors, TensorListEx) else TensorListEx(tensors, check_flags=False)
+    _check(load_library().flashoptim_compress_state(KIND[kind], tl.array, tl.n, _stream(stream)),
+           "flashoptim_compress_state")
+
+
+def decompress_state(kind, tensors, stream=None):
+    tl = tensors if isinstance(tensors, TensorListEx) else TensorListEx(tensors, check_flags=False)
+    _check(load_library().flashoptim_decompress_state(KIND[kind], tl.array, tl.n, _stream(stream)),
+           "flashoptim_decompress_state")
 
 
 def _as_list(tensors):

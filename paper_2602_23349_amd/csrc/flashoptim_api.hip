@@ -215,14 +215,23 @@ int to_dev_ex(const flashoptim_tensor_ex* t, int64_t n, bool has_v, bool split, 
     return FLASHOPTIM_OK;
 }
 
-// Launches one step over the live tensors (already validated and converted).
+// What a multi-tensor launch runs: an optimizer step, or a layout conversion.
+enum LiveOp { kOpStep = 0, kOpCompress = 1, kOpDecompress = 2 };
+
+hipError_t launch_op(LiveOp op, int kind, bool direct, bool split, bool quant, const StepArgs& a, int64_t blocks,
+                     hipStream_t stream) {
+    if (op == kOpStep) return fo::launch_step(kind, direct, split, quant, a, blocks, stream);
+    return fo::launch_convert(kind == FLASHOPTIM_ADAMW, op == kOpCompress, direct, a, blocks, stream);
+}
+
+// Launches one operation over the live tensors (already validated and converted).
 int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, const StepConsts& c,
-                hipStream_t stream) {
+                hipStream_t stream, LiveOp op = kOpStep) {
     if (live.empty()) return FLASHOPTIM_OK;
     StepArgs a;
     std::memset(&a, 0, sizeof(a));
     a.c = c;
-    const int64_t ce = fo::chunk_elems(kind);
+    const int64_t ce = (op == kOpStep) ? fo::chunk_elems(kind) : fo::kConvChunkElems;
     // one workgroup per chunk: the launch grid is a 31-bit count
     int64_t total_chunks = 0;
     for (const TensorDev& d : live) total_chunks += (d.numel + ce - 1) / ce;
@@ -232,7 +241,7 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
         // gradient-release call: no table, no allocation, no lock
         a.single = live[0];
         const int64_t blocks = (live[0].numel + ce - 1) / ce;
-        FO_HIP(fo::launch_step(kind, true, split, quant, a, blocks, stream));
+        FO_HIP(launch_op(op, kind, true, split, quant, a, blocks, stream));
         return FLASHOPTIM_OK;
     }
 
@@ -240,7 +249,7 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
     FO_HIP(hipGetDevice(&device));
     std::string key;
     key.reserve(16 + live.size() * 80);
-    const int32_t tag[4] = {kind, device, (int32_t)split, (int32_t)quant};
+    const int32_t tag[5] = {kind, device, (int32_t)split, (int32_t)quant, (int32_t)op};
     append(key, tag, sizeof(tag));
     for (const TensorDev& d : live) {
         const void* ids[9] = {d.param, d.rho, d.m_q, d.m_scale, d.v_q, d.v_scale, d.theta32, d.m32, d.v32};
@@ -267,7 +276,7 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
     }
     a.tensors = static_cast<const TensorDev*>(plan->d_table);
     a.chunks = plan->d_chunks;
-    FO_HIP(fo::launch_step(kind, false, split, quant, a, plan->n_chunks, stream));
+    FO_HIP(launch_op(op, kind, false, split, quant, a, plan->n_chunks, stream));
     return FLASHOPTIM_OK;
 }
 
@@ -285,6 +294,35 @@ int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, cons
     for (int64_t i = 0; i < n_tensors; ++i)
         if (tensors[i].numel > 0) live.push_back(to_dev(tensors[i], has_v));
     return launch_live(kind, true, true, live, c, static_cast<hipStream_t>(stream_));
+}
+
+// Conversion between the FP32 state and the compressed layout: every buffer of both layouts is needed.
+int run_convert(int kind, const flashoptim_tensor_ex* t, int64_t n, bool compress, void* stream_) {
+    if (kind < 0 || kind > 2) return FLASHOPTIM_ERR_INVALID_ARG;
+    const bool has_v = (kind == FLASHOPTIM_ADAMW);
+    if (n < 0 || (n > 0 && t == nullptr)) return FLASHOPTIM_ERR_INVALID_ARG;
+    std::vector<TensorDev> live;
+    for (int64_t i = 0; i < n; ++i) {
+        const flashoptim_tensor_ex& x = t[i];
+        if (x.t.numel < 0 || x.t.numel >= kMaxNumel) return FLASHOPTIM_ERR_NUMEL_RANGE;
+        if (x.t.numel == 0) continue;
+        const void* need[10] = {x.t.param, x.t.rho, x.t.m_q, x.t.m_scale, x.theta, x.m,
+                                has_v ? (const void*)x.t.v_q : x.theta, has_v ? (const void*)x.t.v_scale : x.theta,
+                                has_v ? (const void*)x.v : x.theta, x.theta};
+        for (const void* p : need) if (!p) return FLASHOPTIM_ERR_INVALID_ARG;
+        for (const void* p : need) if (!aligned16(p)) return FLASHOPTIM_ERR_MISALIGNED;
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        const flashoptim_tensor_ex& x = t[i];
+        if (x.t.numel == 0) continue;
+        TensorDev d = to_dev(x.t, has_v);
+        d.grad = nullptr;
+        d.theta32 = x.theta; d.m32 = x.m; d.v32 = has_v ? x.v : nullptr;
+        live.push_back(d);
+    }
+    StepConsts c;
+    std::memset(&c, 0, sizeof(c));
+    return launch_live(kind, true, true, live, c, static_cast<hipStream_t>(stream_), compress ? kOpCompress : kOpDecompress);
 }
 
 int run_step_ex(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors, const StepConsts& c,
@@ -460,6 +498,14 @@ int flashoptim_lion_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tenso
     StepConsts c;
     if (!lion_consts(hp, c)) return FLASHOPTIM_ERR_INVALID_ARG;
     return run_step_ex(FLASHOPTIM_LION, tensors, n_tensors, c, flags, stream);
+}
+
+int flashoptim_compress_state(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors, void* stream) {
+    return run_convert(kind, tensors, n_tensors, true, stream);
+}
+
+int flashoptim_decompress_state(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors, void* stream) {
+    return run_convert(kind, tensors, n_tensors, false, stream);
 }
 
 int flashoptim_split_weights(const float* theta, void* param_bf16, int8_t* rho, int64_t n, void* stream) {

@@ -81,6 +81,8 @@ struct CopySegment {
 
 hipError_t launch_step(int kind, bool direct, bool split, bool quant, const StepArgs& a, int64_t n_blocks,
                        hipStream_t s);
+constexpr int kConvChunkElems = 256 * 8;   // elements per workgroup of the layout-conversion kernel
+hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s);
 void launch_split(int bits, const float* theta, void* param, void* rho, int64_t n, hipStream_t s);
 void launch_reconstruct(int bits, const void* param, const void* rho, float* theta, int64_t n, hipStream_t s);
 constexpr int kSweepStats = 8 + 2 * 256;

@@ -996,6 +996,98 @@ void launch_nmse(bool variance, bool linear, const float* x, int64_t n, double* 
     dispatch_codec(variance, linear, 2, x, nullptr, nullptr, nullptr, n, sums, s);
 }
 
+// ------------------------------------------------------ layout conversion --
+//
+// Migration between a standard FP32 optimizer state (theta, m, v: 12 B/param for AdamW) and
+// the compressed layout: COMPRESS applies C, Q_m, Q_v (Algorithms 1-3) in one pass over a list;
+// the other direction applies the inverses.  Written with the plain exact forms; same chunk
+// table and lane layout (8 elements per lane, a lane quad per group) as the step kernels.
+constexpr int kConvVec = 8;
+constexpr int kConvThreads = 256;
+
+template <bool HAS_V, bool COMPRESS, bool DIRECT>
+__global__ __launch_bounds__(kConvThreads) void convert_kernel(StepArgs a) {
+    constexpr int VEC = kConvVec;
+    const int tid = (int)threadIdx.x;
+    TensorDev T;
+    int64_t chunk;
+    if (DIRECT) {
+        T = a.single;
+        chunk = (int64_t)blockIdx.x;
+    } else {
+        const uint2 ck = a.chunks[blockIdx.x];
+        T = a.tensors[ck.x];
+        chunk = (int64_t)ck.y;
+    }
+    const int64_t off = chunk * (int64_t)(kConvThreads * VEC) + (int64_t)tid * VEC;
+    const int64_t left = T.numel - off;
+    const int cnt = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+    uint16_t* param = reinterpret_cast<uint16_t*>(T.param);
+    if (COMPRESS) {
+        float th[VEC], m[VEC], v[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            th[i] = (i < cnt) ? T.theta32[off + i] : 0.0f;
+            m[i] = (i < cnt) ? T.m32[off + i] : 0.0f;
+            v[i] = (HAS_V && i < cnt) ? T.v32[off + i] : 0.0f;
+        }
+        float amax_m = 0.0f, amax_v = 0.0f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            amax_m = fmaxf(amax_m, fabsf(m[i]));
+            amax_v = fmaxf(amax_v, v[i]);
+        }
+        amax_m = group_max<VEC>(amax_m);          // every lane takes part, also those past the end
+        float r_m, r_v = 0.0f;
+        const uint32_t ms = group_scale(amax_m, &r_m);
+        uint32_t vs = 0;
+        if (HAS_V) {
+            amax_v = group_max<VEC>(amax_v);
+            vs = group_scale(sqrtf(amax_v), &r_v);   // max of sqrt = sqrt of max
+        }
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            if (i < cnt) {
+                const uint32_t b = bf16_pack(th[i], 0.0f) & 0xffffu;
+                param[off + i] = (uint16_t)b;
+                T.rho[off + i] = (int8_t)split_rho<127>(th[i], b);
+                T.m_q[off + i] = (int8_t)(m_code_exact(m[i], r_m) & 0xffu);
+                if (HAS_V) T.v_q[off + i] = (uint8_t)(v_code_exact(v[i], r_v) & 0xffu);
+            }
+        }
+        if ((tid & (kGroup / VEC - 1)) == 0 && cnt > 0) {
+            T.m_scale[off >> 5] = (uint16_t)ms;
+            if (HAS_V) T.v_scale[off >> 5] = (uint16_t)vs;
+        }
+    } else {
+        if (cnt == 0) return;
+        const float s_m = (float)__builtin_bit_cast(_Float16, T.m_scale[off >> 5]);
+        const float s_v = HAS_V ? (float)__builtin_bit_cast(_Float16, T.v_scale[off >> 5]) : 0.0f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            if (i < cnt) {
+                T.theta32[off + i] = reconstruct_n<127>(param[off + i], (int)T.rho[off + i]);
+                T.m32[off + i] = dequantize_one<false, false>((uint8_t)T.m_q[off + i], s_m);
+                if (HAS_V) T.v32[off + i] = dequantize_one<true, false>(T.v_q[off + i], s_v);
+            }
+        }
+    }
+}
+
+hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
+    const dim3 grid((unsigned)n_blocks), block(kConvThreads);
+#define FO_CONV(HV, CP, DR) hipLaunchKernelGGL((convert_kernel<HV, CP, DR>), grid, block, 0, s, a)
+    if (has_v) {
+        if (compress) { if (direct) FO_CONV(true, true, true); else FO_CONV(true, true, false); }
+        else { if (direct) FO_CONV(true, false, true); else FO_CONV(true, false, false); }
+    } else {
+        if (compress) { if (direct) FO_CONV(false, true, true); else FO_CONV(false, true, false); }
+        else { if (direct) FO_CONV(false, false, true); else FO_CONV(false, false, false); }
+    }
+#undef FO_CONV
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ self-test --
 //
 // The step kernels replace some exactly rounded operations by shorter sequences that give
