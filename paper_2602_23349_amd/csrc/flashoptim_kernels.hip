@@ -320,76 +320,136 @@ struct LaneIO {
     float v32[VEC];         // FP32 variance when states are not quantized
 };
 
-// VEC floats from / to a 16-byte aligned address
-template <int VEC>
-__device__ __forceinline__ void ld_floats(float (&f)[VEC], const float* p) {
-#pragma unroll
-    for (int k = 0; k < VEC / 4; ++k) {
-        const uint4 a = ld128(p + 4 * k);
-        f[4 * k] = u2f(a.x); f[4 * k + 1] = u2f(a.y); f[4 * k + 2] = u2f(a.z); f[4 * k + 3] = u2f(a.w);
-    }
+// Streaming accesses of a full lane.  Every stream of a tile is addressed as a wave-uniform
+// 64-bit base (tensor pointer + tile offset, kept in scalar registers) plus a 32-bit byte offset
+// of the lane, and the pointers are marked as global memory: the loads and stores then take the
+// "scalar base + vector offset" form and no 64-bit address arithmetic is left on the vector ALU.
+typedef const __attribute__((address_space(1))) uint8_t* gcptr_t;
+typedef __attribute__((address_space(1))) uint8_t* gptr_t;
+
+// The base is passed through readfirstlane (a register copy for a value that is already uniform)
+// so that the compiler keeps it apart from the lane offset instead of folding both into one
+// 64-bit vector address.
+__device__ __forceinline__ uint64_t uniform_u64(uint64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
 }
-template <int VEC>
-__device__ __forceinline__ void st_floats(float* p, const float (&f)[VEC]) {
-#pragma unroll
-    for (int k = 0; k < VEC / 4; ++k) st128(p + 4 * k, f2u(f[4 * k]), f2u(f[4 * k + 1]), f2u(f[4 * k + 2]), f2u(f[4 * k + 3]));
+__device__ __forceinline__ gcptr_t gbase(const void* p, int64_t byte_off) {
+    return (gcptr_t)uniform_u64((uint64_t)p + (uint64_t)byte_off);
+}
+__device__ __forceinline__ gptr_t gbase(void* p, int64_t byte_off) {
+    return (gptr_t)uniform_u64((uint64_t)p + (uint64_t)byte_off);
 }
 
-// 4 * N bytes from / to a 4N-byte aligned address
+// Redefines a 32-bit lane offset at the point of use (an empty asm statement, no instruction):
+// its zero-extension then stays next to the access it feeds, which the "scalar base + 32-bit
+// vector offset" addressing form requires.
+__device__ __forceinline__ uint32_t block_local(uint32_t v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
+// 4 * N bytes from / to base + byte_off (4N-byte aligned, N <= 4)
 template <int N>
-__device__ __forceinline__ void ld_words(uint32_t (&w)[N], const void* p) {
-    static_assert(N == 2 || N == 4 || N == 8, "");
-    if constexpr (N == 2) {
+__device__ __forceinline__ void gld(uint32_t (&w)[N], gcptr_t base, uint32_t byte_off) {
+    static_assert(N == 2 || N == 4, "");
+    typedef uint32_t vec_t __attribute__((ext_vector_type(N)));
+    typedef const __attribute__((address_space(1))) vec_t* vptr_t;
 #if FO_NT_LOAD
-        const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+    const vec_t v = __builtin_nontemporal_load((vptr_t)(base + byte_off));
 #else
-        const u32x2_t v = *reinterpret_cast<const u32x2_t*>(p);
+    const vec_t v = *(vptr_t)(base + byte_off);
 #endif
-        w[0] = v.x; w[1] = v.y;
-    } else if constexpr (N == 4) {
-        const uint4 a = ld128(p);
-        w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+#pragma unroll
+    for (int k = 0; k < N; ++k) w[k] = v[k];
+}
+template <int N>
+__device__ __forceinline__ void gst(gptr_t base, uint32_t byte_off, const uint32_t (&w)[N]) {
+    static_assert(N == 2 || N == 4, "");
+    typedef uint32_t vec_t __attribute__((ext_vector_type(N)));
+    typedef __attribute__((address_space(1))) vec_t* vptr_t;
+    vec_t v;
+#pragma unroll
+    for (int k = 0; k < N; ++k) v[k] = w[k];
+#if FO_NT_STORE
+    __builtin_nontemporal_store(v, (vptr_t)(base + byte_off));
+#else
+    *(vptr_t)(base + byte_off) = v;
+#endif
+}
+// 4 * N bytes as consecutive 16-byte (or one 8-byte) accesses
+template <int N>
+__device__ __forceinline__ void gld_words(uint32_t (&w)[N], gcptr_t base, uint32_t byte_off) {
+    if constexpr (N <= 4) {
+        gld(w, base, byte_off);
     } else {
-        const uint4 a = ld128(p), b = ld128(reinterpret_cast<const uint8_t*>(p) + 16);
-        w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+        static_assert(N % 4 == 0, "");
+#pragma unroll
+        for (int k = 0; k < N / 4; ++k) {
+            uint32_t t[4];
+            gld(t, base, byte_off + 16u * k);
+            w[4 * k] = t[0]; w[4 * k + 1] = t[1]; w[4 * k + 2] = t[2]; w[4 * k + 3] = t[3];
+        }
     }
 }
 template <int N>
-__device__ __forceinline__ void st_words(void* p, const uint32_t (&w)[N]) {
-    if constexpr (N == 2) {
-        const u32x2_t v = {w[0], w[1]};
-#if FO_NT_STORE
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x2_t*>(p));
-#else
-        *reinterpret_cast<u32x2_t*>(p) = v;
-#endif
-    } else if constexpr (N == 4) {
-        st128(p, w[0], w[1], w[2], w[3]);
+__device__ __forceinline__ void gst_words(gptr_t base, uint32_t byte_off, const uint32_t (&w)[N]) {
+    if constexpr (N <= 4) {
+        gst(base, byte_off, w);
     } else {
-        st128(p, w[0], w[1], w[2], w[3]);
-        st128(reinterpret_cast<uint8_t*>(p) + 16, w[4], w[5], w[6], w[7]);
+        static_assert(N % 4 == 0, "");
+#pragma unroll
+        for (int k = 0; k < N / 4; ++k) {
+            const uint32_t t[4] = {w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]};
+            gst(base, byte_off + 16u * k, t);
+        }
     }
 }
+template <int VEC>
+__device__ __forceinline__ void gld_floats(float (&f)[VEC], gcptr_t base, uint32_t byte_off) {
+    uint32_t w[VEC];
+    gld_words(w, base, byte_off);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) f[k] = u2f(w[k]);
+}
+template <int VEC>
+__device__ __forceinline__ void gst_floats(gptr_t base, uint32_t byte_off, const float (&f)[VEC]) {
+    uint32_t w[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) w[k] = f2u(f[k]);
+    gst_words(base, byte_off, w);
+}
+__device__ __forceinline__ uint32_t gld_u16(gcptr_t base, uint32_t byte_off) {
+    return *(const __attribute__((address_space(1))) uint16_t*)(base + byte_off);
+}
+__device__ __forceinline__ void gst_u16(gptr_t base, uint32_t byte_off, uint32_t v) {
+    *(__attribute__((address_space(1))) uint16_t*)(base + byte_off) = (uint16_t)v;
+}
 
+// A full lane: tile0 = index of the tile's first element in the tensor (wave-uniform, a multiple
+// of 32), lane_el = index of the lane's first element inside the tile (a multiple of VEC).
 template <int VEC, bool HAS_V, bool SPLIT, bool QUANT>
-__device__ __forceinline__ void load_full(LaneIO<VEC>& x, const TensorDev& T, int64_t off) {
+__device__ __forceinline__ void load_full(LaneIO<VEC>& x, const TensorDev& T, int64_t tile0, uint32_t lane_el) {
+    lane_el = block_local(lane_el);
     if (SPLIT) {
-        ld_words(x.p, reinterpret_cast<const uint16_t*>(T.param) + off);
-        ld_words(x.r, T.rho + off);
+        gld_words(x.p, gbase(T.param, 2 * tile0), 2u * lane_el);
+        gld_words(x.r, gbase(T.rho, tile0), lane_el);
     } else {
-        ld_floats(x.th32, T.theta32 + off);
+        gld_floats(x.th32, gbase(T.theta32, 4 * tile0), 4u * lane_el);
     }
-    ld_words(x.g, reinterpret_cast<const uint16_t*>(T.grad) + off);
+    gld_words(x.g, gbase(T.grad, 2 * tile0), 2u * lane_el);
     if (QUANT) {
-        ld_words(x.mq, T.m_q + off);
-        x.ms = T.m_scale[off >> 5];
+        const uint32_t scale_off = (lane_el >> 5) * 2u;
+        gld_words(x.mq, gbase(T.m_q, tile0), lane_el);
+        x.ms = gld_u16(gbase(T.m_scale, (tile0 >> 5) * 2), scale_off);
         if (HAS_V) {
-            ld_words(x.vq, T.v_q + off);
-            x.vs = T.v_scale[off >> 5];
+            gld_words(x.vq, gbase(T.v_q, tile0), lane_el);
+            x.vs = gld_u16(gbase(T.v_scale, (tile0 >> 5) * 2), scale_off);
         }
     } else {
-        ld_floats(x.m32, T.m32 + off);
-        if (HAS_V) ld_floats(x.v32, T.v32 + off);
+        gld_floats(x.m32, gbase(T.m32, 4 * tile0), 4u * lane_el);
+        if (HAS_V) gld_floats(x.v32, gbase(T.v32, 4 * tile0), 4u * lane_el);
     }
 }
 
@@ -438,24 +498,26 @@ __device__ __forceinline__ void load_tail(LaneIO<VEC>& x, const TensorDev& T, in
 }
 
 template <int VEC, bool HAS_V, bool SPLIT, bool QUANT>
-__device__ __forceinline__ void store_full(const LaneIO<VEC>& y, const TensorDev& T, int64_t off,
+__device__ __forceinline__ void store_full(const LaneIO<VEC>& y, const TensorDev& T, int64_t tile0, uint32_t lane_el,
                                            bool group_leader) {
+    lane_el = block_local(lane_el);
     if (SPLIT) {
-        st_words(reinterpret_cast<uint16_t*>(T.param) + off, y.p);
-        st_words(T.rho + off, y.r);
+        gst_words(gbase(T.param, 2 * tile0), 2u * lane_el, y.p);
+        gst_words(gbase(T.rho, tile0), lane_el, y.r);
     } else {
-        st_floats(T.theta32 + off, y.th32);
+        gst_floats(gbase(T.theta32, 4 * tile0), 4u * lane_el, y.th32);
     }
     if (QUANT) {
-        st_words(T.m_q + off, y.mq);
-        if (HAS_V) st_words(T.v_q + off, y.vq);
+        gst_words(gbase(T.m_q, tile0), lane_el, y.mq);
+        if (HAS_V) gst_words(gbase(T.v_q, tile0), lane_el, y.vq);
         if (group_leader) {
-            T.m_scale[off >> 5] = (uint16_t)y.ms;
-            if (HAS_V) T.v_scale[off >> 5] = (uint16_t)y.vs;
+            const uint32_t scale_off = (lane_el >> 5) * 2u;
+            gst_u16(gbase(T.m_scale, (tile0 >> 5) * 2), scale_off, y.ms);
+            if (HAS_V) gst_u16(gbase(T.v_scale, (tile0 >> 5) * 2), scale_off, y.vs);
         }
     } else {
-        st_floats(T.m32 + off, y.m32);
-        if (HAS_V) st_floats(T.v32 + off, y.v32);
+        gst_floats(gbase(T.m32, 4 * tile0), 4u * lane_el, y.m32);
+        if (HAS_V) gst_floats(gbase(T.v32, 4 * tile0), 4u * lane_el, y.v32);
     }
 }
 
@@ -492,6 +554,24 @@ __device__ __forceinline__ void store_tail(const LaneIO<VEC>& y, const TensorDev
 
 // ------------------------------------------------------- the per-lane update --
 //
+// Splits (or stores as FP32) the four new master weights of block j of a lane.
+template <int VEC, bool SPLIT>
+__device__ __forceinline__ void split_block(LaneIO<VEC>& y, const DecodeTables& tab, const float (&tht)[4], int j) {
+    if (SPLIT) {
+        const uint32_t w0 = bf16_pack(tht[0], tht[1]), w1 = bf16_pack(tht[2], tht[3]);
+        y.p[2 * j] = w0;
+        y.p[2 * j + 1] = w1;
+        const uint32_t e0 = w0 << 1, e1 = w1 << 1;     // exponent fields on byte boundaries
+        y.r[j] = pack_low_bytes(rho_bits_lds(tab, tht[0], w0 & 0xffffu, (e0 >> 8) & 0xffu),
+                                rho_bits_lds(tab, tht[1], w0 >> 16, e0 >> 24),
+                                rho_bits_lds(tab, tht[2], w1 & 0xffffu, (e1 >> 8) & 0xffu),
+                                rho_bits_lds(tab, tht[3], w1 >> 16, e1 >> 24));
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) y.th32[4 * j + k] = tht[k];
+    }
+}
+
 // KIND: 0 AdamW (Algorithm 4), 1 SGD (Algorithm 5), 2 Lion (Algorithm 6).
 // Operates on the VEC elements of one lane; the lanes holding the rest of the same 32-element
 // group (lane ^ 1, and lane ^ 2, lane ^ 3 when VEC == 8) must execute this function with it.
@@ -507,14 +587,14 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
     float mt[VEC];    // new momentum
     float vt[VEC];    // new variance (AdamW)
     float rh[VEC];    // sqrt of the bias-corrected new variance (AdamW)
+    float tha[VEC];   // AdamW: master weights, held until the range tests below are known
     float amax_m = 0.0f, amax_v = 0.0f;
+    float amin_m = 3.0e38f, amin_v = 3.0e38f;     // AdamW: smallest |m_t| and v_t of the lane
 
 #pragma unroll
     for (int j = 0; j < VEC / 4; ++j) {
         // four elements at a time (one word of each byte stream)
-        float th4[4], mh4[4], vh4[4];
-        float tht[4];     // new master weights of this block
-        float vmin = 3.0e38f, vmax = 0.0f, nmin = 3.0e38f, nmax = 0.0f;
+        float tht[4];     // new master weights of this block (SGD, Lion)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int i = 4 * j + k;
@@ -551,16 +631,11 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
                 m_new = (c.beta1 * m) + (c.omb1 * g);
                 const float gg = g * g;
                 const float v_new = (c.beta2 * v) + (c.omb2 * gg);
-                mh4[k] = m_new * c.rbc1;
-                nmin = fminf(nmin, fabsf(mh4[k]));
-                nmax = fmaxf(nmax, fabsf(mh4[k]));
-                const float vhat = v_new * c.rbc2;
-                vmax = fmaxf(vmax, vhat);
-                vh4[k] = vhat;
-                th4[k] = th;
+                tha[i] = th;
                 vt[i] = v_new;
                 amax_v = fmaxf(amax_v, v_new);
-                vmin = fminf(vmin, vhat);
+                amin_v = fminf(amin_v, v_new);
+                amin_m = fminf(amin_m, fabsf(m_new));
             } else if (KIND == 1) {
                 m_new = (c.beta1 * m) + g;                           // beta1 carries the momentum mu
                 tht[k] = th - (lr * (m_new + (wd * th)));
@@ -573,21 +648,37 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
             mt[i] = m_new;
             amax_m = fmaxf(amax_m, fabsf(m_new));
         }
-        if (KIND == 0) {
-            // sqrt(v_hat): the short sequence unless some lane holds a value below 2^-96
-            // (exact zeros take the general sequence too: one comparison covers both)
-            if (any_lane(vmin < kSqrtFastMin)) {
+        // epilogue, part 1 (SGD, Lion): split the new master weights of this block
+        if (KIND != 0) split_block<VEC, SPLIT>(y, tab, tht, j);
+    }
+    if (KIND == 0) {
+        // Range tests for the short square root and division, once per lane.  Multiplying by a
+        // positive constant and rounding is monotone, so the extreme bias-corrected values of the
+        // lane are the products of the extreme raw values: no separate running extremes are needed.
+        const float vmin = amin_v * c.rbc2, vmax = amax_v * c.rbc2;
+        const float nmin = amin_m * c.rbc1, nmax = amax_m * c.rbc1;
+        // sqrt(v_hat): the short sequence unless some lane holds a value below 2^-96
+        // (exact zeros take the general sequence too: one comparison covers both)
+        const bool sqrt_general = any_lane(vmin < kSqrtFastMin);
+        // m_hat / (sqrt(v_hat) + eps): the short division when every operand of the lane is well
+        // inside the normal range (eps <= den <= sqrt(v_hat max) + eps), else the general one
+        const bool div_fast = (c.eps >= kDivFastLo) && (c.eps <= 1.0f) &&
+                              !any_lane(!(nmin >= kDivFastLo && nmax <= kDivFastHi && vmax <= kDivFastHi));
+#pragma unroll
+        for (int j = 0; j < VEC / 4; ++j) {
+            float mh4[4], vh4[4], quo[4], tht[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                mh4[k] = mt[4 * j + k] * c.rbc1;
+                vh4[k] = vt[4 * j + k] * c.rbc2;
+            }
+            if (sqrt_general) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrtf(vh4[k]);
             } else {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrt_rn_midrange(vh4[k]);
             }
-            // m_hat / (sqrt(v_hat) + eps): the short division when every operand of the block is well
-            // inside the normal range (eps <= den <= sqrt(v_hat max) + eps), else the general one
-            const bool div_fast = (c.eps >= kDivFastLo) && (c.eps <= 1.0f) &&
-                                  !any_lane(!(nmin >= kDivFastLo && nmax <= kDivFastHi && vmax <= kDivFastHi));
-            float quo[4];
             if (div_fast) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) quo[k] = div_rn_midrange(mh4[k], rh[4 * j + k] + c.eps);
@@ -597,23 +688,11 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const float upd = quo[k] + (wd * th4[k]);
-                tht[k] = th4[k] - (lr * upd);
+                const float upd = quo[k] + (wd * tha[4 * j + k]);
+                tht[k] = tha[4 * j + k] - (lr * upd);
             }
-        }
-        // epilogue, part 1: split the new master weights of this block
-        if (SPLIT) {
-            const uint32_t w0 = bf16_pack(tht[0], tht[1]), w1 = bf16_pack(tht[2], tht[3]);
-            y.p[2 * j] = w0;
-            y.p[2 * j + 1] = w1;
-            const uint32_t e0 = w0 << 1, e1 = w1 << 1;     // exponent fields on byte boundaries
-            y.r[j] = pack_low_bytes(rho_bits_lds(tab, tht[0], w0 & 0xffffu, (e0 >> 8) & 0xffu),
-                                    rho_bits_lds(tab, tht[1], w0 >> 16, e0 >> 24),
-                                    rho_bits_lds(tab, tht[2], w1 & 0xffffu, (e1 >> 8) & 0xffu),
-                                    rho_bits_lds(tab, tht[3], w1 >> 16, e1 >> 24));
-        } else {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) y.th32[4 * j + k] = tht[k];
+            // epilogue, part 1 (AdamW): split the new master weights of this block
+            split_block<VEC, SPLIT>(y, tab, tht, j);
         }
     }
     if (!QUANT) {
@@ -697,12 +776,17 @@ __global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
     // k+1 are issued BEFORE the stores of tile k, so that waiting for them does not wait for
     // those stores.
     const bool leader = (tid & (kGroup / VEC - 1)) == 0;
-    int64_t off = chunk * (int64_t)(kTile * TILES) + (int64_t)tid * VEC;
-    int64_t left = T.numel - off;
-    int cnt = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+    const uint32_t lane_el = (uint32_t)tid * VEC;              // first element of the lane inside its tile
+    int64_t tile0 = chunk * (int64_t)(kTile * TILES);          // first element of the tile (wave-uniform)
+    // elements of the tensor from the start of this tile on, capped at one tile (wave-uniform), and
+    // the number of them that fall to this lane
+    int64_t rem = T.numel - tile0;
+    int tile_cnt = rem >= kTile ? kTile : (int)rem;
+    int left = tile_cnt - (int)lane_el;
+    int cnt = left >= VEC ? VEC : (left > 0 ? left : 0);
     LaneIO<VEC> x, y;
-    if (cnt == VEC) load_full<VEC, HAS_V, SPLIT, QUANT>(x, T, off);
-    else load_tail<VEC, HAS_V, SPLIT, QUANT>(x, T, off, cnt);
+    if (cnt == VEC) load_full<VEC, HAS_V, SPLIT, QUANT>(x, T, tile0, lane_el);
+    else load_tail<VEC, HAS_V, SPLIT, QUANT>(x, T, tile0 + lane_el, cnt);
     fill_tables<THREADS>(tab, tid);
     __syncthreads();
 #pragma unroll
@@ -710,17 +794,19 @@ __global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
         // All lanes of a group run the update together (a lane with cnt == 0 may share its group
         // with lanes that hold elements); lanes past the end compute on zeros and store nothing.
         update_lane<KIND, VEC, SPLIT, QUANT>(x, y, tab, a.c, T.lr, T.wd);
-        const int64_t off_done = off;
+        const int64_t tile_done = tile0;
         const int cnt_done = cnt;
         if (t + 1 < TILES) {
-            off += kTile;
-            left = T.numel - off;
-            cnt = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
-            if (cnt == VEC) load_full<VEC, HAS_V, SPLIT, QUANT>(x, T, off);
-            else load_tail<VEC, HAS_V, SPLIT, QUANT>(x, T, off, cnt);
+            tile0 += kTile;
+            rem = T.numel - tile0;
+            tile_cnt = rem >= kTile ? kTile : (rem > 0 ? (int)rem : 0);
+            left = tile_cnt - (int)lane_el;
+            cnt = left >= VEC ? VEC : (left > 0 ? left : 0);
+            if (cnt == VEC) load_full<VEC, HAS_V, SPLIT, QUANT>(x, T, tile0, lane_el);
+            else load_tail<VEC, HAS_V, SPLIT, QUANT>(x, T, tile0 + lane_el, cnt);
         }
-        if (cnt_done == VEC) store_full<VEC, HAS_V, SPLIT, QUANT>(y, T, off_done, leader);
-        else store_tail<VEC, HAS_V, SPLIT, QUANT>(y, T, off_done, cnt_done, leader);
+        if (cnt_done == VEC) store_full<VEC, HAS_V, SPLIT, QUANT>(y, T, tile_done, lane_el, leader);
+        else store_tail<VEC, HAS_V, SPLIT, QUANT>(y, T, tile_done + lane_el, cnt_done, leader);
     }
 }
 
