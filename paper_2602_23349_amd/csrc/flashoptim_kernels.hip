@@ -16,9 +16,10 @@
 //   * decoding a state code is a function of one byte: rho/127, code/255 and
 //     phi_m^-1(code/127) come from three 256-entry LDS tables that each workgroup
 //     fills once with the same IEEE divisions the definition uses;
-//   * 2^l scalings of Algorithm 1 are single v_ldexp_f32 operations (exact, or one
-//     rounding when the result is subnormal - the same rounding the two-factor
-//     form of Algorithm 1 performs);
+//   * the 2^l scalings of Algorithm 1 are LDS tables of exact powers of two indexed by the
+//     exponent field of theta' (the decoder multiplies once: exact, or one rounding when
+//     the result is subnormal - the same rounding the two-factor form of Algorithm 1
+//     performs; the encoder multiplies by two exact factors);
 //   * Round(x) to an 8-bit integer is one FP32 addition of 1.5 * 2^23, whose low
 //     mantissa byte is the round-half-even integer in two's complement;
 //   * BF16 rounding uses the hardware v_cvt_pk_bf16_f32 (two elements per issue);
@@ -29,14 +30,18 @@
 //     lands within delta of a rounding tie the code is already decided.  Only when some
 //     lane of the wavefront is that close to a tie (a few percent of the wavefronts) are the
 //     few elements concerned recomputed with the exact sequence.  Codes are bit-identical
-//     to the exact evaluation in every case.
+//     to the exact evaluation in every case;
+//   * sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps) use the 1-ulp hardware root / reciprocal
+//     followed by FMA residual corrections that yield the correctly rounded result for
+//     operands inside a stated range; a wave-uniform range test selects the general
+//     sequence otherwise.
 //
-// Work decomposition.  A lane owns 16 consecutive elements per tile, so every
-// stream moves as 128-bit vectors and a quantisation group (32 elements) is exactly
-// two adjacent lanes: the group absmax needs one DPP lane swap and no LDS.
-// A workgroup (256 lanes) handles one chunk of kChunkElems consecutive elements of
-// one tensor; a chunk table maps blockIdx.x -> (tensor, chunk) so that one launch
-// covers a whole parameter list.
+// Work decomposition.  A lane owns 8 consecutive elements per tile: BF16 streams move as
+// 128-bit and byte streams as 64-bit accesses, and a quantisation group (32 elements) is a
+// lane quad, so the group absmax needs two DPP quad permutes and no LDS.  A workgroup (256
+// lanes for AdamW, 512 for SGD and Lion) handles one tile of consecutive elements of one
+// tensor; a chunk table maps blockIdx.x -> (tensor, tile) so that one launch covers a whole
+// parameter list.  Stream addresses are a scalar 64-bit tile base plus a 32-bit lane offset.
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -406,19 +411,29 @@ __device__ __forceinline__ void gst_words(gptr_t base, uint32_t byte_off, const 
         }
     }
 }
+// FP32 streams (ablation variants): VEC floats per lane are two or more 16-byte accesses, each of
+// which covers only part of every cache line the wavefront touches.  These go without the
+// non-temporal hint: with it the line is not kept between the two accesses and is fetched
+// twice (measured 26.8 vs 19.9 ms for the variant with FP32 weights on the Llama list).
 template <int VEC>
 __device__ __forceinline__ void gld_floats(float (&f)[VEC], gcptr_t base, uint32_t byte_off) {
-    uint32_t w[VEC];
-    gld_words(w, base, byte_off);
+    static_assert(VEC % 4 == 0, "");
+    typedef float vec_t __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) f[k] = u2f(w[k]);
+    for (int k = 0; k < VEC / 4; ++k) {
+        const vec_t v = *(const __attribute__((address_space(1))) vec_t*)(base + byte_off + 16u * k);
+        f[4 * k] = v[0]; f[4 * k + 1] = v[1]; f[4 * k + 2] = v[2]; f[4 * k + 3] = v[3];
+    }
 }
 template <int VEC>
 __device__ __forceinline__ void gst_floats(gptr_t base, uint32_t byte_off, const float (&f)[VEC]) {
-    uint32_t w[VEC];
+    static_assert(VEC % 4 == 0, "");
+    typedef float vec_t __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) w[k] = f2u(f[k]);
-    gst_words(base, byte_off, w);
+    for (int k = 0; k < VEC / 4; ++k) {
+        const vec_t v = {f[4 * k], f[4 * k + 1], f[4 * k + 2], f[4 * k + 3]};
+        *(__attribute__((address_space(1))) vec_t*)(base + byte_off + 16u * k) = v;
+    }
 }
 __device__ __forceinline__ uint32_t gld_u16(gcptr_t base, uint32_t byte_off) {
     return *(const __attribute__((address_space(1))) uint16_t*)(base + byte_off);
@@ -837,8 +852,111 @@ hipError_t launch_step(int kind, bool direct, bool split, bool quant, const Step
 
 // -------------------------------------------------------- standalone codecs --
 //
-// Not on the per-step path (used at initialisation, for inspection and by tests):
-// one lane per element / per group, plain global accesses.
+// Not on the per-step path (used at initialisation, for inspection and by tests).  They share
+// the lane layout of the step kernels: a workgroup of 256 lanes covers a tile of 2048 consecutive
+// elements, 8 per lane, so that BF16 data moves as 128-bit, byte data as 64-bit and FP32 data as
+// two 128-bit accesses per lane, and a quantisation group is a lane quad.  The arithmetic is the
+// plain exact form of each operation.
+
+constexpr int kCodecVec = 8;
+constexpr int kCodecTile = kThreads * kCodecVec;
+
+struct LanePos {
+    int64_t tile0;       // first element of the workgroup's tile (wave-uniform)
+    uint32_t lane_el;    // first element of the lane inside the tile
+    int cnt;             // elements of the lane that exist: kCodecVec, or fewer at the ragged end
+};
+__device__ __forceinline__ LanePos lane_pos_at(int64_t tile0, int64_t n) {
+    LanePos L;
+    L.tile0 = tile0;
+    L.lane_el = (uint32_t)threadIdx.x * kCodecVec;
+    const int64_t rem = n - tile0;
+    const int tile_cnt = rem >= kCodecTile ? kCodecTile : (rem > 0 ? (int)rem : 0);
+    const int left = tile_cnt - (int)L.lane_el;
+    L.cnt = left >= kCodecVec ? kCodecVec : (left > 0 ? left : 0);
+    return L;
+}
+__device__ __forceinline__ LanePos lane_pos(int64_t n) { return lane_pos_at((int64_t)blockIdx.x * kCodecTile, n); }
+
+// Eight elements of a lane from / to an array of 4-, 2- or 1-byte elements.  Full lanes use
+// vector accesses; ragged lanes go element by element and read missing elements as zero.
+__device__ __forceinline__ void load_f32(float (&f)[kCodecVec], const float* p, const LanePos& L) {
+    if (L.cnt == kCodecVec) {
+        gld_floats(f, gbase(p, 4 * L.tile0), 4u * block_local(L.lane_el));
+    } else {
+        const float* q = p + L.tile0 + L.lane_el;
+#pragma unroll
+        for (int i = 0; i < kCodecVec; ++i) f[i] = (i < L.cnt) ? q[i] : 0.0f;
+    }
+}
+__device__ __forceinline__ void store_f32(float* p, const LanePos& L, const float (&f)[kCodecVec]) {
+    if (L.cnt == kCodecVec) {
+        gst_floats(gbase(p, 4 * L.tile0), 4u * block_local(L.lane_el), f);
+    } else {
+        float* q = p + L.tile0 + L.lane_el;
+#pragma unroll
+        for (int i = 0; i < kCodecVec; ++i) if (i < L.cnt) q[i] = f[i];
+    }
+}
+__device__ __forceinline__ void load_u16(uint32_t (&w)[kCodecVec / 2], const void* p, const LanePos& L) {
+    if (L.cnt == kCodecVec) {
+        gld_words(w, gbase(p, 2 * L.tile0), 2u * block_local(L.lane_el));
+    } else {
+        const uint16_t* q = reinterpret_cast<const uint16_t*>(p) + L.tile0 + L.lane_el;
+#pragma unroll
+        for (int j = 0; j < kCodecVec / 2; ++j) {
+            const uint32_t lo = (2 * j < L.cnt) ? q[2 * j] : 0u, hi = (2 * j + 1 < L.cnt) ? q[2 * j + 1] : 0u;
+            w[j] = lo | (hi << 16);
+        }
+    }
+}
+__device__ __forceinline__ void store_u16(void* p, const LanePos& L, const uint32_t (&w)[kCodecVec / 2]) {
+    if (L.cnt == kCodecVec) {
+        gst_words(gbase(p, 2 * L.tile0), 2u * block_local(L.lane_el), w);
+    } else {
+        uint16_t* q = reinterpret_cast<uint16_t*>(p) + L.tile0 + L.lane_el;
+#pragma unroll
+        for (int i = 0; i < kCodecVec; ++i) if (i < L.cnt) q[i] = (uint16_t)(w[i >> 1] >> (16 * (i & 1)));
+    }
+}
+__device__ __forceinline__ void load_u8(uint32_t (&w)[kCodecVec / 4], const void* p, const LanePos& L) {
+    if (L.cnt == kCodecVec) {
+        gld_words(w, gbase(p, L.tile0), block_local(L.lane_el));
+    } else {
+        const uint8_t* q = reinterpret_cast<const uint8_t*>(p) + L.tile0 + L.lane_el;
+#pragma unroll
+        for (int j = 0; j < kCodecVec / 4; ++j) {
+            uint32_t t = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) if (4 * j + k < L.cnt) t |= (uint32_t)q[4 * j + k] << (8 * k);
+            w[j] = t;
+        }
+    }
+}
+__device__ __forceinline__ void store_u8(void* p, const LanePos& L, const uint32_t (&w)[kCodecVec / 4]) {
+    if (L.cnt == kCodecVec) {
+        gst_words(gbase(p, L.tile0), block_local(L.lane_el), w);
+    } else {
+        uint8_t* q = reinterpret_cast<uint8_t*>(p) + L.tile0 + L.lane_el;
+#pragma unroll
+        for (int i = 0; i < kCodecVec; ++i) if (i < L.cnt) q[i] = (uint8_t)(w[i >> 2] >> (8 * (i & 3)));
+    }
+}
+__device__ __forceinline__ uint32_t byte_of(const uint32_t (&w)[kCodecVec / 4], int i) {
+    return (w[i >> 2] >> (8 * (i & 3))) & 0xffu;
+}
+__device__ __forceinline__ uint32_t half_of(const uint32_t (&w)[kCodecVec / 2], int i) {
+    return (w[i >> 1] >> (16 * (i & 1))) & 0xffffu;
+}
+// Eight small integers -> packed bytes / packed 16-bit fields (two's complement).
+__device__ __forceinline__ void pack_u8(uint32_t (&w)[kCodecVec / 4], const uint32_t (&c)[kCodecVec]) {
+#pragma unroll
+    for (int j = 0; j < kCodecVec / 4; ++j) w[j] = pack_low_bytes(c[4 * j], c[4 * j + 1], c[4 * j + 2], c[4 * j + 3]);
+}
+__device__ __forceinline__ void pack_u16(uint32_t (&w)[kCodecVec / 2], const uint32_t (&c)[kCodecVec]) {
+#pragma unroll
+    for (int j = 0; j < kCodecVec / 2; ++j) w[j] = (c[2 * j] & 0xffffu) | (c[2 * j + 1] << 16);
+}
 
 // C and C^-1 for a correction of N = 127 (INT8) or N = 32767 (INT16) levels per side,
 // written out plainly (Algorithm 1; the fused kernels use table-driven forms of the N = 127 case).
@@ -861,20 +979,47 @@ __device__ __forceinline__ float reconstruct_n(uint32_t b, int rho) {
 
 template <int N, typename RHO>
 __global__ __launch_bounds__(kThreads) void split_kernel(const float* theta, uint16_t* param, RHO* rho, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n) return;
-    const float t = theta[i];
-    const uint32_t b = bf16_pack(t, 0.0f) & 0xffffu;
-    param[i] = (uint16_t)b;
-    rho[i] = (RHO)split_rho<N>(t, b);
+    const LanePos L = lane_pos(n);
+    if (L.cnt == 0) return;
+    float th[kCodecVec];
+    load_f32(th, theta, L);
+    uint32_t pw[kCodecVec / 2], c[kCodecVec];
+#pragma unroll
+    for (int j = 0; j < kCodecVec / 2; ++j) pw[j] = bf16_pack(th[2 * j], th[2 * j + 1]);
+#pragma unroll
+    for (int i = 0; i < kCodecVec; ++i) c[i] = (uint32_t)split_rho<N>(th[i], half_of(pw, i));
+    store_u16(param, L, pw);
+    if constexpr (sizeof(RHO) == 1) {
+        uint32_t rw[kCodecVec / 4];
+        pack_u8(rw, c);
+        store_u8(rho, L, rw);
+    } else {
+        uint32_t rw[kCodecVec / 2];
+        pack_u16(rw, c);
+        store_u16(rho, L, rw);
+    }
 }
 
 template <int N, typename RHO>
 __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const uint16_t* param, const RHO* rho, float* theta,
                                                                int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n) return;
-    theta[i] = reconstruct_n<N>(param[i], (int)rho[i]);
+    const LanePos L = lane_pos(n);
+    if (L.cnt == 0) return;
+    uint32_t pw[kCodecVec / 2];
+    load_u16(pw, param, L);
+    float th[kCodecVec];
+    if constexpr (sizeof(RHO) == 1) {
+        uint32_t rw[kCodecVec / 4];
+        load_u8(rw, rho, L);
+#pragma unroll
+        for (int i = 0; i < kCodecVec; ++i) th[i] = reconstruct_n<N>(half_of(pw, i), (int)(int8_t)byte_of(rw, i));
+    } else {
+        uint32_t rw[kCodecVec / 2];
+        load_u16(rw, rho, L);
+#pragma unroll
+        for (int i = 0; i < kCodecVec; ++i) th[i] = reconstruct_n<N>(half_of(pw, i), (int)(int16_t)half_of(rw, i));
+    }
+    store_f32(theta, L, th);
 }
 
 // The data-independent experiment of Section 4.4: FP32 bit patterns first, first + stride, ...
@@ -946,19 +1091,23 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(uint64_t first, uint64_
     }
 }
 
-// Group quantizers written out plainly, one lane per group of 32.  LINEAR drops the compander
-// (the "standard scaled integer quantization" baseline of Section 4.5): momentum code =
-// Round(127 m / s), variance code = Round(255 v / s) with s the group maximum of v itself.
+// Group quantizers written out plainly.  LINEAR drops the compander (the "standard scaled
+// integer quantization" baseline of Section 4.5): momentum code = Round(127 m / s), variance
+// code = Round(255 v / s) with s the group maximum of v itself.
+// quantize_lane: the eight codes of a lane and the FP16 scale bits of its group.  All four lanes of
+// a group must call it together; elements past the end are zero and do not raise the maximum.
+// The group maximum of sqrt(v) is the square root of the maximum of v (the root is monotone).
 template <bool VARIANCE, bool LINEAR>
-__device__ __forceinline__ uint32_t quantize_group(const float* x, int cnt, uint8_t* codes) {
+__device__ __forceinline__ uint32_t quantize_lane(const float (&x)[kCodecVec], uint32_t (&codes)[kCodecVec]) {
     float a = 0.0f;
-    for (int i = 0; i < cnt; ++i) {
-        const float t = VARIANCE ? (LINEAR ? x[i] : sqrtf(x[i])) : fabsf(x[i]);
-        a = fmaxf(a, t);
-    }
+#pragma unroll
+    for (int i = 0; i < kCodecVec; ++i) a = fmaxf(a, VARIANCE ? x[i] : fabsf(x[i]));
+    a = group_max<kCodecVec>(a);
+    if (VARIANCE && !LINEAR) a = sqrtf(a);
     float r;
     const uint32_t sbits = group_scale(a, &r);
-    for (int i = 0; i < cnt; ++i) {
+#pragma unroll
+    for (int i = 0; i < kCodecVec; ++i) {
         uint32_t c;
         if (!LINEAR) {
             c = VARIANCE ? v_code_exact(x[i], r) : m_code_exact(x[i], r);
@@ -967,7 +1116,7 @@ __device__ __forceinline__ uint32_t quantize_group(const float* x, int cnt, uint
         } else {
             c = round_to_int_bits(__builtin_amdgcn_fmed3f((x[i] * r) * 127.0f, -127.0f, 127.0f));
         }
-        codes[i] = (uint8_t)(c & 0xffu);
+        codes[i] = c & 0xffu;
     }
     return sbits;
 }
@@ -982,41 +1131,60 @@ __device__ __forceinline__ float dequantize_one(uint8_t q, float s) {
     return LINEAR ? z * s : (z / (2.0f - fabsf(z))) * s;
 }
 
+__device__ __forceinline__ bool group_leader(const LanePos& L) {
+    return (threadIdx.x & (kGroup / kCodecVec - 1)) == 0 && L.cnt > 0;
+}
+
 template <bool VARIANCE, bool LINEAR>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const float* x, uint8_t* q, uint16_t* scale,
                                                             int64_t n) {
-    const int64_t grp = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int64_t o = grp * kGroup;
-    if (o >= n) return;
-    const int cnt = (n - o < kGroup) ? (int)(n - o) : kGroup;
-    scale[grp] = (uint16_t)quantize_group<VARIANCE, LINEAR>(x + o, cnt, q + o);
+    const LanePos L = lane_pos(n);
+    float v[kCodecVec];
+    load_f32(v, x, L);
+    uint32_t codes[kCodecVec], w[kCodecVec / 4];
+    const uint32_t sbits = quantize_lane<VARIANCE, LINEAR>(v, codes);
+    pack_u8(w, codes);
+    if (L.cnt > 0) store_u8(q, L, w);
+    if (group_leader(L)) scale[(L.tile0 + L.lane_el) >> 5] = (uint16_t)sbits;
 }
 
 template <bool VARIANCE, bool LINEAR>
 __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* q, const uint16_t* scale, float* x,
                                                               int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n) return;
-    x[i] = dequantize_one<VARIANCE, LINEAR>(q[i], (float)__builtin_bit_cast(_Float16, scale[i >> 5]));
+    const LanePos L = lane_pos(n);
+    if (L.cnt == 0) return;
+    uint32_t w[kCodecVec / 4];
+    load_u8(w, q, L);
+    const float s = (float)__builtin_bit_cast(_Float16, scale[(L.tile0 + L.lane_el) >> 5]);
+    float v[kCodecVec];
+#pragma unroll
+    for (int i = 0; i < kCodecVec; ++i) v[i] = dequantize_one<VARIANCE, LINEAR>((uint8_t)byte_of(w, i), s);
+    store_f32(x, L, v);
 }
 
 // Quantisation error of a buffer (Section 4.5): sums[0] += sum (Q^-1(Q(x)) - x)^2 and
-// sums[1] += sum x^2, in double; one lane per group, wavefront reduction, one atomic per wavefront.
+// sums[1] += sum x^2, in double.  A workgroup walks over tiles blockIdx.x, blockIdx.x + gridDim.x,
+// ... and adds its partial sums once at the end (wavefront reduction, one atomic pair per
+// wavefront), so the number of atomics on the two accumulators stays small.
 template <bool VARIANCE, bool LINEAR>
 __global__ __launch_bounds__(kThreads) void nmse_kernel(const float* x, int64_t n, double* sums) {
-    const int64_t grp = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int64_t o = grp * kGroup;
+    const int64_t n_tiles = (n + kCodecTile - 1) / kCodecTile;
     double err = 0.0, ref = 0.0;
-    if (o < n) {
-        const int cnt = (n - o < kGroup) ? (int)(n - o) : kGroup;
-        uint8_t codes[kGroup];
-        const uint32_t sbits = quantize_group<VARIANCE, LINEAR>(x + o, cnt, codes);
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const LanePos L = lane_pos_at(tile * kCodecTile, n);
+        float v[kCodecVec];
+        load_f32(v, x, L);
+        uint32_t codes[kCodecVec];
+        const uint32_t sbits = quantize_lane<VARIANCE, LINEAR>(v, codes);
         const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)sbits);
-        for (int i = 0; i < cnt; ++i) {
-            const double xi = (double)x[o + i];
-            const double d = (double)dequantize_one<VARIANCE, LINEAR>(codes[i], s) - xi;
-            err += d * d;
-            ref += xi * xi;
+#pragma unroll
+        for (int i = 0; i < kCodecVec; ++i) {
+            if (i < L.cnt) {
+                const double xi = (double)v[i];
+                const double d = (double)dequantize_one<VARIANCE, LINEAR>((uint8_t)codes[i], s) - xi;
+                err += d * d;
+                ref += xi * xi;
+            }
         }
     }
     for (int off = 32; off > 0; off >>= 1) {
@@ -1029,18 +1197,20 @@ __global__ __launch_bounds__(kThreads) void nmse_kernel(const float* x, int64_t 
     }
 }
 
-static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads); }
+constexpr unsigned kNmseMaxBlocks = 256 * 8;     // eight resident workgroups per compute unit
+
+static inline unsigned tiles_for(int64_t n) { return (unsigned)((n + kCodecTile - 1) / kCodecTile); }
 
 void launch_split(int bits, const float* theta, void* param, void* rho, int64_t n, hipStream_t s) {
-    if (bits == 8) hipLaunchKernelGGL((split_kernel<127, int8_t>), dim3(blocks_for(n)), dim3(kThreads), 0, s, theta,
+    if (bits == 8) hipLaunchKernelGGL((split_kernel<127, int8_t>), dim3(tiles_for(n)), dim3(kThreads), 0, s, theta,
                                       (uint16_t*)param, (int8_t*)rho, n);
-    else hipLaunchKernelGGL((split_kernel<32767, int16_t>), dim3(blocks_for(n)), dim3(kThreads), 0, s, theta,
+    else hipLaunchKernelGGL((split_kernel<32767, int16_t>), dim3(tiles_for(n)), dim3(kThreads), 0, s, theta,
                             (uint16_t*)param, (int16_t*)rho, n);
 }
 void launch_reconstruct(int bits, const void* param, const void* rho, float* theta, int64_t n, hipStream_t s) {
-    if (bits == 8) hipLaunchKernelGGL((reconstruct_kernel<127, int8_t>), dim3(blocks_for(n)), dim3(kThreads), 0, s,
+    if (bits == 8) hipLaunchKernelGGL((reconstruct_kernel<127, int8_t>), dim3(tiles_for(n)), dim3(kThreads), 0, s,
                                       (const uint16_t*)param, (const int8_t*)rho, theta, n);
-    else hipLaunchKernelGGL((reconstruct_kernel<32767, int16_t>), dim3(blocks_for(n)), dim3(kThreads), 0, s,
+    else hipLaunchKernelGGL((reconstruct_kernel<32767, int16_t>), dim3(tiles_for(n)), dim3(kThreads), 0, s,
                             (const uint16_t*)param, (const int16_t*)rho, theta, n);
 }
 hipError_t launch_sweep(int bits, uint64_t first, uint64_t stride, uint64_t count, double* stats, hipStream_t s) {
@@ -1053,12 +1223,12 @@ hipError_t launch_sweep(int bits, uint64_t first, uint64_t stride, uint64_t coun
 template <bool VARIANCE, bool LINEAR>
 static void launch_codec(int op, const void* in, const uint16_t* scale_in, void* out, uint16_t* scale_out, int64_t n,
                          double* sums, hipStream_t s) {
-    const int64_t groups = (n + kGroup - 1) / kGroup;
-    if (op == 0) hipLaunchKernelGGL((quantize_kernel<VARIANCE, LINEAR>), dim3(blocks_for(groups)), dim3(kThreads), 0, s,
+    if (op == 0) hipLaunchKernelGGL((quantize_kernel<VARIANCE, LINEAR>), dim3(tiles_for(n)), dim3(kThreads), 0, s,
                                     (const float*)in, (uint8_t*)out, scale_out, n);
-    else if (op == 1) hipLaunchKernelGGL((dequantize_kernel<VARIANCE, LINEAR>), dim3(blocks_for(n)), dim3(kThreads), 0, s,
+    else if (op == 1) hipLaunchKernelGGL((dequantize_kernel<VARIANCE, LINEAR>), dim3(tiles_for(n)), dim3(kThreads), 0, s,
                                          (const uint8_t*)in, scale_in, (float*)out, n);
-    else hipLaunchKernelGGL((nmse_kernel<VARIANCE, LINEAR>), dim3(blocks_for(groups)), dim3(kThreads), 0, s,
+    else hipLaunchKernelGGL((nmse_kernel<VARIANCE, LINEAR>), dim3(tiles_for(n) < kNmseMaxBlocks ? tiles_for(n) : kNmseMaxBlocks),
+                            dim3(kThreads), 0, s,
                             (const float*)in, n, sums);
 }
 static void dispatch_codec(bool variance, bool linear, int op, const void* in, const uint16_t* scale_in, void* out,
@@ -1088,13 +1258,10 @@ void launch_nmse(bool variance, bool linear, const float* x, int64_t n, double* 
 // the compressed layout: COMPRESS applies C, Q_m, Q_v (Algorithms 1-3) in one pass over a list;
 // the other direction applies the inverses.  Written with the plain exact forms; same chunk
 // table and lane layout (8 elements per lane, a lane quad per group) as the step kernels.
-constexpr int kConvVec = 8;
-constexpr int kConvThreads = 256;
+static_assert(kCodecTile == kConvChunkElems, "the conversion chunk table is built for tiles of this size");
 
 template <bool HAS_V, bool COMPRESS, bool DIRECT>
-__global__ __launch_bounds__(kConvThreads) void convert_kernel(StepArgs a) {
-    constexpr int VEC = kConvVec;
-    const int tid = (int)threadIdx.x;
+__global__ __launch_bounds__(kThreads) void convert_kernel(StepArgs a) {
     TensorDev T;
     int64_t chunk;
     if (DIRECT) {
@@ -1105,63 +1272,64 @@ __global__ __launch_bounds__(kConvThreads) void convert_kernel(StepArgs a) {
         T = a.tensors[ck.x];
         chunk = (int64_t)ck.y;
     }
-    const int64_t off = chunk * (int64_t)(kConvThreads * VEC) + (int64_t)tid * VEC;
-    const int64_t left = T.numel - off;
-    const int cnt = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
-    uint16_t* param = reinterpret_cast<uint16_t*>(T.param);
+    const LanePos L = lane_pos_at(chunk * (int64_t)kCodecTile, T.numel);
+    const int64_t group = (L.tile0 + L.lane_el) >> 5;
     if (COMPRESS) {
-        float th[VEC], m[VEC], v[VEC];
+        // every lane of a group takes part in the group maxima, also those past the end
+        float th[kCodecVec], m[kCodecVec], v[kCodecVec];
+        load_f32(th, T.theta32, L);
+        load_f32(m, T.m32, L);
+        uint32_t pw[kCodecVec / 2], c[kCodecVec], w[kCodecVec / 4];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) {
-            th[i] = (i < cnt) ? T.theta32[off + i] : 0.0f;
-            m[i] = (i < cnt) ? T.m32[off + i] : 0.0f;
-            v[i] = (HAS_V && i < cnt) ? T.v32[off + i] : 0.0f;
-        }
-        float amax_m = 0.0f, amax_v = 0.0f;
+        for (int j = 0; j < kCodecVec / 2; ++j) pw[j] = bf16_pack(th[2 * j], th[2 * j + 1]);
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) {
-            amax_m = fmaxf(amax_m, fabsf(m[i]));
-            amax_v = fmaxf(amax_v, v[i]);
+        for (int i = 0; i < kCodecVec; ++i) c[i] = (uint32_t)split_rho<127>(th[i], half_of(pw, i));
+        if (L.cnt > 0) {
+            store_u16(T.param, L, pw);
+            pack_u8(w, c);
+            store_u8(T.rho, L, w);
         }
-        amax_m = group_max<VEC>(amax_m);          // every lane takes part, also those past the end
-        float r_m, r_v = 0.0f;
-        const uint32_t ms = group_scale(amax_m, &r_m);
-        uint32_t vs = 0;
+        const uint32_t ms = quantize_lane<false, false>(m, c);
+        if (L.cnt > 0) {
+            pack_u8(w, c);
+            store_u8(T.m_q, L, w);
+        }
+        if (group_leader(L)) T.m_scale[group] = (uint16_t)ms;
         if (HAS_V) {
-            amax_v = group_max<VEC>(amax_v);
-            vs = group_scale(sqrtf(amax_v), &r_v);   // max of sqrt = sqrt of max
-        }
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) {
-            if (i < cnt) {
-                const uint32_t b = bf16_pack(th[i], 0.0f) & 0xffffu;
-                param[off + i] = (uint16_t)b;
-                T.rho[off + i] = (int8_t)split_rho<127>(th[i], b);
-                T.m_q[off + i] = (int8_t)(m_code_exact(m[i], r_m) & 0xffu);
-                if (HAS_V) T.v_q[off + i] = (uint8_t)(v_code_exact(v[i], r_v) & 0xffu);
+            load_f32(v, T.v32, L);
+            const uint32_t vs = quantize_lane<true, false>(v, c);
+            if (L.cnt > 0) {
+                pack_u8(w, c);
+                store_u8(T.v_q, L, w);
             }
-        }
-        if ((tid & (kGroup / VEC - 1)) == 0 && cnt > 0) {
-            T.m_scale[off >> 5] = (uint16_t)ms;
-            if (HAS_V) T.v_scale[off >> 5] = (uint16_t)vs;
+            if (group_leader(L)) T.v_scale[group] = (uint16_t)vs;
         }
     } else {
-        if (cnt == 0) return;
-        const float s_m = (float)__builtin_bit_cast(_Float16, T.m_scale[off >> 5]);
-        const float s_v = HAS_V ? (float)__builtin_bit_cast(_Float16, T.v_scale[off >> 5]) : 0.0f;
+        if (L.cnt == 0) return;
+        uint32_t pw[kCodecVec / 2], w[kCodecVec / 4];
+        float f[kCodecVec];
+        load_u16(pw, T.param, L);
+        load_u8(w, T.rho, L);
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) {
-            if (i < cnt) {
-                T.theta32[off + i] = reconstruct_n<127>(param[off + i], (int)T.rho[off + i]);
-                T.m32[off + i] = dequantize_one<false, false>((uint8_t)T.m_q[off + i], s_m);
-                if (HAS_V) T.v32[off + i] = dequantize_one<true, false>(T.v_q[off + i], s_v);
-            }
+        for (int i = 0; i < kCodecVec; ++i) f[i] = reconstruct_n<127>(half_of(pw, i), (int)(int8_t)byte_of(w, i));
+        store_f32(T.theta32, L, f);
+        const float s_m = (float)__builtin_bit_cast(_Float16, T.m_scale[group]);
+        load_u8(w, T.m_q, L);
+#pragma unroll
+        for (int i = 0; i < kCodecVec; ++i) f[i] = dequantize_one<false, false>((uint8_t)byte_of(w, i), s_m);
+        store_f32(T.m32, L, f);
+        if (HAS_V) {
+            const float s_v = (float)__builtin_bit_cast(_Float16, T.v_scale[group]);
+            load_u8(w, T.v_q, L);
+#pragma unroll
+            for (int i = 0; i < kCodecVec; ++i) f[i] = dequantize_one<true, false>((uint8_t)byte_of(w, i), s_v);
+            store_f32(T.v32, L, f);
         }
     }
 }
 
 hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
-    const dim3 grid((unsigned)n_blocks), block(kConvThreads);
+    const dim3 grid((unsigned)n_blocks), block(kThreads);
 #define FO_CONV(HV, CP, DR) hipLaunchKernelGGL((convert_kernel<HV, CP, DR>), grid, block, 0, s, a)
     if (has_v) {
         if (compress) { if (direct) FO_CONV(true, true, true); else FO_CONV(true, true, false); }

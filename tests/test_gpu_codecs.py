@@ -112,6 +112,58 @@ def test_dequantize_every_code_and_scale():
                           oracle.dequantize_variance(q.astype(np.uint8), s).view(np.uint32))
 
 
+@pytest.mark.parametrize("n", [1, 7, 9, 33, 2047, 2049, 4096 * 3 + 17])
+def test_ragged_ends_write_nothing_past_the_end(n):
+    # every output buffer carries 64 sentinel elements behind the n the call is given
+    pad = 64
+    rng = np.random.default_rng(300 + n)
+    x = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    xd = _dev(x)
+
+    def guarded(dtype, fill):
+        return torch.full((n + pad,), fill, dtype=dtype, device="cuda")
+
+    def tail_intact(t, fill):
+        return bool((t[n:] == fill).all().item())
+
+    p = guarded(torch.bfloat16, 3.0); r = guarded(torch.int8, 77); r16 = guarded(torch.int16, 7777)
+    fo.split_weights(xd, p[:n], r[:n])
+    thp, rho = oracle.split(x)
+    assert np.array_equal(bits16(p[:n]), thp) and np.array_equal(r[:n].cpu().numpy(), rho)
+    assert tail_intact(p, 3.0) and tail_intact(r, 77)
+    p2 = guarded(torch.bfloat16, 3.0)
+    fo.split_weights_i16(xd, p2[:n], r16[:n])
+    thp16, rho16 = oracle.split(x, 32767)
+    assert np.array_equal(bits16(p2[:n]), thp16) and np.array_equal(r16[:n].cpu().numpy(), rho16)
+    assert tail_intact(p2, 3.0) and tail_intact(r16, 7777)
+    th = guarded(torch.float32, 5.0)
+    fo.reconstruct_weights(p[:n], r[:n], th[:n])
+    assert np.array_equal(th[:n].cpu().numpy().view(np.uint32), oracle.reconstruct(thp, rho).view(np.uint32))
+    assert tail_intact(th, 5.0)
+    fo.reconstruct_weights_i16(p2[:n], r16[:n], th[:n])
+    assert np.array_equal(th[:n].cpu().numpy().view(np.uint32), oracle.reconstruct(thp16, rho16, 32767).view(np.uint32))
+    assert tail_intact(th, 5.0)
+
+    ng = (n + 31) // 32
+    q = guarded(torch.int8, 55); s = torch.full((ng + pad,), 9.0, dtype=torch.float16, device="cuda")
+    fo.quantize_momentum(xd, q[:n], s[:ng])
+    wq, ws = oracle.quantize_momentum(x)
+    assert np.array_equal(q[:n].cpu().numpy(), wq) and np.array_equal(bits16(s[:ng]), ws)
+    assert tail_intact(q, 55) and bool((s[ng:] == 9.0).all().item())
+    fo.dequantize_momentum(q[:n], s[:ng], th[:n])
+    assert np.array_equal(th[:n].cpu().numpy().view(np.uint32), oracle.dequantize_momentum(wq, ws).view(np.uint32))
+    assert tail_intact(th, 5.0)
+    v = (x * x).astype(np.float32)
+    qu = guarded(torch.uint8, 200)
+    fo.quantize_variance(_dev(v), qu[:n], s[:ng])
+    wq, ws = oracle.quantize_variance(v)
+    assert np.array_equal(qu[:n].cpu().numpy(), wq) and np.array_equal(bits16(s[:ng]), ws)
+    assert tail_intact(qu, 200) and bool((s[ng:] == 9.0).all().item())
+    fo.dequantize_variance(qu[:n], s[:ng], th[:n])
+    assert np.array_equal(th[:n].cpu().numpy().view(np.uint32), oracle.dequantize_variance(wq, ws).view(np.uint32))
+    assert tail_intact(th, 5.0)
+
+
 def test_empty_inputs_are_noops():
     e32 = torch.empty(0, dtype=torch.float32, device="cuda")
     fo.split_weights(e32, torch.empty(0, dtype=torch.bfloat16, device="cuda"), torch.empty(0, dtype=torch.int8, device="cuda"))

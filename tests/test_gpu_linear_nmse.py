@@ -72,6 +72,19 @@ def test_quantisation_error_on_synthetic_trajectories(dist):
               f"variance companded {r[('variance', False)]:.3e} linear {r[('variance', True)]:.3e}")
 
 
+def test_nmse_of_a_buffer_larger_than_one_pass_of_the_grid():
+    # 2048 workgroups x 2048 elements is one pass; this buffer needs three passes and has a ragged end
+    n = 2 * 2048 * 2048 + 2048 * 700 + 5
+    rng = np.random.default_rng(77)
+    x = (rng.standard_normal(n) * np.repeat(10.0 ** rng.uniform(-6, -2, (n + 31) // 32), 32)[:n]).astype(np.float32)
+    err, ref = fo.quantization_nmse("momentum", False, _dev(x))
+    q, s = oracle.quantize_momentum(x)
+    want = oracle.nmse(x, oracle.dequantize_momentum(q, s))
+    x64 = x.astype(np.float64)
+    assert ref == pytest.approx(float(np.dot(x64, x64)), rel=1e-12)
+    assert err / ref == pytest.approx(want, rel=1e-9)
+
+
 def test_nmse_argument_validation_and_empty():
     assert fo.quantization_nmse("momentum", False, torch.empty(0, dtype=torch.float32, device="cuda")) == (0.0, 0.0)
     L = fo.load_library()
