@@ -37,6 +37,7 @@ WORKLOADS = {
     "gpt2_lion": ("lion", "gpt2_small", "normal", None),
     "resnet50_adamw": ("adamw", "resnet50", "student3", 1e-3),
     "flat_adamw": ("adamw", "flat_tensor", "normal", 1e-3),
+    "llama31_8b_flat_adamw": ("adamw", "llama31_8b_flat", "normal", 1e-4),
 }
 
 
@@ -55,6 +56,8 @@ def parse_args():
                          "oquant: FP32 weights + 8-bit states; ref: plain FP32 optimizer (BF16 gradients). "
                          "The last three are the ablation entry points (fused mode only).")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe", action="store_true",
+                    help="skip the timing of the arithmetic-free stream probe (same traffic as the step)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -130,6 +133,10 @@ def cpu_baseline(W, specs, kind, hp, dist, scale, seed, target_seconds):
                 break
             sample.append((i, s)); tot += s.numel
         what = f"first {len(sample)} tensors of the list"
+        if len(sample) == 1 and sample[0][1].numel > (1 << 26):
+            s0 = sample[0][1]
+            sample = [(0, W.ParamSpec(s0.name, (1 << 26,), s0.role))]
+            what = "leading 2^26 elements of the single tensor"
     n = sum(s.numel for _, s in sample)
     states, grads = [], []
     for i, s in sample:
@@ -268,6 +275,18 @@ def main():
         algo_bytes = 2.0 * payload                          # every payload byte is read once and written once
     achieved = algo_bytes / (ms_per_step * 1e-3) / 1e9
     traffic = None if (release or ckpt or args.variant != "flash") else read_traffic(kind, args.workload)
+    # the memory ceiling of this access pattern: the same bytes through the same launch shape with no
+    # arithmetic (fused flash mode only; run after the timed region, on the same list)
+    probe = None
+    if args.variant == "flash" and args.mode == "fused" and not args.no_probe:
+        fo.stream_probe(kind, tl)
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record(stream)
+        for _ in range(args.steps):
+            fo.stream_probe(kind, tl)
+        p1.record(stream)
+        torch.cuda.synchronize()
+        probe = algo_bytes / (p0.elapsed_time(p1) / args.steps * 1e-3) / 1e9
     out = {
         "metric": "optimizer_step_params_per_sec", "value": value, "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -283,7 +302,9 @@ def main():
                      "kernel": ("fo::copy_kernel" if ckpt else
                                 f"fo::step_kernel<{['adamw', 'sgd', 'lion'].index(kind)}, ..., {'true' if release else 'false'}>"),
                      "algorithmic_bytes_per_launch": algo_bytes if not release else None,
-                     "bytes_per_param": bytes_per_param},
+                     "bytes_per_param": bytes_per_param,
+                     "same_traffic_without_arithmetic": probe,
+                     "frac_of_that": (achieved / probe) if probe else None},
     }
     if not args.no_cpu_baseline and not ckpt and args.variant == "flash":
         del bufs, tl

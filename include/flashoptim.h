@@ -145,6 +145,15 @@ int flashoptim_lion_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tenso
 int flashoptim_compress_state(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors, void* stream);
 int flashoptim_decompress_state(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors, void* stream);
 
+/* ---- measurement aid (no passage of the paper: the memory ceiling of the step's access pattern) ----
+ * stream_probe: reads every array a step of this kind reads (gradients included) and writes every
+ * array it writes back UNCHANGED, through the same launch shape and access instructions as the step,
+ * with no arithmetic.  Timing it gives the rate the memory system delivers for exactly the step's
+ * traffic (12.25 B/param for AdamW, 10.125 for SGD and Lion), to set the step's own rate against.
+ * Same arguments, validation, stream ordering and errors as the *_step calls; lr and weight_decay
+ * are ignored; no state changes. */
+int flashoptim_stream_probe(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, void* stream);
+
 /* ---- weight splitting (Section 3.1, Algorithm 1, N = 127) --------------------------
  * split:       theta (FP32) -> theta' = BF16 round-to-nearest-even, rho = Round(e / (ULP(theta')/2) * 127)
  *              Used once at the start of training (initialisation of Algorithm 4).

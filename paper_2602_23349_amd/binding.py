@@ -26,7 +26,7 @@ EXPORTED_SYMBOLS = [
     "flashoptim_reconstruction_sweep",
     "flashoptim_adamw_step_ex", "flashoptim_sgd_step_ex", "flashoptim_lion_step_ex",
     "flashoptim_quantize_state", "flashoptim_dequantize_state", "flashoptim_quantization_nmse",
-    "flashoptim_compress_state", "flashoptim_decompress_state",
+    "flashoptim_compress_state", "flashoptim_decompress_state", "flashoptim_stream_probe",
 ]
 
 
@@ -90,6 +90,7 @@ def load_library():
         getattr(L, name).argtypes = [vp, vp, vp, i64, vp]
     L.flashoptim_compress_state.argtypes = [i32, C.POINTER(_TensorEx), i64, vp]
     L.flashoptim_decompress_state.argtypes = [i32, C.POINTER(_TensorEx), i64, vp]
+    L.flashoptim_stream_probe.argtypes = [i32, C.POINTER(_Tensor), i64, vp]
     L.flashoptim_quantize_state.argtypes = [i32, i32, vp, vp, vp, i64, vp]
     L.flashoptim_dequantize_state.argtypes = [i32, i32, vp, vp, vp, i64, vp]
     L.flashoptim_quantization_nmse.argtypes = [i32, i32, vp, i64, C.POINTER(C.c_double), vp]
@@ -254,6 +255,12 @@ def lion_step(tensors, beta1, beta2, stream=None):
     tl = _as_list(tensors)
     hp = _LionHp(beta1, beta2)
     _check(load_library().flashoptim_lion_step(tl.array, tl.n, C.byref(hp), _stream(stream)), "flashoptim_lion_step")
+
+
+def stream_probe(kind, tensors, stream=None):
+    """Moves the bytes of one step of `kind` over the list with no arithmetic (state unchanged)."""
+    tl = _as_list(tensors)
+    _check(load_library().flashoptim_stream_probe(KIND[kind], tl.array, tl.n, _stream(stream)), "flashoptim_stream_probe")
 
 
 def split_weights(theta, param_bf16, rho, stream=None):

@@ -64,8 +64,8 @@ struct Plan {
     int device = 0;
     void* d_table = nullptr;       // TensorDev[] or CopySegment[]
     size_t table_bytes = 0;
-    uint2* d_chunks = nullptr;
-    int64_t n_chunks = 0;
+    void* d_index = nullptr;       // uint32 coarse table (steps, conversions) or uint2 chunk table (copies)
+    int64_t n_chunks = 0;          // workgroups of a launch over this plan
     std::string uploaded;          // bytes of the table the device currently holds
     Staging ring[4];
     int next_slot = 0;
@@ -86,8 +86,8 @@ void destroy_plan(Plan& p) {
         s = Staging();
     }
     if (p.d_table) (void)hipFree(p.d_table);
-    if (p.d_chunks) (void)hipFree(p.d_chunks);
-    p.d_table = nullptr; p.d_chunks = nullptr;
+    if (p.d_index) (void)hipFree(p.d_index);
+    p.d_table = nullptr; p.d_index = nullptr;
     (void)hipSetDevice(cur);
 }
 
@@ -110,8 +110,9 @@ int upload_table(Plan& p, const void* src, size_t bytes, hipStream_t stream) {
     return FLASHOPTIM_OK;
 }
 
-// Finds or creates the plan for `key`.  `chunks` is consumed only on creation.
-int get_plan(const std::string& key, size_t table_bytes, const std::vector<uint2>& chunks, Plan** out) {
+// Finds or creates the plan for `key`.  The index table is consumed only on creation.
+int get_plan(const std::string& key, size_t table_bytes, const void* index, size_t index_bytes, int64_t n_chunks,
+             Plan** out) {
     auto it = g_index.find(key);
     if (it != g_index.end()) {
         g_plans.splice(g_plans.begin(), g_plans, it->second);
@@ -121,11 +122,11 @@ int get_plan(const std::string& key, size_t table_bytes, const std::vector<uint2
     Plan p;
     FO_HIP(hipGetDevice(&p.device));
     p.table_bytes = table_bytes;
-    p.n_chunks = (int64_t)chunks.size();
+    p.n_chunks = n_chunks;
     hipError_t e = hipMalloc(&p.d_table, table_bytes);
-    if (e == hipSuccess) e = hipMalloc((void**)&p.d_chunks, chunks.size() * sizeof(uint2));
-    // one-time, blocking upload of the chunk table (it never changes for this list)
-    if (e == hipSuccess) e = hipMemcpy(p.d_chunks, chunks.data(), chunks.size() * sizeof(uint2), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMalloc(&p.d_index, index_bytes);
+    // one-time, blocking upload of the index table (it never changes for this list)
+    if (e == hipSuccess) e = hipMemcpy(p.d_index, index, index_bytes, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;
         (void)hipGetLastError();
@@ -215,12 +216,13 @@ int to_dev_ex(const flashoptim_tensor_ex* t, int64_t n, bool has_v, bool split, 
     return FLASHOPTIM_OK;
 }
 
-// What a multi-tensor launch runs: an optimizer step, or a layout conversion.
-enum LiveOp { kOpStep = 0, kOpCompress = 1, kOpDecompress = 2 };
+// What a multi-tensor launch runs: an optimizer step, a layout conversion, or the stream probe.
+enum LiveOp { kOpStep = 0, kOpCompress = 1, kOpDecompress = 2, kOpProbe = 3 };
 
 hipError_t launch_op(LiveOp op, int kind, bool direct, bool split, bool quant, const StepArgs& a, int64_t blocks,
                      hipStream_t stream) {
     if (op == kOpStep) return fo::launch_step(kind, direct, split, quant, a, blocks, stream);
+    if (op == kOpProbe) return fo::launch_probe(kind, direct, a, blocks, stream);
     return fo::launch_convert(kind == FLASHOPTIM_ADAMW, op == kOpCompress, direct, a, blocks, stream);
 }
 
@@ -231,7 +233,7 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
     StepArgs a;
     std::memset(&a, 0, sizeof(a));
     a.c = c;
-    const int64_t ce = (op == kOpStep) ? fo::chunk_elems(kind) : fo::kConvChunkElems;
+    const int64_t ce = (op == kOpStep || op == kOpProbe) ? fo::chunk_elems(kind) : fo::kConvChunkElems;
     // one workgroup per chunk: the launch grid is a 31-bit count
     int64_t total_chunks = 0;
     for (const TensorDev& d : live) total_chunks += (d.numel + ce - 1) / ce;
@@ -257,16 +259,32 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
         append(key, &d.numel, sizeof(d.numel));
     }
 
-    std::lock_guard<std::mutex> lock(g_mu);
-    Plan* plan = nullptr;
-    std::vector<uint2> chunks;
-    if (g_index.find(key) == g_index.end()) {
-        for (size_t ti = 0; ti < live.size(); ++ti) {
-            const int64_t nc = (live[ti].numel + ce - 1) / ce;
-            for (int64_t ci = 0; ci < nc; ++ci) chunks.push_back(make_uint2((unsigned)ti, (unsigned)ci));
+    // tile ranges of the tensors (part of the device table) and the coarse workgroup -> tensor table
+    uint32_t shift = 0;
+    while ((total_chunks >> shift) > (int64_t)fo::kCoarseMaxEntries) ++shift;
+    {
+        int64_t first = 0;
+        for (TensorDev& d : live) {
+            d.first_tile = (uint32_t)first;
+            d.n_tiles = (uint32_t)((d.numel + ce - 1) / ce);
+            first += d.n_tiles;
         }
     }
-    int rc = get_plan(key, live.size() * sizeof(TensorDev), chunks, &plan);
+    std::lock_guard<std::mutex> lock(g_mu);
+    Plan* plan = nullptr;
+    std::vector<uint32_t> coarse;
+    if (g_index.find(key) == g_index.end()) {
+        const int64_t n_coarse = ((total_chunks - 1) >> shift) + 1;
+        coarse.resize((size_t)n_coarse);
+        size_t ti = 0;
+        for (int64_t j = 0; j < n_coarse; ++j) {
+            const int64_t b = j << shift;
+            while ((int64_t)live[ti].first_tile + live[ti].n_tiles <= b) ++ti;
+            coarse[(size_t)j] = (uint32_t)ti;
+        }
+    }
+    int rc = get_plan(key, live.size() * sizeof(TensorDev), coarse.data(), coarse.size() * sizeof(uint32_t),
+                      total_chunks, &plan);
     if (rc != FLASHOPTIM_OK) return rc;
 
     const size_t bytes = live.size() * sizeof(TensorDev);
@@ -275,12 +293,15 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
         if (rc != FLASHOPTIM_OK) return rc;
     }
     a.tensors = static_cast<const TensorDev*>(plan->d_table);
-    a.chunks = plan->d_chunks;
+    a.coarse = static_cast<const uint32_t*>(plan->d_index);
+    a.coarse_shift = shift;
+    a.n_tensors = (uint32_t)live.size();
     FO_HIP(launch_op(op, kind, false, split, quant, a, plan->n_chunks, stream));
     return FLASHOPTIM_OK;
 }
 
-int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, const StepConsts& c, void* stream_) {
+int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, const StepConsts& c, void* stream_,
+             LiveOp op = kOpStep) {
     const bool has_v = (kind == FLASHOPTIM_ADAMW);
     int rc = validate_tensors(tensors, n_tensors, has_v);
     if (rc != FLASHOPTIM_OK) return rc;
@@ -293,7 +314,7 @@ int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, cons
     live.reserve((size_t)n_tensors);
     for (int64_t i = 0; i < n_tensors; ++i)
         if (tensors[i].numel > 0) live.push_back(to_dev(tensors[i], has_v));
-    return launch_live(kind, true, true, live, c, static_cast<hipStream_t>(stream_));
+    return launch_live(kind, true, true, live, c, static_cast<hipStream_t>(stream_), op);
 }
 
 // Conversion between the FP32 state and the compressed layout: every buffer of both layouts is needed.
@@ -410,13 +431,15 @@ int run_copy(const std::vector<CopySegment>& segs, hipStream_t stream) {
     append(key, segs.data(), segs.size() * sizeof(CopySegment));
     std::lock_guard<std::mutex> lock(g_mu);
     Plan* plan = nullptr;
-    int rc = get_plan(key, segs.size() * sizeof(CopySegment), chunks, &plan);
+    int rc = get_plan(key, segs.size() * sizeof(CopySegment), chunks.data(), chunks.size() * sizeof(uint2),
+                      (int64_t)chunks.size(), &plan);
     if (rc != FLASHOPTIM_OK) return rc;
     if (plan->uploaded.empty()) {
         rc = upload_table(*plan, segs.data(), segs.size() * sizeof(CopySegment), stream);
         if (rc != FLASHOPTIM_OK) return rc;
     }
-    fo::launch_copy(static_cast<const CopySegment*>(plan->d_table), plan->d_chunks, plan->n_chunks, stream);
+    fo::launch_copy(static_cast<const CopySegment*>(plan->d_table), static_cast<const uint2*>(plan->d_index), plan->n_chunks,
+                    stream);
     FO_HIP(hipGetLastError());
     return FLASHOPTIM_OK;
 }
@@ -498,6 +521,13 @@ int flashoptim_lion_step_ex(const flashoptim_tensor_ex* tensors, int64_t n_tenso
     StepConsts c;
     if (!lion_consts(hp, c)) return FLASHOPTIM_ERR_INVALID_ARG;
     return run_step_ex(FLASHOPTIM_LION, tensors, n_tensors, c, flags, stream);
+}
+
+int flashoptim_stream_probe(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, void* stream) {
+    if (kind < 0 || kind > 2) return FLASHOPTIM_ERR_INVALID_ARG;
+    StepConsts c;
+    std::memset(&c, 0, sizeof(c));
+    return run_step(kind, tensors, n_tensors, c, stream, kOpProbe);
 }
 
 int flashoptim_compress_state(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors, void* stream) {

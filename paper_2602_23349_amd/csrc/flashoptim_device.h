@@ -11,8 +11,8 @@ namespace fo {
 constexpr int kGroup = 32;                         // quantisation group (Algorithms 2, 3)
 constexpr int kThreads = 256;                      // lanes per workgroup (codec and copy kernels)
 // Launch shape of the step kernels, per optimizer kind (0 AdamW, 1 SGD, 2 Lion): consecutive
-// elements per lane, lanes per workgroup, and tiles (passes) per workgroup.  One workgroup handles
-// one chunk-table entry of chunk_elems(kind) elements.
+// elements per lane and lanes per workgroup.  One workgroup handles one tile of chunk_elems(kind)
+// elements.
 #ifndef FO_VEC_ADAMW
 #define FO_VEC_ADAMW 8
 #endif
@@ -25,22 +25,15 @@ constexpr int kThreads = 256;                      // lanes per workgroup (codec
 #ifndef FO_THREADS_SGD_LION
 #define FO_THREADS_SGD_LION 512
 #endif
-#ifndef FO_TILES_ADAMW
-#define FO_TILES_ADAMW 1
-#endif
-#ifndef FO_TILES_SGD_LION
-#define FO_TILES_SGD_LION 1
-#endif
 constexpr int step_vec(int kind) { return kind == 0 ? FO_VEC_ADAMW : FO_VEC_SGD_LION; }
 constexpr int step_threads(int kind) { return kind == 0 ? FO_THREADS_ADAMW : FO_THREADS_SGD_LION; }
-constexpr int step_tiles(int kind) { return kind == 0 ? FO_TILES_ADAMW : FO_TILES_SGD_LION; }
-constexpr int chunk_elems(int kind) { return step_threads(kind) * step_vec(kind) * step_tiles(kind); }
+constexpr int chunk_elems(int kind) { return step_threads(kind) * step_vec(kind); }
 #ifndef FO_COPY_CHUNK_KB
 #define FO_COPY_CHUNK_KB 64
 #endif
 constexpr int kCopyChunkBytes = FO_COPY_CHUNK_KB * 1024;   // checkpoint copy: bytes per workgroup
 
-// One tensor as the kernels see it (device pointers), 96 bytes.
+// One tensor as the kernels see it (device pointers), 104 bytes.
 struct TensorDev {
     void* param;
     int8_t* rho;
@@ -54,6 +47,8 @@ struct TensorDev {
     float* v32;       // ablation variants: FP32 variance
     int64_t numel;
     float lr, wd;
+    uint32_t first_tile;   // multi-tensor launch: index of the workgroup that handles the tensor's first tile
+    uint32_t n_tiles;      // multi-tensor launch: number of tiles (workgroups) of the tensor
 };
 
 // Per-call scalars, computed once on the host.
@@ -65,9 +60,17 @@ struct StepConsts {
     float root_bc2;       // (float)sqrt(1 / (double)rbc2): used only to pre-estimate variance codes
 };
 
+// A multi-tensor launch maps workgroup b to (tensor, tile) in two steps: coarse[b >> coarse_shift] is
+// the tensor that holds tile (b >> coarse_shift) << coarse_shift, and the tensors' first_tile /
+// n_tiles fields carry the search on from there (usually zero further steps).  Both tables are
+// small (at most 16 K coarse entries) and stay cache-resident, unlike a table with one entry per
+// workgroup, whose entries every workgroup would fetch from HBM.
+constexpr int kCoarseMaxEntries = 16384;
 struct StepArgs {
     const TensorDev* tensors;   // device table (multi-tensor launch)
-    const uint2* chunks;        // device chunk table: {tensor index, chunk index within the tensor}
+    const uint32_t* coarse;     // device table: tensor index per 2^coarse_shift workgroups
+    uint32_t coarse_shift;
+    uint32_t n_tensors;
     TensorDev single;           // the one tensor of a direct launch
     StepConsts c;
 };
@@ -83,6 +86,7 @@ hipError_t launch_step(int kind, bool direct, bool split, bool quant, const Step
                        hipStream_t s);
 constexpr int kConvChunkElems = 256 * 8;   // elements per workgroup of the layout-conversion kernel
 hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s);
+hipError_t launch_probe(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s);
 void launch_split(int bits, const float* theta, void* param, void* rho, int64_t n, hipStream_t s);
 void launch_reconstruct(int bits, const void* param, const void* rho, float* theta, int64_t n, hipStream_t s);
 constexpr int kSweepStats = 8 + 2 * 256;

@@ -191,7 +191,7 @@ __device__ __forceinline__ uint32_t m_code_exact(float m, float r) {
 // quotient uses v_rcp_f32 (1 ulp), so y differs from the exact y by at most
 // (2 + 1 + 1 + 2) * 2^-24 * 128 < 4.6e-5 wherever the clamp is not active.  *resid is the
 // distance of y from the integer it rounds to.
-constexpr float kTieWindowM = 1.0e-4f;
+constexpr float kTieWindowM = 6.0e-5f;
 __device__ __forceinline__ uint32_t m_code_fast(float m, float r, float* resid) {
     const float m1 = m * r;
     const float den = 1.0f + fabsf(m1);
@@ -208,11 +208,17 @@ __device__ __forceinline__ uint32_t v_code_exact(float v, float r) {
     return round_to_int_bits(y);
 }
 
+// The same value when v is known to be 0 or at least 2^-96 (the range of sqrt_rn_midrange).
+__device__ __forceinline__ uint32_t v_code_exact_midrange(float v, float r) {
+    const float y = __builtin_amdgcn_fmed3f((sqrt_rn_midrange(v) * r) * 255.0f, 0.0f, 255.0f);
+    return round_to_int_bits(y);
+}
+
 // Same code from root_hat = sqrt(v * rbc2) (exactly rounded, already computed for the update)
 // and kr255 = ((sqrt(1/rbc2) rounded) * r) * 255.  Relative errors: v*rbc2 (1), its root
 // (0.5 + 1), the three roundings inside kr255 (3), this product (1), against the three
 // roundings of the exact chain (3): below 9.5 * 2^-24 * 255 < 1.45e-4 in y.
-constexpr float kTieWindowV = 2.5e-4f;
+constexpr float kTieWindowV = 1.8e-4f;
 __device__ __forceinline__ uint32_t v_code_fast(float root_hat, float kr255, float* resid) {
     const float y = __builtin_amdgcn_fmed3f(root_hat * kr255, 0.0f, 255.0f);
     const float t = y + 12582912.0f;
@@ -270,19 +276,45 @@ constexpr DecodeTables make_decode_tables() {
 __device__ const DecodeTables g_decode_tables = make_decode_tables();
 
 // Each workgroup stages the tables (6 KB, L2-resident) into LDS: one entry per lane per table.
-// With 512 lanes the two halves of the workgroup share the work.
+// With 512 lanes the two halves of the workgroup share the work.  The staging is split into its
+// load half and its store half so that a kernel can issue the loads first of all (they depend on
+// nothing) and store to LDS only after it has issued its streaming loads.
+struct TableEntries {
+    float rho, m, v, half_ulp;
+    float2 split;
+};
 template <int THREADS>
-__device__ __forceinline__ void fill_tables(DecodeTables& t, int tid) {
+__device__ __forceinline__ void load_table_entries(TableEntries& e, int tid) {
     static_assert(THREADS == 256 || THREADS == 512, "");
-    const int i = tid & 255;
+    // scalar base + 32-bit lane offset, so that no 64-bit address arithmetic lands on the vector ALU
+    typedef const __attribute__((address_space(1))) uint8_t* base_t;
+    typedef const __attribute__((address_space(1))) float* fptr_t;
+    typedef float f2_t __attribute__((ext_vector_type(2)));
+    typedef const __attribute__((address_space(1))) f2_t* f2ptr_t;
+    const base_t base = (base_t)&g_decode_tables;
+    const uint32_t o4 = (uint32_t)(tid & 255) * 4u;
     if (THREADS == 256 || tid < 256) {
-        t.rho[i] = g_decode_tables.rho[i];
-        t.m[i] = g_decode_tables.m[i];
-        t.v[i] = g_decode_tables.v[i];
+        e.rho = *(fptr_t)(base + offsetof(DecodeTables, rho) + o4);
+        e.m = *(fptr_t)(base + offsetof(DecodeTables, m) + o4);
+        e.v = *(fptr_t)(base + offsetof(DecodeTables, v) + o4);
     }
     if (THREADS == 256 || tid >= 256) {
-        t.half_ulp[i] = g_decode_tables.half_ulp[i];
-        t.split[i] = g_decode_tables.split[i];
+        e.half_ulp = *(fptr_t)(base + offsetof(DecodeTables, half_ulp) + o4);
+        const f2_t sp = *(f2ptr_t)(base + offsetof(DecodeTables, split) + (o4 + o4));
+        e.split = make_float2(sp[0], sp[1]);
+    }
+}
+template <int THREADS>
+__device__ __forceinline__ void store_table_entries(DecodeTables& t, const TableEntries& e, int tid) {
+    const int i = tid & 255;
+    if (THREADS == 256 || tid < 256) {
+        t.rho[i] = e.rho;
+        t.m[i] = e.m;
+        t.v[i] = e.v;
+    }
+    if (THREADS == 256 || tid >= 256) {
+        t.half_ulp[i] = e.half_ulp;
+        t.split[i] = e.split;
     }
 }
 
@@ -731,6 +763,7 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
         kr255 = (c.root_bc2 * r_v) * 255.0f;
     }
 
+    const bool vt_root_general = HAS_V && any_lane(amin_v < kSqrtFastMin);
     // epilogue: state codes, four at a time; exact recomputation only near rounding ties
 #pragma unroll
     for (int j = 0; j < VEC / 4; ++j) {
@@ -757,8 +790,15 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
                 dv = fmaxf(dv, d);
             }
             if (any_lane(dv > 0.5f - kTieWindowV)) {
+                // exact recomputation; the short exact root serves when every v_t of the wavefront
+                // is in its range (v_t and v_hat differ by the factor rbc2 >= 1: a separate test)
+                if (vt_root_general) {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) cv[k] = v_code_exact(vt[4 * j + k], r_v);
+                    for (int k = 0; k < 4; ++k) cv[k] = v_code_exact(vt[4 * j + k], r_v);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) cv[k] = v_code_exact_midrange(vt[4 * j + k], r_v);
+                }
             }
             y.vq[j] = pack_low_bytes(cv[0], cv[1], cv[2], cv[3]);
         }
@@ -766,71 +806,77 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
 }
 
 // ------------------------------------------------------------ step kernels --
-
-template <int KIND, int VEC, int THREADS, int TILES, bool DIRECT, bool SPLIT, bool QUANT>
-__global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
-    constexpr bool HAS_V = (KIND == 0);
-    constexpr int kTile = THREADS * VEC;       // elements per pass of the workgroup
-    __shared__ DecodeTables tab;
-    const int tid = (int)threadIdx.x;
-
-    TensorDev T;
-    int64_t chunk;
+// The tensor and the tile within it that workgroup blockIdx.x handles.  Every load is wave-uniform
+// (scalar).  The search loop ends at the last tensor at the latest.
+template <bool DIRECT>
+__device__ __forceinline__ int64_t locate_tile(const StepArgs& a, TensorDev& T) {
+    const uint32_t b = blockIdx.x;
     if (DIRECT) {
         T = a.single;
-        chunk = (int64_t)blockIdx.x;
-    } else {
-        const uint2 ck = a.chunks[blockIdx.x];
-        T = a.tensors[ck.x];
-        chunk = (int64_t)ck.y;
+        return (int64_t)b;
     }
-    // A workgroup handles TILES consecutive tiles of one tensor and then retires (persistent
-    // workgroups that loop over many tiles were measured 10 % slower: an iteration's loads then
-    // wait behind the previous iteration's stores).  The first tile's streaming loads go out
-    // before the decode tables are staged, so the staging hides behind them; the loads of tile
-    // k+1 are issued BEFORE the stores of tile k, so that waiting for them does not wait for
-    // those stores.
+    uint32_t t = a.coarse[b >> a.coarse_shift];
+    T = a.tensors[t];
+    while (b - T.first_tile >= T.n_tiles && t + 1 < a.n_tensors) {
+        ++t;
+        T = a.tensors[t];
+    }
+    return (int64_t)(b - T.first_tile);
+}
+
+
+// One tile of one tensor.  FULL: every lane of the workgroup holds VEC elements (all tiles of a
+// tensor but possibly its last); the code then has no per-lane case distinction at all, so the
+// table staging below waits for the table loads only and overlaps the streaming loads.
+template <int KIND, int VEC, int THREADS, bool SPLIT, bool QUANT, bool FULL>
+__device__ __forceinline__ void step_tile(const TensorDev& T, const StepConsts& c, DecodeTables& tab,
+                                          const TableEntries& entries, int64_t tile0, int tile_cnt, int tid) {
+    constexpr bool HAS_V = (KIND == 0);
     const bool leader = (tid & (kGroup / VEC - 1)) == 0;
     const uint32_t lane_el = (uint32_t)tid * VEC;              // first element of the lane inside its tile
-    int64_t tile0 = chunk * (int64_t)(kTile * TILES);          // first element of the tile (wave-uniform)
-    // elements of the tensor from the start of this tile on, capped at one tile (wave-uniform), and
-    // the number of them that fall to this lane
-    int64_t rem = T.numel - tile0;
-    int tile_cnt = rem >= kTile ? kTile : (int)rem;
-    int left = tile_cnt - (int)lane_el;
-    int cnt = left >= VEC ? VEC : (left > 0 ? left : 0);
+    // the number of the tile's elements that fall to this lane
+    const int left = tile_cnt - (int)lane_el;
+    const int cnt = FULL ? VEC : (left >= VEC ? VEC : (left > 0 ? left : 0));
     LaneIO<VEC> x, y;
-    if (cnt == VEC) load_full<VEC, HAS_V, SPLIT, QUANT>(x, T, tile0, lane_el);
+    if (FULL || cnt == VEC) load_full<VEC, HAS_V, SPLIT, QUANT>(x, T, tile0, lane_el);
     else load_tail<VEC, HAS_V, SPLIT, QUANT>(x, T, tile0 + lane_el, cnt);
-    fill_tables<THREADS>(tab, tid);
+    store_table_entries<THREADS>(tab, entries, tid);
     __syncthreads();
-#pragma unroll
-    for (int t = 0; t < TILES; ++t) {
-        // All lanes of a group run the update together (a lane with cnt == 0 may share its group
-        // with lanes that hold elements); lanes past the end compute on zeros and store nothing.
-        update_lane<KIND, VEC, SPLIT, QUANT>(x, y, tab, a.c, T.lr, T.wd);
-        const int64_t tile_done = tile0;
-        const int cnt_done = cnt;
-        if (t + 1 < TILES) {
-            tile0 += kTile;
-            rem = T.numel - tile0;
-            tile_cnt = rem >= kTile ? kTile : (rem > 0 ? (int)rem : 0);
-            left = tile_cnt - (int)lane_el;
-            cnt = left >= VEC ? VEC : (left > 0 ? left : 0);
-            if (cnt == VEC) load_full<VEC, HAS_V, SPLIT, QUANT>(x, T, tile0, lane_el);
-            else load_tail<VEC, HAS_V, SPLIT, QUANT>(x, T, tile0 + lane_el, cnt);
-        }
-        if (cnt_done == VEC) store_full<VEC, HAS_V, SPLIT, QUANT>(y, T, tile_done, lane_el, leader);
-        else store_tail<VEC, HAS_V, SPLIT, QUANT>(y, T, tile_done + lane_el, cnt_done, leader);
+    // All lanes of a group run the update together (a lane with cnt == 0 may share its group
+    // with lanes that hold elements); lanes past the end compute on zeros and store nothing.
+    update_lane<KIND, VEC, SPLIT, QUANT>(x, y, tab, c, T.lr, T.wd);
+    if (FULL || cnt == VEC) store_full<VEC, HAS_V, SPLIT, QUANT>(y, T, tile0, lane_el, leader);
+    else store_tail<VEC, HAS_V, SPLIT, QUANT>(y, T, tile0 + lane_el, cnt, leader);
+}
+
+// A workgroup handles one tile of one tensor and then retires (persistent workgroups that loop
+// over many tiles were measured 10 % slower: an iteration's loads then wait behind the previous
+// iteration's stores).  Order of issue: decode-table loads, the (tensor, tile) look-up, the
+// streaming loads; then the tables go to LDS while the streaming loads are still in flight.
+template <int KIND, int VEC, int THREADS, bool DIRECT, bool SPLIT, bool QUANT>
+__global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
+    constexpr int kTile = THREADS * VEC;       // elements per workgroup
+    __shared__ DecodeTables tab;
+    const int tid = (int)threadIdx.x;
+    TableEntries entries;
+    load_table_entries<THREADS>(entries, tid);
+    TensorDev T;
+    const int64_t chunk = locate_tile<DIRECT>(a, T);
+    const int64_t tile0 = chunk * (int64_t)kTile;              // first element of the tile (wave-uniform)
+    const int64_t rem = T.numel - tile0;                       // elements from there to the tensor's end
+    if (rem >= kTile) {
+        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, true>(T, a.c, tab, entries, tile0, kTile, tid);
+    } else {
+        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, false>(T, a.c, tab, entries, tile0, rem > 0 ? (int)rem : 0, tid);
     }
 }
 
 template <int KIND, bool SPLIT, bool QUANT>
 static hipError_t launch_variant(bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
-    constexpr int VEC = step_vec(KIND), THREADS = step_threads(KIND), TILES = step_tiles(KIND);
+    constexpr int VEC = step_vec(KIND), THREADS = step_threads(KIND);
     const dim3 grid((unsigned)n_blocks), block(THREADS);
-    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, TILES, true, SPLIT, QUANT>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, TILES, false, SPLIT, QUANT>), grid, block, 0, s, a);
+    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, true, SPLIT, QUANT>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, false, SPLIT, QUANT>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
@@ -848,6 +894,48 @@ hipError_t launch_step(int kind, bool direct, bool split, bool quant, const Step
     if (kind == 0) return launch_kind<0>(direct, split, quant, a, n_blocks, s);
     if (kind == 1) return launch_kind<1>(direct, split, quant, a, n_blocks, s);
     return launch_kind<2>(direct, split, quant, a, n_blocks, s);
+}
+
+// ------------------------------------------------------------- stream probe --
+//
+// Moves exactly the bytes of one optimizer step with no arithmetic: every stream the step reads is
+// read (gradients included) and every stream it writes is written back unchanged, through the same
+// chunk table, lane layout and access instructions.  Its rate is what the memory system delivers
+// for this access pattern, the ceiling the step kernel's rate is compared with.
+template <int KIND, int VEC, int THREADS, bool DIRECT>
+__global__ __launch_bounds__(THREADS) void probe_kernel(StepArgs a) {
+    constexpr bool HAS_V = (KIND == 0);
+    constexpr int kTile = THREADS * VEC;
+    const int tid = (int)threadIdx.x;
+    TensorDev T;
+    const int64_t chunk = locate_tile<DIRECT>(a, T);
+    const bool leader = (tid & (kGroup / VEC - 1)) == 0;
+    const uint32_t lane_el = (uint32_t)tid * VEC;
+    const int64_t tile0 = chunk * (int64_t)kTile;
+    const int64_t rem = T.numel - tile0;
+    const int tile_cnt = rem >= kTile ? kTile : (int)rem;
+    const int left = tile_cnt - (int)lane_el;
+    const int cnt = left >= VEC ? VEC : (left > 0 ? left : 0);
+    LaneIO<VEC> x;
+    if (cnt == VEC) load_full<VEC, HAS_V, true, true>(x, T, tile0, lane_el);
+    else load_tail<VEC, HAS_V, true, true>(x, T, tile0 + lane_el, cnt);
+    // The gradient takes no part in what is stored; an empty asm statement that names its registers
+    // keeps the load from being removed.
+#pragma unroll
+    for (int j = 0; j < VEC / 2; ++j) asm volatile("" : : "v"(x.g[j]));
+    if (cnt == VEC) store_full<VEC, HAS_V, true, true>(x, T, tile0, lane_el, leader);
+    else store_tail<VEC, HAS_V, true, true>(x, T, tile0 + lane_el, cnt, leader);
+}
+
+hipError_t launch_probe(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
+    const dim3 grid((unsigned)n_blocks);
+#define FO_PROBE(K, DR) hipLaunchKernelGGL((probe_kernel<K, step_vec(K), step_threads(K), DR>), grid, \
+                                           dim3(step_threads(K)), 0, s, a)
+    if (kind == 0) { if (direct) FO_PROBE(0, true); else FO_PROBE(0, false); }
+    else if (kind == 1) { if (direct) FO_PROBE(1, true); else FO_PROBE(1, false); }
+    else { if (direct) FO_PROBE(2, true); else FO_PROBE(2, false); }
+#undef FO_PROBE
+    return hipGetLastError();
 }
 
 // -------------------------------------------------------- standalone codecs --
@@ -1263,15 +1351,7 @@ static_assert(kCodecTile == kConvChunkElems, "the conversion chunk table is buil
 template <bool HAS_V, bool COMPRESS, bool DIRECT>
 __global__ __launch_bounds__(kThreads) void convert_kernel(StepArgs a) {
     TensorDev T;
-    int64_t chunk;
-    if (DIRECT) {
-        T = a.single;
-        chunk = (int64_t)blockIdx.x;
-    } else {
-        const uint2 ck = a.chunks[blockIdx.x];
-        T = a.tensors[ck.x];
-        chunk = (int64_t)ck.y;
-    }
+    const int64_t chunk = locate_tile<DIRECT>(a, T);
     const LanePos L = lane_pos_at(chunk * (int64_t)kCodecTile, T.numel);
     const int64_t group = (L.tile0 + L.lane_el) >> 5;
     if (COMPRESS) {

@@ -84,6 +84,34 @@ def test_ragged_sizes_multi_tensor(kind, hp):
     assert total_mismatches(report) == 0
 
 
+@pytest.mark.parametrize("kind", ["adamw", "sgd", "lion"])
+def test_stream_probe_changes_nothing(kind):
+    # the measurement aid moves a step's bytes and must leave every array as it was, ragged ends
+    # and single-tensor (table-free) lists included
+    specs = W.odd_sizes()
+    bufs = []
+    for i, sp in enumerate(specs):
+        st = W.random_state(sp.numel, i, seed=9, with_variance=(kind == "adamw"))
+        b = fo.ParamBuffers(sp.numel, kind)
+        b.param.copy_(st["thp"].cuda()); b.rho.copy_(st["rho"].cuda())
+        b.m_q.copy_(st["mq"].cuda()); b.m_scale.copy_(st["ms"].cuda())
+        if kind == "adamw":
+            b.v_q.copy_(st["vq"].cuda()); b.v_scale.copy_(st["vs"].cuda())
+        b.grad.copy_(W.grad_bf16(sp, i, 1, seed=9).cuda())
+        bufs.append(b)
+    before = [download(b) for b in bufs]
+    fo.stream_probe(kind, fo.TensorList(bufs))
+    fo.stream_probe(kind, fo.TensorList([bufs[3]]))
+    torch.cuda.synchronize()
+    for b, want in zip(bufs, before):
+        got = download(b)
+        for k in want:
+            assert np.array_equal(got[k], want[k]), k
+    L = fo.load_library()
+    assert L.flashoptim_stream_probe(7, None, 0, None) == -1
+    assert L.flashoptim_stream_probe(0, None, 0, None) == 0
+
+
 def test_single_tensor_direct_path_matches_list_path():
     # a list of length one takes the table-free launch (the gradient-release call)
     spec = W.ParamSpec("x", (3 * 8192 + 4096 + 77,), "matrix")

@@ -27,6 +27,12 @@ def flat_tensor(n: int = 1 << 20) -> List[ParamSpec]:
     return [ParamSpec("flat", (n,), "matrix")]
 
 
+def llama31_8b_flat() -> List[ParamSpec]:
+    """The Llama-3.1-8B parameter count as ONE flat tensor: the shape a flattened (FSDP-style)
+    parameter buffer of the whole model presents to the optimizer step."""
+    return flat_tensor(sum(s.numel for s in llama31_8b()))
+
+
 def odd_sizes() -> List[ParamSpec]:
     """Small tensors whose sizes straddle the group (32), vector and chunk boundaries."""
     sizes = [1, 2, 7, 8, 15, 16, 17, 31, 32, 33, 63, 64, 65, 255, 257, 1000, 1023, 1025,
