@@ -184,6 +184,17 @@ def _run_list(kind, hp, specs, seed, dist, scale, per_tensor_sigma, steps, nthre
     assert total_mismatches(report) == 0
 
 
+@pytest.mark.parametrize("kind,hp", [("adamw", ADAMW), ("sgd", SGD)])
+def test_list_whose_tile_lookup_needs_several_steps(kind, hp):
+    # More than 16 K tiles in one launch, so that one coarse-table entry stands for several tiles, with runs
+    # of tiny tensors inside single buckets: workgroups there walk over several descriptors to find theirs.
+    big = (2048 if kind == "adamw" else 4096) * 20000      # 20000 tiles of the kind's tile size
+    sizes = [big + 77] + [1, 33, 2048, 2049, 4096, 100, 6000, 31, 2047, 5000] + [big // 2 + 5] + \
+            [7, 2048 * 3 + 1, 64, 4097] + [big // 4]
+    specs = [W.ParamSpec(f"t{i}", (n,), "matrix") for i, n in enumerate(sizes)]
+    _run_list(kind, hp, specs, seed=21, dist="normal", scale=1e-3, per_tensor_sigma=False, steps=(1, 2), nthreads=0)
+
+
 def test_gpt2_list_sgd():
     # workload 2: GPT-2 124M parameter list, per-tensor gradient scale log-uniform in [1e-5, 1e-2]
     _run_list("sgd", SGD, W.gpt2_small(), seed=0, dist="normal", scale=None, per_tensor_sigma=True, steps=(1, 2, 3))
