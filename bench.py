@@ -145,15 +145,15 @@ def cpu_baseline(W, specs, kind, hp, dist, scale, seed, target_seconds):
         grads.append(W.grad_bf16(s, i, 1, seed=seed, dist=dist, scale=sc).view(torch.int16).numpy().view(np.uint16))
     threads = oracle.max_threads()
 
-    def one(t):
+    def one(t, nthreads=0):
         for (i, s), st, g in zip(sample, states, grads):
             wd = hp["wd"] if s.role == "matrix" else 0.0
             if kind == "adamw":
-                oracle.adamw_step(st, g, hp["lr"], wd, hp["beta1"], hp["beta2"], hp["eps"], t)
+                oracle.adamw_step(st, g, hp["lr"], wd, hp["beta1"], hp["beta2"], hp["eps"], t, nthreads=nthreads)
             elif kind == "sgd":
-                oracle.sgd_step(st, g, hp["lr"], wd, hp["momentum"])
+                oracle.sgd_step(st, g, hp["lr"], wd, hp["momentum"], nthreads=nthreads)
             else:
-                oracle.lion_step(st, g, hp["lr"], wd, hp["beta1"], hp["beta2"])
+                oracle.lion_step(st, g, hp["lr"], wd, hp["beta1"], hp["beta2"], nthreads=nthreads)
 
     one(1)                                  # untimed: page in, reach a non-zero state
     t0 = time.perf_counter(); one(2); dt = time.perf_counter() - t0
@@ -162,8 +162,11 @@ def cpu_baseline(W, specs, kind, hp, dist, scale, seed, target_seconds):
     for r in range(reps):
         one(3 + r)
     total = time.perf_counter() - t0
+    # the same sample on one thread, one step
+    t0 = time.perf_counter(); one(3 + reps, nthreads=1); single = time.perf_counter() - t0
     return {"value": n * reps / total, "unit": "params/s", "cores": threads, "kind": "oracle",
-            "sample": f"{what}: {n} params x {reps} steps, {total:.1f} s"}
+            "sample": f"{what}: {n} params x {reps} steps, {total:.1f} s",
+            "single_thread_value": n / single}
 
 
 def read_traffic(kind, workload):
