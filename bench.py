@@ -38,6 +38,8 @@ WORKLOADS = {
     "resnet50_adamw": ("adamw", "resnet50", "student3", 1e-3),
     "flat_adamw": ("adamw", "flat_tensor", "normal", 1e-3),
     "llama31_8b_flat_adamw": ("adamw", "llama31_8b_flat", "normal", 1e-4),
+    "llama31_8b_flat_sgd": ("sgd", "llama31_8b_flat", "normal", 1e-4),
+    "llama31_8b_flat_lion": ("lion", "llama31_8b_flat", "normal", 1e-4),
 }
 
 

@@ -219,11 +219,25 @@ int to_dev_ex(const flashoptim_tensor_ex* t, int64_t n, bool has_v, bool split, 
 // What a multi-tensor launch runs: an optimizer step, a layout conversion, or the stream probe.
 enum LiveOp { kOpStep = 0, kOpCompress = 1, kOpDecompress = 2, kOpProbe = 3 };
 
-hipError_t launch_op(LiveOp op, int kind, bool direct, bool split, bool quant, const StepArgs& a, int64_t blocks,
-                     hipStream_t stream) {
+hipError_t launch_segment(LiveOp op, int kind, bool direct, bool split, bool quant, const StepArgs& a, int64_t blocks,
+                          hipStream_t stream) {
     if (op == kOpStep) return fo::launch_step(kind, direct, split, quant, a, blocks, stream);
     if (op == kOpProbe) return fo::launch_probe(kind, direct, a, blocks, stream);
     return fo::launch_convert(kind == FLASHOPTIM_ADAMW, op == kOpCompress, direct, a, blocks, stream);
+}
+
+// The workgroups 0 .. blocks-1 of one logical launch (each handles `tile_elems` elements), issued as
+// back-to-back launches on the same stream, each covering at most kSegmentElems elements.
+hipError_t launch_op(LiveOp op, int kind, bool direct, bool split, bool quant, StepArgs a, int64_t blocks,
+                     int64_t tile_elems, hipStream_t stream) {
+    const int64_t seg = fo::kSegmentElems / tile_elems > 0 ? fo::kSegmentElems / tile_elems : 1;
+    for (int64_t first = 0; first < blocks; first += seg) {
+        a.block_offset = (uint32_t)first;
+        const int64_t n = blocks - first < seg ? blocks - first : seg;
+        const hipError_t e = launch_segment(op, kind, direct, split, quant, a, n, stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // Launches one operation over the live tensors (already validated and converted).
@@ -243,7 +257,7 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
         // gradient-release call: no table, no allocation, no lock
         a.single = live[0];
         const int64_t blocks = (live[0].numel + ce - 1) / ce;
-        FO_HIP(launch_op(op, kind, true, split, quant, a, blocks, stream));
+        FO_HIP(launch_op(op, kind, true, split, quant, a, blocks, ce, stream));
         return FLASHOPTIM_OK;
     }
 
@@ -296,7 +310,7 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
     a.coarse = static_cast<const uint32_t*>(plan->d_index);
     a.coarse_shift = shift;
     a.n_tensors = (uint32_t)live.size();
-    FO_HIP(launch_op(op, kind, false, split, quant, a, plan->n_chunks, stream));
+    FO_HIP(launch_op(op, kind, false, split, quant, a, plan->n_chunks, ce, stream));
     return FLASHOPTIM_OK;
 }
 
