@@ -3,12 +3,13 @@
 
 Default workload (the one the headline metric is quoted on): FlashAdamW over the
 Llama-3.1-8B parameter list (291 tensors, 8,030,261,248 parameters, 57.2 GB of resident
-state), one fused multi-tensor launch per step, synthetic values.  A "step" is one pass of the
+state), one fused multi-tensor call per step (issued as ~30 back-to-back kernel launches), synthetic values.  A "step" is one pass of the
 whole path: reconstruct master weights and states, AdamW update from BF16 gradients, re-quantise
 states, re-split weights.  Inputs are resident in HBM before the timed region starts.
 
 Prints ONE JSON line:  params/s (value), ms per step, the HBM roofline of the step kernel
-(algorithmic bytes per launch / mean launch time measured with HIP events on the launch stream),
+(algorithmic bytes per step / time per step measured with HIP events on the launch stream; equivalently
+mean bytes per kernel launch / mean launch duration),
 and the CPU oracle's throughput on a bounded sample of the same workload.
 """
 import argparse
@@ -172,8 +173,8 @@ def cpu_baseline(W, specs, kind, hp, dist, scale, seed, target_seconds):
 
 
 def read_traffic(kind, workload):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary
-    for this workload has been recorded under profiles/."""
+    """HBM bytes per step (all kernel launches of one call) measured with rocprofv3 --pmc (FETCH_SIZE,
+    WRITE_SIZE), if a summary for this workload has been recorded under profiles/."""
     path = os.path.join(ROOT, "profiles", f"{kind}_step_{workload}_pmc.txt")
     if not os.path.exists(path):
         return None
@@ -185,9 +186,7 @@ def read_traffic(kind, workload):
                 vals[k.strip()] = float(v.split()[0])
             except ValueError:
                 pass
-    if "HBM_BYTES_PER_LAUNCH" in vals:
-        return vals["HBM_BYTES_PER_LAUNCH"]
-    return None
+    return vals.get("HBM_BYTES_PER_STEP")
 
 
 def main():
@@ -270,7 +269,13 @@ def main():
     ms_per_step = total_ms / args.steps
     value = n_params * args.steps / (total_ms * 1e-3)
 
-    launches = len(specs) if release else 1
+    calls = len(specs) if release else 1
+    if ckpt or args.variant != "flash":
+        launches = None if args.variant != "flash" else 1
+    elif release:
+        launches = sum(fo.step_launch_count(kind, [s.numel]) for s in specs)
+    else:
+        launches = fo.step_launch_count(kind, [s.numel for s in specs])
     bytes_per_param = variant_bytes(kind, args.variant)
     assert args.variant != "flash" or bytes_per_param == BYTES_PER_PARAM[kind]
     algo_bytes = bytes_per_param * n_params                 # per step = per launch in fused mode
@@ -298,15 +303,19 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "optimizer": kind, "tensors": len(specs), "params": n_params,
-                   "mode": args.mode, "variant": args.variant, "launches_per_step": launches,
+                   "mode": args.mode, "variant": args.variant, "calls_per_step": calls,
+                   "kernel_launches_per_step": launches,
                    "resident_bytes_per_param": (7.125 if kind == "adamw" else 6.0625) - (2 if release else 0),
                    "min_ms_step": min(per_step_ms), "max_ms_step": max(per_step_ms),
                    "wall_ms_per_step": wall * 1e3 / args.steps},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": (traffic / launches) if (traffic and launches) else None,
+                     "traffic_per_step": traffic,
                      "kernel": ("fo::copy_kernel" if ckpt else
                                 f"fo::step_kernel<{['adamw', 'sgd', 'lion'].index(kind)}, ..., {'true' if release else 'false'}>"),
-                     "algorithmic_bytes_per_launch": algo_bytes if not release else None,
+                     "algorithmic_bytes_per_step": algo_bytes,
+                     "algorithmic_bytes_per_launch": (algo_bytes / launches) if launches else None,
                      "bytes_per_param": bytes_per_param,
                      "same_traffic_without_arithmetic": probe,
                      "frac_of_that": (achieved / probe) if probe else None},

@@ -89,10 +89,11 @@ typedef struct flashoptim_sgd_hp { float momentum; } flashoptim_sgd_hp;
 typedef struct flashoptim_lion_hp { float beta1, beta2; } flashoptim_lion_hp;
 
 /* ---- fused steps over a list of tensors ------------------------------------------
- * One kernel launch for the whole list (hundreds of small tensors fill the chip
- * through a chunk table that the library builds once per distinct list and caches on
- * the device).  A list of length one is the gradient-release call (Section 3.4): it
- * needs no table and no device allocation.  The grad pointers are not part of the
+ * One call covers the whole list: hundreds of small tensors fill the chip through a small
+ * index table that the library builds once per distinct list and caches on the device; the
+ * work is issued as a few back-to-back kernel launches on the given stream (one per 2^28
+ * elements).  A list of length one is the gradient-release call (Section 3.4): it needs no
+ * table and no device allocation.  The grad pointers are not part of the
  * cached identity of a list, so gradients may live in different buffers each step.
  *
  * flashoptim_adamw_step: Algorithm 4, the body of the loop after the gradient (reconstruct m, v, theta; AdamW
@@ -248,6 +249,10 @@ const char* flashoptim_strerror(int status);
  * n_checked, n_failed: HOST arrays of 6 counters (one per section above).  Waits for completion.
  * Returns FLASHOPTIM_OK, FLASHOPTIM_ERR_SELFTEST if any check failed, or another status. */
 int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream);
+/* Number of kernel launches one step call of `kind` issues for a list with these element counts
+ * (host arithmetic only; for reading profiles: per-kernel durations are per launch).  Negative
+ * status on invalid arguments. */
+int64_t flashoptim_step_launch_count(int kind, const int64_t* numels, int64_t n_tensors);
 int flashoptim_last_hip_error(void);
 int flashoptim_release_cache(void);
 int flashoptim_version(void);

@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     SPLIT_WEIGHTS, QUANTIZE_STATES,
     split_weights, reconstruct_weights, split_weights_i16, reconstruct_weights_i16, reconstruction_sweep,
     quantize_momentum, dequantize_momentum, quantize_variance, dequantize_variance,
-    quantize_state, dequantize_state, quantization_nmse, compress_state, decompress_state, stream_probe,
+    quantize_state, dequantize_state, quantization_nmse, compress_state, decompress_state, stream_probe, step_launch_count,
     checkpoint_size, checkpoint_pack, checkpoint_unpack,
     strerror, release_cache, version, selftest, EXPORTED_SYMBOLS, KIND,
 )

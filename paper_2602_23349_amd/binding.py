@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = [
     "flashoptim_quantize_variance", "flashoptim_dequantize_variance",
     "flashoptim_checkpoint_size", "flashoptim_checkpoint_pack", "flashoptim_checkpoint_unpack",
     "flashoptim_strerror", "flashoptim_last_hip_error", "flashoptim_release_cache", "flashoptim_version",
+    "flashoptim_step_launch_count",
     "flashoptim_selftest", "flashoptim_split_weights_i16", "flashoptim_reconstruct_weights_i16",
     "flashoptim_reconstruction_sweep",
     "flashoptim_adamw_step_ex", "flashoptim_sgd_step_ex", "flashoptim_lion_step_ex",
@@ -96,6 +97,8 @@ def load_library():
     L.flashoptim_quantization_nmse.argtypes = [i32, i32, vp, i64, C.POINTER(C.c_double), vp]
     L.flashoptim_checkpoint_size.argtypes = [i32, C.POINTER(i64), i64]
     L.flashoptim_checkpoint_size.restype = i64
+    L.flashoptim_step_launch_count.argtypes = [i32, C.POINTER(i64), i64]
+    L.flashoptim_step_launch_count.restype = i64
     L.flashoptim_checkpoint_pack.argtypes = [i32, C.POINTER(_Tensor), i64, i64, vp, i64, vp]
     L.flashoptim_checkpoint_unpack.argtypes = [i32, vp, i64, C.POINTER(_Tensor), i64, C.POINTER(i64), vp]
     L.flashoptim_selftest.argtypes = [C.POINTER(i64), C.POINTER(i64), vp]
@@ -371,6 +374,15 @@ def selftest(stream=None):
 
 def strerror(status):
     return load_library().flashoptim_strerror(int(status)).decode()
+
+
+def step_launch_count(kind, numels):
+    """Kernel launches that one step call of `kind` issues for a list with these element counts."""
+    arr = (C.c_int64 * max(len(numels), 1))(*[int(n) for n in numels])
+    n = int(load_library().flashoptim_step_launch_count(KIND[kind], arr, len(numels)))
+    if n < 0:
+        raise FlashOptimError(n, "flashoptim_step_launch_count")
+    return n
 
 
 def release_cache():

@@ -1,6 +1,6 @@
 // Host side of the FlashOptim C ABI (include/flashoptim.h): argument validation, the
-// cached device chunk tables that let one launch cover a whole parameter list, per-call
-// scalar set-up, and the checkpoint container.
+// cached device tables that let one call cover a whole parameter list, per-call scalar
+// set-up, and the checkpoint container.
 //
 // Nothing here computes on the CPU what the GPU should: if HIP is unavailable every
 // compute entry point returns FLASHOPTIM_ERR_HIP.
@@ -47,10 +47,11 @@ inline int64_t align64(int64_t x) { return (x + 63) & ~(int64_t)63; }
 
 // ----------------------------------------------------- cached device tables --
 //
-// A "plan" is what a multi-tensor launch needs on the device: the tensor table and the
-// chunk table.  It is keyed by the list's identity (device, kind, every state pointer and
+// A "plan" is what a multi-tensor launch needs on the device: the tensor table and the index
+// table (for steps and conversions a coarse workgroup -> tensor table, for copies one entry
+// per workgroup).  It is keyed by the list's identity (device, kind, every state pointer and
 // numel; NOT the gradient pointers or lr/wd, which legitimately change from step to step).
-// The tensor table is re-uploaded (72 B per tensor, through pinned staging, in stream
+// The tensor table is re-uploaded (104 B per tensor, through pinned staging, in stream
 // order) only when its content differs from what the device already holds.
 
 struct Staging {          // pinned host buffer + the event that marks its last copy done
@@ -794,6 +795,18 @@ const char* flashoptim_strerror(int status) {
 }
 
 int flashoptim_last_hip_error(void) { return g_last_hip_error; }
+
+int64_t flashoptim_step_launch_count(int kind, const int64_t* numels, int64_t n_tensors) {
+    if (kind < 0 || kind > 2 || n_tensors < 0 || (n_tensors > 0 && !numels)) return FLASHOPTIM_ERR_INVALID_ARG;
+    const int64_t ce = fo::chunk_elems(kind);
+    int64_t tiles = 0;
+    for (int64_t i = 0; i < n_tensors; ++i) {
+        if (numels[i] < 0 || numels[i] >= kMaxNumel) return FLASHOPTIM_ERR_NUMEL_RANGE;
+        tiles += (numels[i] + ce - 1) / ce;
+    }
+    const int64_t seg = fo::kSegmentElems / ce > 0 ? fo::kSegmentElems / ce : 1;
+    return (tiles + seg - 1) / seg;
+}
 
 int flashoptim_release_cache(void) {
     std::lock_guard<std::mutex> lock(g_mu);

@@ -11,9 +11,8 @@ namespace fo {
 constexpr int kGroup = 32;                         // quantisation group (Algorithms 2, 3)
 constexpr int kThreads = 256;                      // lanes per workgroup (codec and copy kernels)
 // Launch shape of the step kernels, per optimizer kind (0 AdamW, 1 SGD, 2 Lion): consecutive
-// elements per lane per pass, lanes per workgroup, and passes per workgroup.  One workgroup handles
-// one tile of chunk_elems(kind) consecutive elements; with P passes a lane owns P runs of VEC elements,
-// THREADS * VEC apart, all of whose loads are issued before any of them is used.
+// elements per lane and lanes per workgroup.  One workgroup handles one tile of chunk_elems(kind)
+// consecutive elements.
 #ifndef FO_VEC_ADAMW
 #define FO_VEC_ADAMW 8
 #endif
@@ -26,16 +25,9 @@ constexpr int kThreads = 256;                      // lanes per workgroup (codec
 #ifndef FO_THREADS_SGD_LION
 #define FO_THREADS_SGD_LION 512
 #endif
-#ifndef FO_PASSES_ADAMW
-#define FO_PASSES_ADAMW 1
-#endif
-#ifndef FO_PASSES_SGD_LION
-#define FO_PASSES_SGD_LION 1
-#endif
 constexpr int step_vec(int kind) { return kind == 0 ? FO_VEC_ADAMW : FO_VEC_SGD_LION; }
-constexpr int step_passes(int kind) { return kind == 0 ? FO_PASSES_ADAMW : FO_PASSES_SGD_LION; }
 constexpr int step_threads(int kind) { return kind == 0 ? FO_THREADS_ADAMW : FO_THREADS_SGD_LION; }
-constexpr int chunk_elems(int kind) { return step_threads(kind) * step_vec(kind) * step_passes(kind); }
+constexpr int chunk_elems(int kind) { return step_threads(kind) * step_vec(kind); }
 #ifndef FO_COPY_CHUNK_KB
 #define FO_COPY_CHUNK_KB 64
 #endif

@@ -40,8 +40,9 @@
 // 128-bit and byte streams as 64-bit accesses, and a quantisation group (32 elements) is a
 // lane quad, so the group absmax needs two DPP quad permutes and no LDS.  A workgroup (256
 // lanes for AdamW, 512 for SGD and Lion) handles one tile of consecutive elements of one
-// tensor; a chunk table maps blockIdx.x -> (tensor, tile) so that one launch covers a whole
-// parameter list.  Stream addresses are a scalar 64-bit tile base plus a 32-bit lane offset.
+// tensor; a small two-level table maps the workgroup index to (tensor, tile) so that one call covers a
+// whole parameter list, issued as a few consecutive launches.  Stream addresses are a scalar 64-bit
+// tile base plus a 32-bit lane offset.
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -825,48 +826,38 @@ __device__ __forceinline__ int64_t locate_tile(const StepArgs& a, TensorDev& T) 
 }
 
 
-// One tile of one tensor: PASSES sub-tiles of THREADS * VEC elements each.  All streaming loads of
-// the tile are issued up front (one look-up and one load latency per tile, however many passes);
-// then each pass is updated and stored in turn.  FULL: every lane holds VEC elements in every pass
-// (all tiles of a tensor but possibly its last); the code then has no per-lane case distinction.
-template <int KIND, int VEC, int THREADS, int PASSES, bool SPLIT, bool QUANT, bool FULL>
+// One tile of one tensor.  FULL: every lane of the workgroup holds VEC elements (all tiles of a
+// tensor but possibly its last); the code then has no per-lane case distinction at all.
+// (Variants in which a workgroup loads two or four such tiles up front and then updates them in
+// turn - fewer look-ups, more bytes in flight per workgroup - ran at the same rate.)
+template <int KIND, int VEC, int THREADS, bool SPLIT, bool QUANT, bool FULL>
 __device__ __forceinline__ void step_tile(const TensorDev& T, const StepConsts& c, DecodeTables& tab,
                                           const TableEntries& entries, int64_t tile0, int tile_cnt, int tid) {
     constexpr bool HAS_V = (KIND == 0);
-    constexpr int kPass = THREADS * VEC;
     const bool leader = (tid & (kGroup / VEC - 1)) == 0;
-    const uint32_t lane_el = (uint32_t)tid * VEC;              // first element of the lane inside a pass
-    LaneIO<VEC> x[PASSES];
-    int cnt[PASSES];                                           // elements of each pass that fall to this lane
-#pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-        const int left = tile_cnt - p * kPass - (int)lane_el;
-        cnt[p] = FULL ? VEC : (left >= VEC ? VEC : (left > 0 ? left : 0));
-        const int64_t pass0 = tile0 + (int64_t)p * kPass;
-        if (FULL || cnt[p] == VEC) load_full<VEC, HAS_V, SPLIT, QUANT>(x[p], T, pass0, lane_el);
-        else load_tail<VEC, HAS_V, SPLIT, QUANT>(x[p], T, pass0 + lane_el, cnt[p]);
-    }
+    const uint32_t lane_el = (uint32_t)tid * VEC;              // first element of the lane inside its tile
+    // the number of the tile's elements that fall to this lane
+    const int left = tile_cnt - (int)lane_el;
+    const int cnt = FULL ? VEC : (left >= VEC ? VEC : (left > 0 ? left : 0));
+    LaneIO<VEC> x, y;
+    if (FULL || cnt == VEC) load_full<VEC, HAS_V, SPLIT, QUANT>(x, T, tile0, lane_el);
+    else load_tail<VEC, HAS_V, SPLIT, QUANT>(x, T, tile0 + lane_el, cnt);
     store_table_entries<THREADS>(tab, entries, tid);
     __syncthreads();
-#pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-        // All lanes of a group run the update together (a lane with cnt == 0 may share its group
-        // with lanes that hold elements); lanes past the end compute on zeros and store nothing.
-        LaneIO<VEC> y;
-        update_lane<KIND, VEC, SPLIT, QUANT>(x[p], y, tab, c, T.lr, T.wd);
-        const int64_t pass0 = tile0 + (int64_t)p * kPass;
-        if (FULL || cnt[p] == VEC) store_full<VEC, HAS_V, SPLIT, QUANT>(y, T, pass0, lane_el, leader);
-        else store_tail<VEC, HAS_V, SPLIT, QUANT>(y, T, pass0 + lane_el, cnt[p], leader);
-    }
+    // All lanes of a group run the update together (a lane with cnt == 0 may share its group
+    // with lanes that hold elements); lanes past the end compute on zeros and store nothing.
+    update_lane<KIND, VEC, SPLIT, QUANT>(x, y, tab, c, T.lr, T.wd);
+    if (FULL || cnt == VEC) store_full<VEC, HAS_V, SPLIT, QUANT>(y, T, tile0, lane_el, leader);
+    else store_tail<VEC, HAS_V, SPLIT, QUANT>(y, T, tile0 + lane_el, cnt, leader);
 }
 
 // A workgroup handles one tile of one tensor and then retires (persistent workgroups that loop
 // over many tiles were measured 10 % slower: an iteration's loads then wait behind the previous
 // iteration's stores).  Order of issue: decode-table loads, the (tensor, tile) look-up, the
 // streaming loads; then the tables go to LDS.
-template <int KIND, int VEC, int THREADS, int PASSES, bool DIRECT, bool SPLIT, bool QUANT>
+template <int KIND, int VEC, int THREADS, bool DIRECT, bool SPLIT, bool QUANT>
 __global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
-    constexpr int kTile = THREADS * VEC * PASSES;   // elements per workgroup
+    constexpr int kTile = THREADS * VEC;       // elements per workgroup
     __shared__ DecodeTables tab;
     const int tid = (int)threadIdx.x;
     TableEntries entries;
@@ -876,19 +867,18 @@ __global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
     const int64_t tile0 = chunk * (int64_t)kTile;              // first element of the tile (wave-uniform)
     const int64_t rem = T.numel - tile0;                       // elements from there to the tensor's end
     if (rem >= kTile) {
-        step_tile<KIND, VEC, THREADS, PASSES, SPLIT, QUANT, true>(T, a.c, tab, entries, tile0, kTile, tid);
+        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, true>(T, a.c, tab, entries, tile0, kTile, tid);
     } else {
-        step_tile<KIND, VEC, THREADS, PASSES, SPLIT, QUANT, false>(T, a.c, tab, entries, tile0,
-                                                                   rem > 0 ? (int)rem : 0, tid);
+        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, false>(T, a.c, tab, entries, tile0, rem > 0 ? (int)rem : 0, tid);
     }
 }
 
 template <int KIND, bool SPLIT, bool QUANT>
 static hipError_t launch_variant(bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
-    constexpr int VEC = step_vec(KIND), THREADS = step_threads(KIND), PASSES = step_passes(KIND);
+    constexpr int VEC = step_vec(KIND), THREADS = step_threads(KIND);
     const dim3 grid((unsigned)n_blocks), block(THREADS);
-    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, PASSES, true, SPLIT, QUANT>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, PASSES, false, SPLIT, QUANT>), grid, block, 0, s, a);
+    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, true, SPLIT, QUANT>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, false, SPLIT, QUANT>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
@@ -914,10 +904,10 @@ hipError_t launch_step(int kind, bool direct, bool split, bool quant, const Step
 // read (gradients included) and every stream it writes is written back unchanged, through the same
 // chunk table, lane layout and access instructions.  Its rate is what the memory system delivers
 // for this access pattern, the ceiling the step kernel's rate is compared with.
-template <int KIND, int VEC, int THREADS, int PASSES, bool DIRECT>
+template <int KIND, int VEC, int THREADS, bool DIRECT>
 __global__ __launch_bounds__(THREADS) void probe_kernel(StepArgs a) {
     constexpr bool HAS_V = (KIND == 0);
-    constexpr int kPass = THREADS * VEC, kTile = kPass * PASSES;
+    constexpr int kTile = THREADS * VEC;
     const int tid = (int)threadIdx.x;
     TensorDev T;
     const int64_t chunk = locate_tile<DIRECT>(a, T);
@@ -926,31 +916,22 @@ __global__ __launch_bounds__(THREADS) void probe_kernel(StepArgs a) {
     const int64_t tile0 = chunk * (int64_t)kTile;
     const int64_t rem = T.numel - tile0;
     const int tile_cnt = rem >= kTile ? kTile : (int)rem;
-    LaneIO<VEC> x[PASSES];
-    int cnt[PASSES];
+    const int left = tile_cnt - (int)lane_el;
+    const int cnt = left >= VEC ? VEC : (left > 0 ? left : 0);
+    LaneIO<VEC> x;
+    if (cnt == VEC) load_full<VEC, HAS_V, true, true>(x, T, tile0, lane_el);
+    else load_tail<VEC, HAS_V, true, true>(x, T, tile0 + lane_el, cnt);
+    // The gradient takes no part in what is stored; an empty asm statement that names its registers
+    // keeps the load from being removed.
 #pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-        const int left = tile_cnt - p * kPass - (int)lane_el;
-        cnt[p] = left >= VEC ? VEC : (left > 0 ? left : 0);
-        const int64_t pass0 = tile0 + (int64_t)p * kPass;
-        if (cnt[p] == VEC) load_full<VEC, HAS_V, true, true>(x[p], T, pass0, lane_el);
-        else load_tail<VEC, HAS_V, true, true>(x[p], T, pass0 + lane_el, cnt[p]);
-    }
-#pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-        // The gradient takes no part in what is stored; an empty asm statement that names its
-        // registers keeps the load from being removed.
-#pragma unroll
-        for (int j = 0; j < VEC / 2; ++j) asm volatile("" : : "v"(x[p].g[j]));
-        const int64_t pass0 = tile0 + (int64_t)p * kPass;
-        if (cnt[p] == VEC) store_full<VEC, HAS_V, true, true>(x[p], T, pass0, lane_el, leader);
-        else store_tail<VEC, HAS_V, true, true>(x[p], T, pass0 + lane_el, cnt[p], leader);
-    }
+    for (int j = 0; j < VEC / 2; ++j) asm volatile("" : : "v"(x.g[j]));
+    if (cnt == VEC) store_full<VEC, HAS_V, true, true>(x, T, tile0, lane_el, leader);
+    else store_tail<VEC, HAS_V, true, true>(x, T, tile0 + lane_el, cnt, leader);
 }
 
 hipError_t launch_probe(int kind, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
     const dim3 grid((unsigned)n_blocks);
-#define FO_PROBE(K, DR) hipLaunchKernelGGL((probe_kernel<K, step_vec(K), step_threads(K), step_passes(K), DR>), grid, \
+#define FO_PROBE(K, DR) hipLaunchKernelGGL((probe_kernel<K, step_vec(K), step_threads(K), DR>), grid, \
                                            dim3(step_threads(K)), 0, s, a)
     if (kind == 0) { if (direct) FO_PROBE(0, true); else FO_PROBE(0, false); }
     else if (kind == 1) { if (direct) FO_PROBE(1, true); else FO_PROBE(1, false); }

@@ -96,3 +96,23 @@ def test_invalid_arguments_are_rejected_before_any_device_work():
     assert L.flashoptim_checkpoint_unpack(0, 0x100000, 64, arr, 1, C.byref(step), None) == -5
     assert "aligned" in fo.strerror(-2) and fo.strerror(0) == "ok" and fo.strerror(-99) == "unknown status"
     assert fo.version() >= 1
+
+
+def test_step_launch_count_is_one_launch_per_2_to_28_elements_of_whole_tiles():
+    import workloads as W
+    # a step call covers its list tile by tile (2048 elements for AdamW, 4096 for SGD and Lion, per tensor)
+    # and issues one kernel launch per 2^28 elements' worth of tiles
+    def expect(kind, numels):
+        tile = 2048 if kind == "adamw" else 4096
+        tiles = sum(-(-n // tile) for n in numels)
+        per_launch = (1 << 28) // tile
+        return -(-tiles // per_launch)
+    cases = [[], [1], [1 << 28], [(1 << 28) + 1], [5, 0, 7], [s.numel for s in W.llama31_8b()],
+             [s.numel for s in W.resnet50()], [(1 << 33) + 12345]]
+    for kind in ("adamw", "sgd", "lion"):
+        for numels in cases:
+            assert fo.step_launch_count(kind, numels) == expect(kind, numels), (kind, numels[:3])
+    assert fo.step_launch_count("adamw", [s.numel for s in W.llama31_8b()]) == 30
+    L = fo.load_library()
+    assert L.flashoptim_step_launch_count(3, None, 0) == -1
+    assert L.flashoptim_step_launch_count(0, (C.c_int64 * 1)(-5), 1) == -3
