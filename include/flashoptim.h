@@ -93,7 +93,8 @@ typedef struct flashoptim_lion_hp { float beta1, beta2; } flashoptim_lion_hp;
  * index table that the library builds once per distinct list and caches on the device; the
  * work is issued as a few back-to-back kernel launches on the given stream (one per 2^28
  * elements).  A list of length one is the gradient-release call (Section 3.4): it needs no
- * table and no device allocation.  The grad pointers are not part of the
+ * table and no device allocation.  Tables of the 256 most recently used lists are kept; a call
+ * with a further distinct list frees the least recently used one after synchronising the device.  The grad pointers are not part of the
  * cached identity of a list, so gradients may live in different buffers each step.
  *
  * flashoptim_adamw_step: Algorithm 4, the body of the loop after the gradient (reconstruct m, v, theta; AdamW

@@ -75,7 +75,7 @@ struct Plan {
 std::mutex g_mu;
 std::unordered_map<std::string, std::list<std::pair<std::string, Plan>>::iterator> g_index;
 std::list<std::pair<std::string, Plan>> g_plans;   // most recently used first
-constexpr size_t kMaxPlans = 64;
+constexpr size_t kMaxPlans = 256;   // least recently used beyond this are freed (after a device synchronisation)
 
 void destroy_plan(Plan& p) {
     int cur = 0;

@@ -303,7 +303,7 @@ def test_many_distinct_lists_evict_cached_tables():
     # more distinct lists than the library keeps cached tables for; every call must still be right
     spec = W.ParamSpec("w", (3000,), "matrix")
     results = []
-    for k in range(70):
+    for k in range(270):
         sts = [oracle.TensorState(W.theta0(spec, 100 * k + j, seed=14).numpy(), "sgd") for j in range(2)]
         bufs = [upload_state(s) for s in sts]
         for b in bufs:
