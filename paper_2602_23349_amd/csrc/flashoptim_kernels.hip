@@ -1553,6 +1553,9 @@ hipError_t launch_selftest(unsigned long long* counters, int section, const Step
 // segment with 128-bit accesses (segment starts are 16-byte aligned on both sides), the
 // ragged end byte by byte, and - when packing - zero-fills the padding up to pad_bytes.
 
+#ifndef FO_COPY_BATCH
+#define FO_COPY_BATCH 16
+#endif
 __global__ __launch_bounds__(kThreads) void copy_kernel(const CopySegment* segs, const uint2* chunks) {
     const uint2 ck = chunks[blockIdx.x];
     const CopySegment sg = segs[ck.x];
@@ -1561,7 +1564,18 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const CopySegment* segs,
     const int64_t end = (total - begin < kCopyChunkBytes) ? total : begin + kCopyChunkBytes;
     const uint8_t* src = sg.src;
     uint8_t* dst = sg.dst;
-    for (int64_t o = begin + (int64_t)threadIdx.x * 16; o < end; o += (int64_t)kThreads * 16) {
+    constexpr int kBatch = FO_COPY_BATCH;                 // 128-bit loads in flight per lane
+    constexpr int64_t kStride = (int64_t)kThreads * 16;
+    int64_t o = begin + (int64_t)threadIdx.x * 16;
+    // whole batches inside the copied bytes: all loads of a batch are issued before its stores
+    for (; o + (kBatch - 1) * kStride + 16 <= sg.bytes && o + (kBatch - 1) * kStride < end; o += kBatch * kStride) {
+        uint4 v[kBatch];
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) v[k] = ld128(src + o + k * kStride);
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) st128(dst + o + k * kStride, v[k].x, v[k].y, v[k].z, v[k].w);
+    }
+    for (; o < end; o += kStride) {
         if (o + 16 <= sg.bytes) {
             const uint4 v = ld128(src + o);
             st128(dst + o, v.x, v.y, v.z, v.w);
