@@ -902,7 +902,7 @@ hipError_t launch_step(int kind, bool direct, bool split, bool quant, const Step
 //
 // Moves exactly the bytes of one optimizer step with no arithmetic: every stream the step reads is
 // read (gradients included) and every stream it writes is written back unchanged, through the same
-// chunk table, lane layout and access instructions.  Its rate is what the memory system delivers
+// tile look-up, lane layout and access instructions.  Its rate is what the memory system delivers
 // for this access pattern, the ceiling the step kernel's rate is compared with.
 template <int KIND, int VEC, int THREADS, bool DIRECT>
 __global__ __launch_bounds__(THREADS) void probe_kernel(StepArgs a) {
@@ -1346,9 +1346,9 @@ void launch_nmse(bool variance, bool linear, const float* x, int64_t n, double* 
 //
 // Migration between a standard FP32 optimizer state (theta, m, v: 12 B/param for AdamW) and
 // the compressed layout: COMPRESS applies C, Q_m, Q_v (Algorithms 1-3) in one pass over a list;
-// the other direction applies the inverses.  Written with the plain exact forms; same chunk
-// table and lane layout (8 elements per lane, a lane quad per group) as the step kernels.
-static_assert(kCodecTile == kConvChunkElems, "the conversion chunk table is built for tiles of this size");
+// the other direction applies the inverses.  Written with the plain exact forms; same tile
+// look-up and lane layout (8 elements per lane, a lane quad per group) as the step kernels.
+static_assert(kCodecTile == kConvChunkElems, "the host builds the conversion's tables for tiles of this size");
 
 template <bool HAS_V, bool COMPRESS, bool DIRECT>
 __global__ __launch_bounds__(kThreads) void convert_kernel(StepArgs a) {
