@@ -195,6 +195,16 @@ def test_list_whose_tile_lookup_needs_several_steps(kind, hp):
     _run_list(kind, hp, specs, seed=21, dist="normal", scale=1e-3, per_tensor_sigma=False, steps=(1, 2), nthreads=0)
 
 
+def test_list_that_spans_several_kernel_launches():
+    # A call is issued as consecutive launches of 2^28 elements' worth of tiles: here the boundary between
+    # the first two launches falls inside the second tensor, and the third tensor ends raggedly in the
+    # second launch.  Every element of every tensor is compared.
+    sizes = [(1 << 28) - 5000, 70000, (1 << 26) + 123]
+    assert fo.step_launch_count("adamw", sizes) == 2
+    specs = [W.ParamSpec(f"t{i}", (n,), "matrix") for i, n in enumerate(sizes)]
+    _run_list("adamw", ADAMW, specs, seed=23, dist="normal", scale=1e-3, per_tensor_sigma=False, steps=(1, 2), nthreads=0)
+
+
 def test_gpt2_list_sgd():
     # workload 2: GPT-2 124M parameter list, per-tensor gradient scale log-uniform in [1e-5, 1e-2]
     _run_list("sgd", SGD, W.gpt2_small(), seed=0, dist="normal", scale=None, per_tensor_sigma=True, steps=(1, 2, 3))
