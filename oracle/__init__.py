@@ -17,7 +17,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # FLASHOPTIM_ORACLE_LIB: an alternative build to load instead (the mutant test plants mistakes
+        # in copies of the source and checks that the pins notice)
+        path = os.environ.get("FLASHOPTIM_ORACLE_LIB") or _build.build(force=False)
         _lib = C.CDLL(path)
         _declare(_lib)
     return _lib

@@ -104,3 +104,45 @@ def grads_for(specs, step, seed=0, dist="normal", scale=1e-3, per_tensor_sigma=F
 
 def weight_decay_for(spec, wd):
     return wd if spec.role == "matrix" else 0.0
+
+
+# ---- inputs whose quantisation lands exactly on a rounding tie (scale 1.0) --------------------------
+# Found by evaluating the printed operations of Algorithms 2 and 3 in numpy FP32; they hold none of the
+# method's decisions (the expected code is just "the even neighbour of k + 1/2").
+
+def _f32_neighbours(x, span):
+    base = int(np.float32(x).view(np.uint32))
+    return (np.arange(-span, span + 1, dtype=np.int64) + base).astype(np.uint32).view(np.float32)
+
+
+def tie_inputs_momentum():
+    """Momentum values m (to be quantised in a group whose absmax is 1.0) with 127 * 2m / (1 + |m|) == k + 1/2
+    exactly in FP32, of both signs, and the even neighbours."""
+    f = np.float32
+    ms, want = [], []
+    for k in range(0, 60):
+        a = (k + 0.5) / (254.0 - (k + 0.5))              # real solution of 127 * 2a / (1 + a) = k + 1/2
+        cand = _f32_neighbours(a, 3000)
+        den = (f(1.0) + np.abs(cand)).astype(np.float32)
+        y = (((f(2.0) * cand).astype(np.float32) / den).astype(np.float32) * f(127.0)).astype(np.float32)
+        for m in cand[y == f(k + 0.5)][:1]:
+            even = k if k % 2 == 0 else k + 1
+            ms += [m, -m]
+            want += [even, -even]
+    return ms, want
+
+
+def tie_inputs_variance():
+    """Variance values v (group absmax of sqrt(v) is 1.0) with 255 * sqrt(v) == k + 1/2 exactly in FP32."""
+    f = np.float32
+    vs, want = [], []
+    for k in range(0, 200):
+        for vr in _f32_neighbours((k + 0.5) / 255.0, 40):
+            if (vr * f(255.0)).astype(np.float32) != f(k + 0.5):
+                continue
+            v = (vr * vr).astype(np.float32)
+            if np.sqrt(v, dtype=np.float32) == vr:        # the square root gives back exactly this v'
+                vs.append(v)
+                want.append(k if k % 2 == 0 else k + 1)
+                break
+    return vs, want

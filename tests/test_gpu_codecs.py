@@ -164,6 +164,23 @@ def test_ragged_ends_write_nothing_past_the_end(n):
     assert tail_intact(th, 5.0)
 
 
+def test_exact_rounding_ties_take_the_even_code():
+    # inputs whose FP32 value before Round() is exactly k + 1/2 (scale 1.0): the device rounds them as the
+    # oracle does, in the standalone quantisers
+    from helpers import tie_inputs_momentum, tie_inputs_variance
+    ms, _ = tie_inputs_momentum()
+    vs, _ = tie_inputs_variance()
+    for vals, quant_gpu, quant_cpu, dt in ((ms, fo.quantize_momentum, oracle.quantize_momentum, torch.int8),
+                                           (vs, fo.quantize_variance, oracle.quantize_variance, torch.uint8)):
+        x = np.concatenate([np.array([1.0] + vals[i:i + 31], np.float32) for i in range(0, len(vals), 31)])
+        x = np.concatenate([x, np.zeros((-x.size) % 32, np.float32)])
+        q = torch.empty(x.size, dtype=dt, device="cuda")
+        s = torch.empty(x.size // 32, dtype=torch.float16, device="cuda")
+        quant_gpu(_dev(x), q, s)
+        wq, ws = quant_cpu(x)
+        assert np.array_equal(bits16(s), ws) and np.array_equal(q.cpu().numpy(), wq)
+
+
 def test_empty_inputs_are_noops():
     e32 = torch.empty(0, dtype=torch.float32, device="cuda")
     fo.split_weights(e32, torch.empty(0, dtype=torch.bfloat16, device="cuda"), torch.empty(0, dtype=torch.int8, device="cuda"))

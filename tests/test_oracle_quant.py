@@ -278,3 +278,24 @@ def test_companding_lowers_variance_quantisation_error():
     rel_l = np.abs(lb - vv) / vv
     assert np.median(rel_c) < 0.25 * np.median(rel_l)
     assert (lq == 0).mean() > 3 * (cq == 0).mean()       # linear codes lose far more entries entirely
+
+
+def test_codes_round_exact_ties_to_even():
+    # Reading Q4: when the FP32 value handed to Round() is exactly k + 1/2, the code is the even neighbour.
+    # The inputs are found by evaluating the printed operations in numpy FP32 (scale 1.0, so m' = m and
+    # v' = sqrt(v)); what is asserted is the tie rule alone.
+    from helpers import tie_inputs_momentum, tie_inputs_variance
+    ms, want_m = tie_inputs_momentum()
+    assert len(ms) >= 60 and any(w % 4 == 0 for w in want_m) and any(w % 4 == 2 for w in want_m)
+    for i in range(0, len(ms), 31):                       # groups of 31 ties plus the element 1.0 that fixes the scale
+        grp = np.array([1.0] + ms[i:i + 31], np.float32)
+        q, s = oracle.quantize_momentum(grp)
+        assert s[0] == 0x3C00 and q[0] == 127
+        assert list(q[1:]) == want_m[i:i + 31]
+    vs, want_v = tie_inputs_variance()
+    assert len(vs) >= 60 and any(w % 4 == 0 for w in want_v) and any(w % 4 == 2 for w in want_v)
+    for i in range(0, len(vs), 31):
+        grp = np.array([1.0] + vs[i:i + 31], np.float32)
+        q, s = oracle.quantize_variance(grp)
+        assert s[0] == 0x3C00 and q[0] == 255
+        assert list(q[1:]) == want_v[i:i + 31]
