@@ -58,3 +58,44 @@ def test_random_hyperparameters_and_states(case):
         compare_state(download(buf), st, where=f"case {case} {kind} n={n} t={t}", report=report)
     bad = [r for r in report if r[2]]
     assert not bad, (kind, n, lr, wd, b1, b2, eps, t0, gscale, bad)
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_random_lists(case):
+    # random lists (2..40 tensors, sizes log-uniform over 1..3M elements, per-tensor lr / weight decay),
+    # random code states, three steps through the multi-tensor path
+    rng = np.random.default_rng(5000 + case)
+    kind = ("adamw", "sgd", "lion", "adamw")[case % 4]
+    n_t = int(rng.integers(2, 41))
+    sizes = [int(10.0 ** rng.uniform(0, 6.5)) for _ in range(n_t)]
+    f = lambda v: float(np.float32(v))
+    b1, b2, eps = f(rng.choice([0.9, 0.95, 0.5])), f(rng.choice([0.999, 0.99, 0.95])), f(10.0 ** rng.uniform(-10, -6))
+    sts = [_random_state(kind, n, 100 * case + i, seed=91) for i, n in enumerate(sizes)]
+    bufs = [upload_state(s) for s in sts]
+    hyper = [(f(10.0 ** rng.uniform(-5, -1.5)), f(rng.choice([0.0, 0.01, 0.1]))) for _ in sizes]
+    for b, (lr, wd) in zip(bufs, hyper):
+        b.lr, b.weight_decay = lr, wd
+    tl = fo.TensorList(bufs)
+    report = []
+    for t in (1, 2, 3):
+        gs = [W.grad_bf16(W.ParamSpec("r", (n,), "matrix"), 100 * case + i, t, seed=91, scale=10.0 ** rng.uniform(-5, -2))
+              for i, n in enumerate(sizes)]
+        for b, g in zip(bufs, gs):
+            b.grad.copy_(g.cuda())
+        if kind == "adamw":
+            fo.adamw_step(tl, b1, b2, eps, t)
+        elif kind == "sgd":
+            fo.sgd_step(tl, b1)
+        else:
+            fo.lion_step(tl, b1, b2)
+        for i, (st, g, (lr, wd)) in enumerate(zip(sts, gs, hyper)):
+            gb = g.view(torch.int16).numpy().view(np.uint16)
+            if kind == "adamw":
+                oracle.adamw_step(st, gb, lr, wd, b1, b2, eps, t)
+            elif kind == "sgd":
+                oracle.sgd_step(st, gb, lr, wd, b1)
+            else:
+                oracle.lion_step(st, gb, lr, wd, b1, b2)
+            compare_state(download(bufs[i]), st, where=f"list case {case} {kind} tensor {i} n={sizes[i]} t={t}", report=report)
+    bad = [r for r in report if r[2]]
+    assert not bad, (kind, sizes, bad)
