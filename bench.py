@@ -306,7 +306,8 @@ def main():
                    "mode": args.mode, "variant": args.variant, "calls_per_step": calls,
                    "kernel_launches_per_step": launches,
                    "resident_bytes_per_param": (7.125 if kind == "adamw" else 6.0625) - (2 if release else 0),
-                   "min_ms_step": min(per_step_ms), "max_ms_step": max(per_step_ms),
+                   "min_ms_step": min(per_step_ms), "median_ms_step": sorted(per_step_ms)[len(per_step_ms) // 2],
+                   "max_ms_step": max(per_step_ms),
                    "wall_ms_per_step": wall * 1e3 / args.steps},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
