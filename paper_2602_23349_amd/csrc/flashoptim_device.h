@@ -29,7 +29,7 @@ constexpr int step_vec(int kind) { return kind == 0 ? FO_VEC_ADAMW : FO_VEC_SGD_
 constexpr int step_threads(int kind) { return kind == 0 ? FO_THREADS_ADAMW : FO_THREADS_SGD_LION; }
 constexpr int chunk_elems(int kind) { return step_threads(kind) * step_vec(kind); }
 #ifndef FO_COPY_CHUNK_KB
-#define FO_COPY_CHUNK_KB 64
+#define FO_COPY_CHUNK_KB 128
 #endif
 constexpr int kCopyChunkBytes = FO_COPY_CHUNK_KB * 1024;   // checkpoint copy: bytes per workgroup
 

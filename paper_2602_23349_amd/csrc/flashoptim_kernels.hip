@@ -1556,7 +1556,11 @@ hipError_t launch_selftest(unsigned long long* counters, int section, const Step
 #ifndef FO_COPY_BATCH
 #define FO_COPY_BATCH 16
 #endif
-__global__ __launch_bounds__(kThreads) void copy_kernel(const CopySegment* segs, const uint2* chunks) {
+#ifndef FO_COPY_THREADS
+#define FO_COPY_THREADS 512
+#endif
+constexpr int kCopyThreads = FO_COPY_THREADS;
+__global__ __launch_bounds__(kCopyThreads) void copy_kernel(const CopySegment* segs, const uint2* chunks) {
     const uint2 ck = chunks[blockIdx.x];
     const CopySegment sg = segs[ck.x];
     const int64_t begin = (int64_t)ck.y * kCopyChunkBytes;
@@ -1565,7 +1569,7 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const CopySegment* segs,
     const uint8_t* src = sg.src;
     uint8_t* dst = sg.dst;
     constexpr int kBatch = FO_COPY_BATCH;                 // 128-bit loads in flight per lane
-    constexpr int64_t kStride = (int64_t)kThreads * 16;
+    constexpr int64_t kStride = (int64_t)kCopyThreads * 16;
     int64_t o = begin + (int64_t)threadIdx.x * 16;
     // whole batches inside the copied bytes: all loads of a batch are issued before its stores
     for (; o + (kBatch - 1) * kStride + 16 <= sg.bytes && o + (kBatch - 1) * kStride < end; o += kBatch * kStride) {
@@ -1588,7 +1592,7 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const CopySegment* segs,
 // (Issuing the copy as several shorter launches, which helps the step kernels, changed its rate by
 // less than 2 %: it stays one launch.)
 void launch_copy(const CopySegment* segs, const uint2* chunks, int64_t n_chunks, hipStream_t s) {
-    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)n_chunks), dim3(kThreads), 0, s, segs, chunks);
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)n_chunks), dim3(kCopyThreads), 0, s, segs, chunks);
 }
 
 }  // namespace fo
