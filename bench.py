@@ -58,6 +58,9 @@ def parse_args():
                     help="flash: both techniques on (the product path); wsplit: split weights + FP32 states; "
                          "oquant: FP32 weights + 8-bit states; ref: plain FP32 optimizer (BF16 gradients). "
                          "The last three are the ablation entry points (fused mode only).")
+    ap.add_argument("--rounding", default="default", choices=["default", "exact"],
+                    help="AdamW only: default = flashoptim_adamw_step (faithfully rounded square root and division, "
+                         "inside the parity bar); exact = flashoptim_adamw_step_exact (bit-identical to the oracle)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the timing of the arithmetic-free stream probe (same traffic as the step)")
@@ -100,7 +103,7 @@ def build_state(fo, W, torch, specs, kind, hp, dist, scale, seed, with_grads, va
     return bufs
 
 
-def step_call(fo, kind, tl, hp, t):
+def step_call(fo, kind, tl, hp, t, exact=False):
     if isinstance(tl, fo.TensorListEx):
         if kind == "adamw":
             fo.adamw_step_ex(tl, hp["beta1"], hp["beta2"], hp["eps"], t)
@@ -109,7 +112,7 @@ def step_call(fo, kind, tl, hp, t):
         else:
             fo.lion_step_ex(tl, hp["beta1"], hp["beta2"])
     elif kind == "adamw":
-        fo.adamw_step(tl, hp["beta1"], hp["beta2"], hp["eps"], t)
+        (fo.adamw_step_exact if exact else fo.adamw_step)(tl, hp["beta1"], hp["beta2"], hp["eps"], t)
     elif kind == "sgd":
         fo.sgd_step(tl, hp["momentum"])
     else:
@@ -213,6 +216,7 @@ def main():
     seed = 0
     release = args.mode == "grad_release"
     ckpt = args.mode.startswith("ckpt")
+    exact = args.rounding == "exact"
 
     if args.variant != "flash" and args.mode != "fused":
         print("bench.py: --variant other than flash is available in fused mode only", file=sys.stderr)
@@ -243,10 +247,10 @@ def main():
 
         def do_step(t):
             for s in singles:
-                step_call(fo, kind, s, hp, t)
+                step_call(fo, kind, s, hp, t, exact)
     else:
         def do_step(t):
-            step_call(fo, kind, tl, hp, t)
+            step_call(fo, kind, tl, hp, t, exact)
 
     t = 0
     for _ in range(args.warmup):
@@ -303,7 +307,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "optimizer": kind, "tensors": len(specs), "params": n_params,
-                   "mode": args.mode, "variant": args.variant, "calls_per_step": calls,
+                   "mode": args.mode, "variant": args.variant,
+                   "rounding": (args.rounding if kind == "adamw" and args.variant == "flash" and not ckpt else None),
+                   "calls_per_step": calls,
                    "kernel_launches_per_step": launches,
                    "resident_bytes_per_param": (7.125 if kind == "adamw" else 6.0625) - (2 if release else 0),
                    "min_ms_step": min(per_step_ms), "median_ms_step": sorted(per_step_ms)[len(per_step_ms) // 2],

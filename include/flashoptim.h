@@ -35,7 +35,8 @@
  *    their own element or group but never cause out-of-bounds accesses.  An infinite
  *    weight keeps rho = 0; the rho byte stored next to a NaN weight is unspecified.
  *  - Arithmetic: IEEE binary32, round-to-nearest-even, subnormals kept, no fused
- *    multiply-add, in the order the algorithms print it; divisions by a group scale
+ *    multiply-add, in the order the algorithms print it (one documented exception: the
+ *    default AdamW step rounds two operations faithfully, see flashoptim_adamw_step); divisions by a group scale
  *    or by a bias correction 1 - beta^t multiply by the correctly rounded FP32
  *    reciprocal of that scalar.
  *  - There is no CPU fallback: without a HIP device every compute entry point
@@ -102,9 +103,23 @@ typedef struct flashoptim_lion_hp { float beta1, beta2; } flashoptim_lion_hp;
  * flashoptim_sgd_step:   Algorithm 5, loop body (m <- mu m + g; theta <- theta - eta (m + lambda theta)).
  * flashoptim_lion_step:  Algorithm 6, loop body (u = sign(b1 m + (1-b1) g); m <- b2 m + (1-b2) g;
  *   theta <- theta - eta (u + lambda theta)); sign(0) = 0.
- * tensors: host array of n_tensors descriptors (n_tensors >= 0). */
+ * tensors: host array of n_tensors descriptors (n_tensors >= 0).
+ *
+ * Rounding of the AdamW update (the two per-element operations sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps)):
+ *   flashoptim_adamw_step        faithful: each is the hardware estimate plus one FMA correction, whose value
+ *                                before the final rounding is within ~1e-6 ulp of the exact one.  The result is
+ *                                the correctly rounded one except when the exact value lies that close to the
+ *                                midpoint of two FP32 numbers (about one element in 10^6 per operation), and then
+ *                                its other neighbour.  Such a 1-ulp difference reaches the stored theta' / rho in
+ *                                about one element in 10^9 per step (rho then differs by one unit); the momentum
+ *                                and variance codes and all scales never depend on it and are always exact.
+ *   flashoptim_adamw_step_exact  both are correctly rounded for every input: the whole step is bit-identical
+ *                                to the arithmetic stated above.  About 4 % slower on MI355X.
+ * Everything else is identical between the two. */
 int flashoptim_adamw_step(const flashoptim_tensor* tensors, int64_t n_tensors,
                           const flashoptim_adamw_hp* hp, void* stream);
+int flashoptim_adamw_step_exact(const flashoptim_tensor* tensors, int64_t n_tensors,
+                                const flashoptim_adamw_hp* hp, void* stream);
 int flashoptim_sgd_step(const flashoptim_tensor* tensors, int64_t n_tensors,
                         const flashoptim_sgd_hp* hp, void* stream);
 int flashoptim_lion_step(const flashoptim_tensor* tensors, int64_t n_tensors,
@@ -247,9 +262,15 @@ const char* flashoptim_strerror(int status);
  *   [3] momentum codes (Algorithm 2) and [4] variance codes (Algorithm 3): the estimate equals the
  *       exact code wherever the kernel's tie test does not ask for the exact evaluation.
  *   [5] short division == IEEE division on 2^26 + 2^24 operand pairs inside its range.
- * n_checked, n_failed: HOST arrays of 6 counters (one per section above).  Waits for completion.
+ *   [6] faithful square root and [7] faithful division of flashoptim_adamw_step: within 1 ulp of the IEEE
+ *       result on the inputs of [2] and [5].
+ * n_checked, n_failed: HOST arrays of 8 counters (one per section above).  Waits for completion.
  * Returns FLASHOPTIM_OK, FLASHOPTIM_ERR_SELFTEST if any check failed, or another status. */
 int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream);
+/* How often the faithful forms differ from the exactly rounded results at all, measured on this device:
+ * counts (HOST, 4 entries) = {square-root inputs, of these not exact, division operand pairs, of these not
+ * exact}.  Waits for completion.  FLASHOPTIM_ERR_SELFTEST if any result is off by more than one ulp. */
+int flashoptim_faithful_rounding_stats(int64_t* counts, void* stream);
 /* Number of kernel launches one step call of `kind` issues for a list with these element counts
  * (host arithmetic only; for reading profiles: per-kernel durations are per launch).  Negative
  * status on invalid arguments. */

@@ -16,12 +16,13 @@ _lib = None
 KIND = {"adamw": 0, "sgd": 1, "lion": 2}
 
 EXPORTED_SYMBOLS = [
-    "flashoptim_adamw_step", "flashoptim_sgd_step", "flashoptim_lion_step",
+    "flashoptim_adamw_step", "flashoptim_adamw_step_exact", "flashoptim_sgd_step", "flashoptim_lion_step",
     "flashoptim_split_weights", "flashoptim_reconstruct_weights",
     "flashoptim_quantize_momentum", "flashoptim_dequantize_momentum",
     "flashoptim_quantize_variance", "flashoptim_dequantize_variance",
     "flashoptim_checkpoint_size", "flashoptim_checkpoint_pack", "flashoptim_checkpoint_unpack",
     "flashoptim_strerror", "flashoptim_last_hip_error", "flashoptim_release_cache", "flashoptim_version",
+    "flashoptim_faithful_rounding_stats",
     "flashoptim_step_launch_count",
     "flashoptim_selftest", "flashoptim_split_weights_i16", "flashoptim_reconstruct_weights_i16",
     "flashoptim_reconstruction_sweep",
@@ -102,6 +103,7 @@ def load_library():
     L.flashoptim_checkpoint_pack.argtypes = [i32, C.POINTER(_Tensor), i64, i64, vp, i64, vp]
     L.flashoptim_checkpoint_unpack.argtypes = [i32, vp, i64, C.POINTER(_Tensor), i64, C.POINTER(i64), vp]
     L.flashoptim_selftest.argtypes = [C.POINTER(i64), C.POINTER(i64), vp]
+    L.flashoptim_faithful_rounding_stats.argtypes = [C.POINTER(i64), vp]
     L.flashoptim_strerror.argtypes = [i32]
     L.flashoptim_strerror.restype = C.c_char_p
     for name in EXPORTED_SYMBOLS:
@@ -248,6 +250,13 @@ def adamw_step(tensors, beta1, beta2, eps, step, stream=None):
     _check(load_library().flashoptim_adamw_step(tl.array, tl.n, C.byref(hp), _stream(stream)), "flashoptim_adamw_step")
 
 
+def adamw_step_exact(tensors, beta1, beta2, eps, step, stream=None):
+    tl = _as_list(tensors)
+    hp = _AdamWHp(beta1, beta2, eps, int(step))
+    _check(load_library().flashoptim_adamw_step_exact(tl.array, tl.n, C.byref(hp), _stream(stream)),
+           "flashoptim_adamw_step_exact")
+
+
 def sgd_step(tensors, momentum, stream=None):
     tl = _as_list(tensors)
     hp = _SgdHp(momentum)
@@ -362,10 +371,17 @@ def checkpoint_unpack(kind, blob, tensors, stream=None):
     return int(step.value)
 
 
+def faithful_rounding_stats(stream=None):
+    """(square-root inputs, of these not exactly rounded, division operand pairs, of these not exactly rounded)."""
+    counts = (C.c_int64 * 4)()
+    _check(load_library().flashoptim_faithful_rounding_stats(counts, _stream(stream)), "flashoptim_faithful_rounding_stats")
+    return tuple(counts)
+
+
 def selftest(stream=None):
-    """Runs the device self-test; returns (status, checked[6], failed[6])."""
-    checked = (C.c_int64 * 6)()
-    failed = (C.c_int64 * 6)()
+    """Runs the device self-test; returns (status, checked[8], failed[8])."""
+    checked = (C.c_int64 * 8)()
+    failed = (C.c_int64 * 8)()
     status = load_library().flashoptim_selftest(checked, failed, _stream(stream))
     if status not in (0, -6):
         raise FlashOptimError(status, "flashoptim_selftest")

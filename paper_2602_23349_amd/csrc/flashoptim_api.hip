@@ -217,12 +217,14 @@ int to_dev_ex(const flashoptim_tensor_ex* t, int64_t n, bool has_v, bool split, 
     return FLASHOPTIM_OK;
 }
 
-// What a multi-tensor launch runs: an optimizer step, a layout conversion, or the stream probe.
-enum LiveOp { kOpStep = 0, kOpCompress = 1, kOpDecompress = 2, kOpProbe = 3 };
+// What a multi-tensor launch runs: an optimizer step (kOpStepExact: with the exactly rounded square root
+// and division of the AdamW update), a layout conversion, or the stream probe.
+enum LiveOp { kOpStep = 0, kOpCompress = 1, kOpDecompress = 2, kOpProbe = 3, kOpStepExact = 4 };
 
 hipError_t launch_segment(LiveOp op, int kind, bool direct, bool split, bool quant, const StepArgs& a, int64_t blocks,
                           hipStream_t stream) {
-    if (op == kOpStep) return fo::launch_step(kind, direct, split, quant, a, blocks, stream);
+    if (op == kOpStep || op == kOpStepExact)
+        return fo::launch_step(kind, direct, split, quant, op == kOpStepExact, a, blocks, stream);
     if (op == kOpProbe) return fo::launch_probe(kind, direct, a, blocks, stream);
     return fo::launch_convert(kind == FLASHOPTIM_ADAMW, op == kOpCompress, direct, a, blocks, stream);
 }
@@ -248,7 +250,7 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
     StepArgs a;
     std::memset(&a, 0, sizeof(a));
     a.c = c;
-    const int64_t ce = (op == kOpStep || op == kOpProbe) ? fo::chunk_elems(kind) : fo::kConvChunkElems;
+    const int64_t ce = (op == kOpCompress || op == kOpDecompress) ? fo::kConvChunkElems : fo::chunk_elems(kind);
     // one workgroup per chunk: the launch grid is a 31-bit count
     int64_t total_chunks = 0;
     for (const TensorDev& d : live) total_chunks += (d.numel + ce - 1) / ce;
@@ -368,7 +370,8 @@ int run_step_ex(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors
     std::vector<TensorDev> live;
     int rc = to_dev_ex(tensors, n_tensors, kind == FLASHOPTIM_ADAMW, split, quant, live);
     if (rc != FLASHOPTIM_OK) return rc;
-    return launch_live(kind, split, quant, live, c, static_cast<hipStream_t>(stream_));
+    // the ablation and reference variants always use the exactly rounded arithmetic
+    return launch_live(kind, split, quant, live, c, static_cast<hipStream_t>(stream_), kOpStepExact);
 }
 
 // 1 / (float)(1 - beta^t): the bias correction is formed in double and rounded to FP32
@@ -501,6 +504,13 @@ int flashoptim_adamw_step(const flashoptim_tensor* tensors, int64_t n_tensors, c
     StepConsts c;
     if (!adamw_consts(hp, c)) return FLASHOPTIM_ERR_INVALID_ARG;
     return run_step(FLASHOPTIM_ADAMW, tensors, n_tensors, c, stream);
+}
+
+int flashoptim_adamw_step_exact(const flashoptim_tensor* tensors, int64_t n_tensors, const flashoptim_adamw_hp* hp,
+                                void* stream) {
+    StepConsts c;
+    if (!adamw_consts(hp, c)) return FLASHOPTIM_ERR_INVALID_ARG;
+    return run_step(FLASHOPTIM_ADAMW, tensors, n_tensors, c, stream, kOpStepExact);
 }
 
 int flashoptim_sgd_step(const flashoptim_tensor* tensors, int64_t n_tensors, const flashoptim_sgd_hp* hp,
@@ -745,25 +755,27 @@ int flashoptim_checkpoint_unpack(int kind, const void* blob, int64_t blob_bytes,
     return FLASHOPTIM_OK;
 }
 
-int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream_) {
-    if (!n_checked || !n_failed) return FLASHOPTIM_ERR_INVALID_ARG;
+// Runs the self-test sections and copies the raw device counters to h.
+static int run_selftest(unsigned long long (&h)[fo::kSelftestCounters], bool only_faithful, void* stream_) {
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     unsigned long long* d = nullptr;
     FO_HIP(hipMalloc((void**)&d, fo::kSelftestCounters * sizeof(unsigned long long)));
     hipError_t e = hipMemsetAsync(d, 0, fo::kSelftestCounters * sizeof(unsigned long long), stream);
     StepConsts c;
     std::memset(&c, 0, sizeof(c));
-    for (int section = 0; section < 4 && e == hipSuccess; ++section) e = fo::launch_selftest(d, section, c, 1.0f, stream);
-    if (e == hipSuccess) e = fo::launch_selftest(d, 5, c, 1.0f, stream);
-    // variance codes: bias corrections of steps 1, 2, 10, 1000 and "infinity", three group scales
-    const int64_t steps[5] = {1, 2, 10, 1000, 100000000};
-    const float scales[3] = {0.000244140625f /* 2^-12 */, 0.00131988525390625f, 0.03125f};
-    for (int i = 0; i < 5 && e == hipSuccess; ++i) {
-        c.rbc2 = recip_bias_correction(0.999f, steps[i]);
-        c.root_bc2 = (float)std::sqrt(1.0 / (double)c.rbc2);
-        for (int k = 0; k < 3 && e == hipSuccess; ++k) e = fo::launch_selftest(d, 4, c, 1.0f / scales[k], stream);
+    for (int section = 6; section < 8 && e == hipSuccess; ++section) e = fo::launch_selftest(d, section, c, 1.0f, stream);
+    if (!only_faithful) {
+        for (int section = 0; section < 4 && e == hipSuccess; ++section) e = fo::launch_selftest(d, section, c, 1.0f, stream);
+        if (e == hipSuccess) e = fo::launch_selftest(d, 5, c, 1.0f, stream);
+        // variance codes: bias corrections of steps 1, 2, 10, 1000 and "infinity", three group scales
+        const int64_t steps[5] = {1, 2, 10, 1000, 100000000};
+        const float scales[3] = {0.000244140625f /* 2^-12 */, 0.00131988525390625f, 0.03125f};
+        for (int i = 0; i < 5 && e == hipSuccess; ++i) {
+            c.rbc2 = recip_bias_correction(0.999f, steps[i]);
+            c.root_bc2 = (float)std::sqrt(1.0 / (double)c.rbc2);
+            for (int k = 0; k < 3 && e == hipSuccess; ++k) e = fo::launch_selftest(d, 4, c, 1.0f / scales[k], stream);
+        }
     }
-    unsigned long long h[fo::kSelftestCounters] = {0};
     if (e == hipSuccess) e = hipMemcpyAsync(h, d, sizeof(h), hipMemcpyDeviceToHost, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     (void)hipFree(d);
@@ -772,13 +784,31 @@ int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream_) {
         (void)hipGetLastError();
         return FLASHOPTIM_ERR_HIP;
     }
+    return FLASHOPTIM_OK;
+}
+
+int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream) {
+    if (!n_checked || !n_failed) return FLASHOPTIM_ERR_INVALID_ARG;
+    unsigned long long h[fo::kSelftestCounters] = {0};
+    const int rc = run_selftest(h, false, stream);
+    if (rc != FLASHOPTIM_OK) return rc;
     int64_t failed = 0;
-    for (int sct = 0; sct < fo::kSelftestCounters / 2; ++sct) {
+    for (int sct = 0; sct < fo::kSelftestSectionCount; ++sct) {
         n_checked[sct] = (int64_t)h[2 * sct];
         n_failed[sct] = (int64_t)h[2 * sct + 1];
         failed += n_failed[sct];
     }
     return failed == 0 ? FLASHOPTIM_OK : FLASHOPTIM_ERR_SELFTEST;
+}
+
+int flashoptim_faithful_rounding_stats(int64_t* counts, void* stream) {
+    if (!counts) return FLASHOPTIM_ERR_INVALID_ARG;
+    unsigned long long h[fo::kSelftestCounters] = {0};
+    const int rc = run_selftest(h, true, stream);
+    if (rc != FLASHOPTIM_OK) return rc;
+    counts[0] = (int64_t)h[12]; counts[1] = (int64_t)h[16];     // square root: inputs, results that are not the exact one
+    counts[2] = (int64_t)h[14]; counts[3] = (int64_t)h[17];     // division:    inputs, results that are not the exact one
+    return (h[13] == 0 && h[15] == 0) ? FLASHOPTIM_OK : FLASHOPTIM_ERR_SELFTEST;
 }
 
 const char* flashoptim_strerror(int status) {

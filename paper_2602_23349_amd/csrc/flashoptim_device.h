@@ -92,7 +92,7 @@ struct CopySegment {
     int64_t pad_bytes;   // >= bytes; [bytes, pad_bytes) of dst is zero-filled
 };
 
-hipError_t launch_step(int kind, bool direct, bool split, bool quant, const StepArgs& a, int64_t n_blocks,
+hipError_t launch_step(int kind, bool direct, bool split, bool quant, bool exact, const StepArgs& a, int64_t n_blocks,
                        hipStream_t s);
 constexpr int kConvChunkElems = 256 * 8;   // elements per workgroup of the layout-conversion kernel
 hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s);
@@ -106,7 +106,8 @@ void launch_dequantize(bool variance, bool linear, const void* q, const uint16_t
                        hipStream_t s);
 void launch_nmse(bool variance, bool linear, const float* x, int64_t n, double* sums, hipStream_t s);
 void launch_copy(const CopySegment* segs, const uint2* chunks, int64_t n_chunks, hipStream_t s);
-constexpr int kSelftestCounters = 12;   // two per section
+constexpr int kSelftestSectionCount = 8;
+constexpr int kSelftestCounters = 18;   // two per section, then the inexact counts of sections 6 and 7
 hipError_t launch_selftest(unsigned long long* counters, int section, const StepConsts& c, float scale_r,
                            hipStream_t s);
 

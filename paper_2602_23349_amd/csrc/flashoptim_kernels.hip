@@ -177,6 +177,23 @@ __device__ __forceinline__ float div_rn_midrange(float n, float d) {
     return q;
 }
 
+// Faithful square root and division: one Newton-type correction of the 1-ulp hardware estimate, each
+// step one FMA.  The value before the final rounding is within ~1e-6 ulp of the exact one, so the result
+// is the correctly rounded one except when the exact value lies that close to the middle between two
+// FP32 numbers (about one operand in a million); then it is the other neighbour.  Operand ranges as for
+// the exact short forms; the square root clamps its argument at the smallest normal number (a
+// subnormal v_hat has a root below 1e-19, which vanishes next to any admissible eps).
+__device__ __forceinline__ float sqrt_faithful(float x) {
+    const float y = __builtin_amdgcn_rsqf(fmaxf(x, 1.17549435e-38f));
+    const float s = x * y, h = 0.5f * y;
+    return fmaf(fmaf(-s, s, x), h, s);
+}
+__device__ __forceinline__ float div_faithful(float n, float d) {
+    const float r = __builtin_amdgcn_rcpf(d);
+    const float q = n * r;
+    return fmaf(fmaf(-d, q, n), r, q);
+}
+
 // Exact Q_m code (low byte of the result) of one element given the reciprocal group scale
 // (Algorithm 2, encoder).
 __device__ __forceinline__ uint32_t m_code_exact(float m, float r) {
@@ -625,7 +642,10 @@ __device__ __forceinline__ void split_block(LaneIO<VEC>& y, const DecodeTables& 
 // group (lane ^ 1, and lane ^ 2, lane ^ 3 when VEC == 8) must execute this function with it.
 // SPLIT / QUANT: the paper's ablations (Section 4.3).  SPLIT = false keeps the master weight in
 // FP32 (x.th32 -> y.th32); QUANT = false keeps the states in FP32 (x.m32, x.v32 -> y.m32, y.v32).
-template <int KIND, int VEC, bool SPLIT, bool QUANT>
+// EXACT (AdamW only): sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps) are the correctly rounded results for
+// every input; otherwise they are the faithful forms above.  Everything else, the state codes and
+// scales included, is exact in both modes.
+template <int KIND, int VEC, bool SPLIT, bool QUANT, bool EXACT>
 __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y, const DecodeTables& tab,
                                             const StepConsts& c, float lr, float wd) {
     constexpr bool HAS_V = (KIND == 0);
@@ -707,11 +727,12 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
         const float nmin = amin_m * c.rbc1, nmax = amax_m * c.rbc1;
         // sqrt(v_hat): the short sequence unless some lane holds a value below 2^-96
         // (exact zeros take the general sequence too: one comparison covers both)
-        const bool sqrt_general = any_lane(vmin < kSqrtFastMin);
+        const bool sqrt_general = EXACT && any_lane(vmin < kSqrtFastMin);
         // m_hat / (sqrt(v_hat) + eps): the short division when every operand of the lane is well
         // inside the normal range (eps <= den <= sqrt(v_hat max) + eps), else the general one
+        // (the faithful division has no lower limit on the numerator)
         const bool div_fast = (c.eps >= kDivFastLo) && (c.eps <= 1.0f) &&
-                              !any_lane(!(nmin >= kDivFastLo && nmax <= kDivFastHi && vmax <= kDivFastHi));
+                              !any_lane(!((!EXACT || nmin >= kDivFastLo) && nmax <= kDivFastHi && vmax <= kDivFastHi));
 #pragma unroll
         for (int j = 0; j < VEC / 4; ++j) {
             float mh4[4], vh4[4], quo[4], tht[4];
@@ -720,19 +741,33 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
                 mh4[k] = mt[4 * j + k] * c.rbc1;
                 vh4[k] = vt[4 * j + k] * c.rbc2;
             }
-            if (sqrt_general) {
+            if (EXACT) {
+                if (sqrt_general) {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrtf(vh4[k]);
+                    for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrtf(vh4[k]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrt_rn_midrange(vh4[k]);
+                }
+                if (div_fast) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) quo[k] = div_rn_midrange(mh4[k], rh[4 * j + k] + c.eps);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) quo[k] = mh4[k] / (rh[4 * j + k] + c.eps);
+                }
+            } else if (div_fast) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    rh[4 * j + k] = sqrt_faithful(vh4[k]);
+                    quo[k] = div_faithful(mh4[k], rh[4 * j + k] + c.eps);
+                }
             } else {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrt_rn_midrange(vh4[k]);
-            }
-            if (div_fast) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) quo[k] = div_rn_midrange(mh4[k], rh[4 * j + k] + c.eps);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) quo[k] = mh4[k] / (rh[4 * j + k] + c.eps);
+                for (int k = 0; k < 4; ++k) {
+                    rh[4 * j + k] = sqrtf(vh4[k]);
+                    quo[k] = mh4[k] / (rh[4 * j + k] + c.eps);
+                }
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -830,7 +865,7 @@ __device__ __forceinline__ int64_t locate_tile(const StepArgs& a, TensorDev& T) 
 // tensor but possibly its last); the code then has no per-lane case distinction at all.
 // (Variants in which a workgroup loads two or four such tiles up front and then updates them in
 // turn - fewer look-ups, more bytes in flight per workgroup - ran at the same rate.)
-template <int KIND, int VEC, int THREADS, bool SPLIT, bool QUANT, bool FULL>
+template <int KIND, int VEC, int THREADS, bool SPLIT, bool QUANT, bool EXACT, bool FULL>
 __device__ __forceinline__ void step_tile(const TensorDev& T, const StepConsts& c, DecodeTables& tab,
                                           const TableEntries& entries, int64_t tile0, int tile_cnt, int tid) {
     constexpr bool HAS_V = (KIND == 0);
@@ -846,7 +881,7 @@ __device__ __forceinline__ void step_tile(const TensorDev& T, const StepConsts& 
     __syncthreads();
     // All lanes of a group run the update together (a lane with cnt == 0 may share its group
     // with lanes that hold elements); lanes past the end compute on zeros and store nothing.
-    update_lane<KIND, VEC, SPLIT, QUANT>(x, y, tab, c, T.lr, T.wd);
+    update_lane<KIND, VEC, SPLIT, QUANT, EXACT>(x, y, tab, c, T.lr, T.wd);
     if (FULL || cnt == VEC) store_full<VEC, HAS_V, SPLIT, QUANT>(y, T, tile0, lane_el, leader);
     else store_tail<VEC, HAS_V, SPLIT, QUANT>(y, T, tile0 + lane_el, cnt, leader);
 }
@@ -855,7 +890,7 @@ __device__ __forceinline__ void step_tile(const TensorDev& T, const StepConsts& 
 // over many tiles were measured 10 % slower: an iteration's loads then wait behind the previous
 // iteration's stores).  Order of issue: decode-table loads, the (tensor, tile) look-up, the
 // streaming loads; then the tables go to LDS.
-template <int KIND, int VEC, int THREADS, bool DIRECT, bool SPLIT, bool QUANT>
+template <int KIND, int VEC, int THREADS, bool DIRECT, bool SPLIT, bool QUANT, bool EXACT>
 __global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
     constexpr int kTile = THREADS * VEC;       // elements per workgroup
     __shared__ DecodeTables tab;
@@ -867,32 +902,36 @@ __global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
     const int64_t tile0 = chunk * (int64_t)kTile;              // first element of the tile (wave-uniform)
     const int64_t rem = T.numel - tile0;                       // elements from there to the tensor's end
     if (rem >= kTile) {
-        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, true>(T, a.c, tab, entries, tile0, kTile, tid);
+        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, EXACT, true>(T, a.c, tab, entries, tile0, kTile, tid);
     } else {
-        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, false>(T, a.c, tab, entries, tile0, rem > 0 ? (int)rem : 0, tid);
+        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, EXACT, false>(T, a.c, tab, entries, tile0, rem > 0 ? (int)rem : 0,
+                                                                 tid);
     }
 }
 
-template <int KIND, bool SPLIT, bool QUANT>
+template <int KIND, bool SPLIT, bool QUANT, bool EXACT>
 static hipError_t launch_variant(bool direct, const StepArgs& a, int64_t n_blocks, hipStream_t s) {
     constexpr int VEC = step_vec(KIND), THREADS = step_threads(KIND);
     const dim3 grid((unsigned)n_blocks), block(THREADS);
-    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, true, SPLIT, QUANT>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, false, SPLIT, QUANT>), grid, block, 0, s, a);
+    if (direct) hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, true, SPLIT, QUANT, EXACT>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((step_kernel<KIND, VEC, THREADS, false, SPLIT, QUANT, EXACT>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
 template <int KIND>
 static hipError_t launch_kind(bool direct, bool split, bool quant, const StepArgs& a, int64_t n_blocks,
                               hipStream_t s) {
-    if (split && quant) return launch_variant<KIND, true, true>(direct, a, n_blocks, s);
-    if (split) return launch_variant<KIND, true, false>(direct, a, n_blocks, s);
-    if (quant) return launch_variant<KIND, false, true>(direct, a, n_blocks, s);
-    return launch_variant<KIND, false, false>(direct, a, n_blocks, s);
+    if (split && quant) return launch_variant<KIND, true, true, true>(direct, a, n_blocks, s);
+    if (split) return launch_variant<KIND, true, false, true>(direct, a, n_blocks, s);
+    if (quant) return launch_variant<KIND, false, true, true>(direct, a, n_blocks, s);
+    return launch_variant<KIND, false, false, true>(direct, a, n_blocks, s);
 }
 
-hipError_t launch_step(int kind, bool direct, bool split, bool quant, const StepArgs& a, int64_t n_blocks,
+// exact = false selects the faithful square root and division; it exists for AdamW in the compressed
+// layout only (SGD and Lion have neither operation; the ablation variants are always exact).
+hipError_t launch_step(int kind, bool direct, bool split, bool quant, bool exact, const StepArgs& a, int64_t n_blocks,
                        hipStream_t s) {
+    if (kind == 0 && split && quant && !exact) return launch_variant<0, true, true, false>(direct, a, n_blocks, s);
     if (kind == 0) return launch_kind<0>(direct, split, quant, a, n_blocks, s);
     if (kind == 1) return launch_kind<1>(direct, split, quant, a, n_blocks, s);
     return launch_kind<2>(direct, split, quant, a, n_blocks, s);
@@ -1440,9 +1479,13 @@ hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs
 //              four binades of v, several bias-correction pairs and several group scales.
 //   section 5: div_rn_midrange(n, d) == n / d on 2^26 pseudo-random operand pairs with magnitudes
 //              in [2^-60, 2^60] (n of either sign), plus pairs that share d across all mantissas of n.
+//   section 6: sqrt_faithful(x) within 1 ulp of sqrtf(x) on the inputs of section 2 (2^-96 and up);
+//   section 7: div_faithful(n, d) within 1 ulp of n / d on the operand pairs of section 5.
+//              (Sections 6 and 7 fail on a difference of more than one ulp; how often the faithful
+//              forms differ from the exact ones at all is reported by counters[16] and counters[17].)
 // counters[2 * section] counts checks, counters[2 * section + 1] failures.
 
-constexpr int kSelftestSections = 6;
+constexpr int kSelftestSections = 8;
 
 __device__ __forceinline__ uint32_t selftest_hash(uint64_t x) {
     x ^= x >> 33; x *= 0xff51afd7ed558ccdull; x ^= x >> 33; x *= 0xc4ceb9fe1a85ec53ull; x ^= x >> 33;
@@ -1497,7 +1540,21 @@ __global__ __launch_bounds__(kThreads) void selftest_kernel(unsigned long long* 
             checked = !(resid > 0.5f - kTieWindowM);
             failed = fast != exact;
         }
-    } else if (section == 5) {
+    } else if (section == 6) {
+        if (gid < (1ull << 25) + (1ull << 24)) {
+            uint32_t bits;
+            if (gid < (1ull << 25)) bits = 0x0f800000u + (uint32_t)(gid * 55u);
+            else bits = 0x3f800000u + (uint32_t)(gid - (1ull << 25));
+            if (bits < 0x7f800000u) {
+                const float x = u2f(bits);
+                const int32_t diff = (int32_t)f2u(sqrt_faithful(x)) - (int32_t)f2u(sqrtf(x));
+                checked = true;
+                failed = diff > 1 || diff < -1;
+                const unsigned long long inexact = __popcll(__builtin_amdgcn_ballot_w64(diff != 0));
+                if ((threadIdx.x & 63) == 0 && inexact) atomicAdd(&counters[16], inexact);
+            }
+        }
+    } else if (section == 5 || section == 7) {
         if (gid < (1ull << 26) + (1ull << 24)) {
             uint32_t nb, db;
             if (gid < (1ull << 26)) {
@@ -1512,7 +1569,14 @@ __global__ __launch_bounds__(kThreads) void selftest_kernel(unsigned long long* 
             }
             const float n = u2f(nb), d = u2f(db);
             checked = true;
-            failed = f2u(div_rn_midrange(n, d)) != f2u(n / d);
+            if (section == 5) {
+                failed = f2u(div_rn_midrange(n, d)) != f2u(n / d);
+            } else {
+                const int32_t diff = (int32_t)f2u(div_faithful(n, d)) - (int32_t)f2u(n / d);
+                failed = diff > 1 || diff < -1;
+                const unsigned long long inexact = __popcll(__builtin_amdgcn_ballot_w64(diff != 0));
+                if ((threadIdx.x & 63) == 0 && inexact) atomicAdd(&counters[17], inexact);
+            }
         }
     } else {
         if (gid < 4ull * (1ull << 23)) {
@@ -1540,7 +1604,8 @@ hipError_t launch_selftest(unsigned long long* counters, int section, const Step
     else if (section == 1) n = 1ull << 24;
     else if (section == 2) n = (1ull << 25) + (1ull << 24);
     else if (section == 3) n = 2ull * 14 * (1ull << 23);
-    else if (section == 5) n = (1ull << 26) + (1ull << 24);
+    else if (section == 5 || section == 7) n = (1ull << 26) + (1ull << 24);
+    else if (section == 6) n = (1ull << 25) + (1ull << 24);
     else n = 4ull * (1ull << 23);
     hipLaunchKernelGGL(selftest_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s,
                        counters, section, c, scale_r);

@@ -84,7 +84,7 @@ def test_compress_then_step_equals_oracle_from_fp32_start():
     for t in (4, 5):
         g = W.grad_bf16(spec, 0, t, seed=32)
         b.grad.copy_(g.cuda())
-        fo.adamw_step([b], 0.9, 0.999, 1e-8, t)
+        fo.adamw_step_exact([b], 0.9, 0.999, 1e-8, t)
         oracle.adamw_step(st, g.view(torch.int16).numpy().view(np.uint16), 1e-3, 0.01, 0.9, 0.999, 1e-8, t)
     assert np.array_equal(bits16(b.param), st.thp) and np.array_equal(b.rho.cpu().numpy(), st.rho)
     assert np.array_equal(b.m_q.cpu().numpy(), st.mq) and np.array_equal(b.v_q.cpu().numpy(), st.vq)

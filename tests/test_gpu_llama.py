@@ -19,7 +19,7 @@ import torch
 import oracle
 import paper_2602_23349_amd as fo
 import workloads as W
-from helpers import compare_state, bits16, to_dev_u16
+from helpers import assert_parity, compare_state, bits16, to_dev_u16
 
 pytestmark = pytest.mark.gpu
 
@@ -120,7 +120,8 @@ def test_llama_fused_adamw_sampled_parity(llama):
     n_groups = sum(g.size for g in smp.groups)
     bad = [r for r in report if r[2]]
     print(f"sampled {n_groups} groups ({n_groups * 32} elements) of 291 tensors, steps 1-2: mismatches {bad or 'none'}")
-    assert not bad
+    # this is the default entry point, the one bench.py times: held to the parity bar (compare_state asserts it)
+    assert_parity(report, "default", "Llama list, fused")
     # whole-list properties: codes in range, states became non-trivial everywhere
     for b in bufs[:12]:
         assert int(b.m_q.min()) >= -127 and bool(b.m_q.any()) and bool(b.v_q.any())

@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2602_23349_amd as fo
 import workloads as W
-from helpers import bits16, compare_state, download, upload_state
+from helpers import ADAMW_MODES, adamw_step_fn, assert_parity, bits16, compare_state, download, upload_state
 
 pytestmark = pytest.mark.gpu
 
@@ -23,10 +23,19 @@ def _random_state(kind, n, idx, seed):
     return st
 
 
-@pytest.mark.parametrize("case", range(16))
-def test_random_hyperparameters_and_states(case):
+def _cases(n_cases, kinds):
+    """(case, mode) pairs: AdamW cases run through both entry points, SGD and Lion have one."""
+    return [(c, m) for c in range(n_cases) for m in ADAMW_MODES if kinds[c % 4] == "adamw" or m == "exact"]
+
+
+_KINDS_SINGLE = ("adamw", "adamw", "sgd", "lion")
+_KINDS_LIST = ("adamw", "sgd", "lion", "adamw")
+
+
+@pytest.mark.parametrize("case,mode", _cases(16, _KINDS_SINGLE))
+def test_random_hyperparameters_and_states(case, mode):
     rng = np.random.default_rng(1000 + case)
-    kind = ("adamw", "adamw", "sgd", "lion")[case % 4]
+    kind = _KINDS_SINGLE[case % 4]
     n = int(rng.integers(1, 300000))
     f = lambda v: float(np.float32(v))
     lr = f(10.0 ** rng.uniform(-6, -0.5))
@@ -47,7 +56,7 @@ def test_random_hyperparameters_and_states(case):
         buf.grad.copy_(g.cuda())
         gb = g.view(torch.int16).numpy().view(np.uint16)
         if kind == "adamw":
-            fo.adamw_step(tl, b1, b2, eps, t)
+            adamw_step_fn(mode)(tl, b1, b2, eps, t)
             oracle.adamw_step(st, gb, lr, wd, b1, b2, eps, t)
         elif kind == "sgd":
             fo.sgd_step(tl, b1)
@@ -56,16 +65,15 @@ def test_random_hyperparameters_and_states(case):
             fo.lion_step(tl, b1, b2)
             oracle.lion_step(st, gb, lr, wd, b1, b2)
         compare_state(download(buf), st, where=f"case {case} {kind} n={n} t={t}", report=report)
-    bad = [r for r in report if r[2]]
-    assert not bad, (kind, n, lr, wd, b1, b2, eps, t0, gscale, bad)
+    assert_parity(report, mode, f"{(kind, n, lr, wd, b1, b2, eps, t0, gscale)}")
 
 
-@pytest.mark.parametrize("case", range(8))
-def test_random_lists(case):
+@pytest.mark.parametrize("case,mode", _cases(8, _KINDS_LIST))
+def test_random_lists(case, mode):
     # random lists (2..40 tensors, sizes log-uniform over 1..3M elements, per-tensor lr / weight decay),
     # random code states, three steps through the multi-tensor path
     rng = np.random.default_rng(5000 + case)
-    kind = ("adamw", "sgd", "lion", "adamw")[case % 4]
+    kind = _KINDS_LIST[case % 4]
     n_t = int(rng.integers(2, 41))
     sizes = [int(10.0 ** rng.uniform(0, 6.5)) for _ in range(n_t)]
     f = lambda v: float(np.float32(v))
@@ -83,7 +91,7 @@ def test_random_lists(case):
         for b, g in zip(bufs, gs):
             b.grad.copy_(g.cuda())
         if kind == "adamw":
-            fo.adamw_step(tl, b1, b2, eps, t)
+            adamw_step_fn(mode)(tl, b1, b2, eps, t)
         elif kind == "sgd":
             fo.sgd_step(tl, b1)
         else:
@@ -97,5 +105,4 @@ def test_random_lists(case):
             else:
                 oracle.lion_step(st, gb, lr, wd, b1, b2)
             compare_state(download(bufs[i]), st, where=f"list case {case} {kind} tensor {i} n={sizes[i]} t={t}", report=report)
-    bad = [r for r in report if r[2]]
-    assert not bad, (kind, sizes, bad)
+    assert_parity(report, mode, f"{(kind, sizes)}")

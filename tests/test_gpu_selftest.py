@@ -17,3 +17,15 @@ def test_device_selftest_passes():
     assert checked[3] > 0.99 * 2 * 14 * (1 << 23)
     assert checked[4] > 0.95 * 15 * 4 * (1 << 23)
     assert checked[5] == (1 << 26) + (1 << 24)       # short division against IEEE division
+    assert checked[6] == checked[2]                  # faithful square root on the same inputs
+    assert checked[7] == checked[5]                  # faithful division on the same operand pairs
+
+
+def test_faithful_forms_are_rarely_inexact():
+    # the default AdamW step's square root and division: never more than one ulp off (checked by the
+    # self-test), and different from the exactly rounded result for only a few inputs in a million
+    n_sqrt, bad_sqrt, n_div, bad_div = fo.faithful_rounding_stats()
+    print(f"faithful sqrt: {bad_sqrt} of {n_sqrt} not exactly rounded ({bad_sqrt / n_sqrt:.2e}); "
+          f"faithful division: {bad_div} of {n_div} ({bad_div / n_div:.2e})")
+    assert n_sqrt > (1 << 25) and n_div == (1 << 26) + (1 << 24)
+    assert bad_sqrt <= 1e-5 * n_sqrt and bad_div <= 1e-5 * n_div
