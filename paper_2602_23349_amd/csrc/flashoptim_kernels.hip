@@ -7,6 +7,10 @@
 // with -ffp-contract=off and correctly rounded division / square root (hipcc's
 // default), because 8-bit codes and correction bytes are compared bit for bit
 // against an independent CPU implementation of the same algorithms.
+// One exception, selected by the EXACT template flag of the AdamW step: with EXACT = false
+// (the default entry point) sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps) are faithfully
+// rounded (within one ulp of the correctly rounded value, and equal to it for nearly every
+// input); the state codes and scales are unaffected, the master weight can differ by one ulp.
 //
 // The step is bandwidth-bound by definition (12.25 algorithmic bytes per parameter
 // for AdamW), but an exactly rounded body costs on the order of a hundred VALU
@@ -34,7 +38,8 @@
 //   * sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps) use the 1-ulp hardware root / reciprocal
 //     followed by FMA residual corrections that yield the correctly rounded result for
 //     operands inside a stated range; a wave-uniform range test selects the general
-//     sequence otherwise.
+//     sequence otherwise.  With EXACT = false each takes one residual correction instead
+//     (sqrt_faithful, div_faithful).
 //
 // Work decomposition.  A lane owns 8 consecutive elements per tile: BF16 streams move as
 // 128-bit and byte streams as 64-bit accesses, and a quantisation group (32 elements) is a
@@ -232,10 +237,12 @@ __device__ __forceinline__ uint32_t v_code_exact_midrange(float v, float r) {
     return round_to_int_bits(y);
 }
 
-// Same code from root_hat = sqrt(v * rbc2) (exactly rounded, already computed for the update)
-// and kr255 = ((sqrt(1/rbc2) rounded) * r) * 255.  Relative errors: v*rbc2 (1), its root
-// (0.5 + 1), the three roundings inside kr255 (3), this product (1), against the three
-// roundings of the exact chain (3): below 9.5 * 2^-24 * 255 < 1.45e-4 in y.
+// Same code from root_hat = sqrt(v * rbc2) (already computed for the update) and
+// kr255 = ((sqrt(1/rbc2) rounded) * r) * 255.  Relative errors in units of 2^-24: v*rbc2 (1), its
+// root (0.5 + 1 when exactly rounded, 0.5 + 2 when faithfully rounded), the three roundings inside
+// kr255 (3), this product (1), against the three roundings of the exact chain (3): below
+// 9.5 * 2^-24 * 255 < 1.45e-4 in y with the exact root, 10.5 * 2^-24 * 255 < 1.6e-4 with the
+// faithful one; the window covers both.
 constexpr float kTieWindowV = 1.8e-4f;
 __device__ __forceinline__ uint32_t v_code_fast(float root_hat, float kr255, float* resid) {
     const float y = __builtin_amdgcn_fmed3f(root_hat * kr255, 0.0f, 255.0f);
