@@ -106,15 +106,20 @@ typedef struct flashoptim_lion_hp { float beta1, beta2; } flashoptim_lion_hp;
  * tensors: host array of n_tensors descriptors (n_tensors >= 0).
  *
  * Rounding of the AdamW update (the two per-element operations sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps)):
- *   flashoptim_adamw_step        faithful: each is the hardware estimate plus one FMA correction, whose value
- *                                before the final rounding is within ~1e-6 ulp of the exact one.  The result is
- *                                the correctly rounded one except when the exact value lies that close to the
- *                                midpoint of two FP32 numbers (about one element in 10^6 per operation), and then
- *                                its other neighbour.  Such a 1-ulp difference reaches the stored theta' / rho in
- *                                about one element in 10^9 per step (rho then differs by one unit); the momentum
- *                                and variance codes and all scales never depend on it and are always exact.
+ *   flashoptim_adamw_step        faithful: each is the hardware estimate (reciprocal square root, reciprocal)
+ *                                plus one FMA residual correction.  The result is within one ulp of the correctly
+ *                                rounded one (flashoptim_selftest bounds this on the device) and differs from it
+ *                                only when the exact value lies very close to the midpoint of two FP32 numbers;
+ *                                flashoptim_faithful_rounding_stats counts such inputs (on MI355X: none among
+ *                                1.3e8).  A 1-ulp difference can move the new master weight by one FP32 ulp,
+ *                                hence rho by one unit on a rare element.  Momentum codes, variance codes and
+ *                                all scales are the exact ones in either case (the variance-code estimate reuses
+ *                                the square root, and its tie test allows for the extra ulp).  Used when
+ *                                2^-37 <= eps <= 1 and the operands are inside 2^-60 .. 2^60; otherwise this entry
+ *                                point takes the correctly rounded general sequences (slower, same results as
+ *                                the exact entry point).
  *   flashoptim_adamw_step_exact  both are correctly rounded for every input: the whole step is bit-identical
- *                                to the arithmetic stated above.  About 4 % slower on MI355X.
+ *                                to the arithmetic stated above.  About 5 % slower on MI355X.
  * Everything else is identical between the two. */
 int flashoptim_adamw_step(const flashoptim_tensor* tensors, int64_t n_tensors,
                           const flashoptim_adamw_hp* hp, void* stream);

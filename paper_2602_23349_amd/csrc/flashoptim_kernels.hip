@@ -186,8 +186,11 @@ __device__ __forceinline__ float div_rn_midrange(float n, float d) {
 // step one FMA.  The value before the final rounding is within ~1e-6 ulp of the exact one, so the result
 // is the correctly rounded one except when the exact value lies that close to the middle between two
 // FP32 numbers (about one operand in a million); then it is the other neighbour.  Operand ranges as for
-// the exact short forms; the square root clamps its argument at the smallest normal number (a
-// subnormal v_hat has a root below 1e-19, which vanishes next to any admissible eps).
+// the exact short forms; the square root clamps its argument at the smallest normal number: for a zero
+// or subnormal v_hat it returns 2^-63 instead of a value in [0, 2^-63], and callers use it only with
+// eps >= kFaithfulEpsMin = 2^-37, whose half ulp (2^-61) exceeds that, so that sqrt(v_hat) + eps
+// rounds to eps either way.
+constexpr float kFaithfulEpsMin = 7.275957614183426e-12f;   // 2^-37
 __device__ __forceinline__ float sqrt_faithful(float x) {
     const float y = __builtin_amdgcn_rsqf(fmaxf(x, 1.17549435e-38f));
     const float s = x * y, h = 0.5f * y;
@@ -738,7 +741,7 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
         // m_hat / (sqrt(v_hat) + eps): the short division when every operand of the lane is well
         // inside the normal range (eps <= den <= sqrt(v_hat max) + eps), else the general one
         // (the faithful division has no lower limit on the numerator)
-        const bool div_fast = (c.eps >= kDivFastLo) && (c.eps <= 1.0f) &&
+        const bool div_fast = (c.eps >= (EXACT ? kDivFastLo : kFaithfulEpsMin)) && (c.eps <= 1.0f) &&
                               !any_lane(!((!EXACT || nmin >= kDivFastLo) && nmax <= kDivFastHi && vmax <= kDivFastHi));
 #pragma unroll
         for (int j = 0; j < VEC / 4; ++j) {

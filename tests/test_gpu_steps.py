@@ -149,18 +149,46 @@ def test_edge_values_in_one_step():
     g[256:288] = 1e30       # g^2 overflows FP32: v = inf, both scales saturate at 65504
     g[288:] = np.random.default_rng(6).standard_normal(n - 288) * 1e-3
     gb = torch.from_numpy(g).to(torch.bfloat16)
-    for kind, hp in (("adamw", ADAMW), ("sgd", SGD), ("lion", LION)):
+    for kind, hp, mode in (("adamw", ADAMW, "exact"), ("adamw", ADAMW, "default"), ("sgd", SGD, "exact"),
+                           ("lion", LION, "exact")):
         st = oracle.TensorState(theta, kind)
         buf = upload_state(st)
         buf.lr, buf.weight_decay = hp["lr"], hp["wd"]
         buf.grad.copy_(gb.cuda())
         tl = fo.TensorList([buf])
         for t in (1, 2):
-            _gpu_step(kind, tl, hp, t)
+            _gpu_step(kind, tl, hp, t, mode)
             _oracle_step(kind, st, _g_bits(gb), hp["lr"], hp["wd"], hp, t)
-            rep = compare_state(download(buf), st, where=f"edge {kind} t={t}")
-            assert sum(r[1] for r in rep) == 0
+            rep = compare_state(download(buf), st, where=f"edge {kind} {mode} t={t}")
+            assert sum(r[1] for r in rep) == 0      # a few hundred elements: a systematic difference, not a rare tie
             assert np.isfinite(oracle.bf16_to_f32(st.thp)).all()
+
+
+@pytest.mark.parametrize("mode", ADAMW_MODES)
+@pytest.mark.parametrize("eps", [1e-15, 1e-12, 1e-11, 1e-8])
+def test_zero_variance_with_live_momentum_and_small_eps(eps, mode):
+    # v_hat = 0 (variance codes 0, gradient 0) under a non-zero momentum: the update is m_hat / eps, and
+    # sqrt(v_hat) + eps must round to eps whichever square-root sequence the kernel selects for this eps
+    n = 2048 * 3 + 96
+    rs = W.random_state(n, 0, seed=21, with_variance=True)
+    st = oracle.TensorState(np.zeros(n, np.float32), "adamw")
+    st.thp = bits16(rs["thp"]); st.rho = rs["rho"].numpy().copy()
+    st.mq = rs["mq"].numpy().copy(); st.ms = bits16(rs["ms"])
+    st.vq = np.zeros(n, np.uint8); st.vs = bits16(rs["vs"])
+    st.vq[1::7] = rs["vq"].numpy()[1::7]                 # most elements have v = 0, some do not
+    finite = np.isfinite(oracle.bf16_to_f32(st.thp))
+    st.thp[~finite] = 0x3f80
+    buf = upload_state(st)
+    buf.lr, buf.weight_decay = 1e-9, 0.0                 # m_hat / eps is huge: keep the weights finite
+    g = torch.zeros(n, dtype=torch.bfloat16)
+    g[5::11] = 1e-4
+    buf.grad.copy_(g.cuda())
+    tl = fo.TensorList([buf])
+    for t in (1, 2):
+        adamw_step_fn(mode)(tl, 0.9, 0.999, eps, t)
+        oracle.adamw_step(st, _g_bits(g), 1e-9, 0.0, 0.9, 0.999, eps, t)
+        rep = compare_state(download(buf), st, where=f"zero variance eps={eps} {mode} t={t}")
+        assert sum(r[1] for r in rep) == 0
 
 
 def _run_list(kind, hp, specs, seed, dist, scale, per_tensor_sigma, steps, nthreads=0, mode="exact"):
