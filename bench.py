@@ -6,7 +6,7 @@ Llama-3.1-8B parameter list (291 tensors, 8,030,261,248 parameters, 57.2 GB of r
 state), one fused multi-tensor call per step (issued as ~30 back-to-back kernel launches), synthetic values.  A "step" is one pass of the
 whole path: reconstruct master weights and states, AdamW update from BF16 gradients, re-quantise
 states, re-split weights.  Inputs are resident in HBM before the timed region starts.  The timed call is
-flashoptim_adamw_step (square root and division of the update faithfully rounded; held to the parity bar
+flashoptim_adamw_step (the division of the update faithfully rounded; held to the parity bar
 by the GPU tests); --rounding exact times flashoptim_adamw_step_exact instead, and the default run also
 reports it, measured after the timed region, under roofline.bit_exact_entry_point.
 
@@ -62,7 +62,7 @@ def parse_args():
                          "oquant: FP32 weights + 8-bit states; ref: plain FP32 optimizer (BF16 gradients). "
                          "The last three are the ablation entry points (fused mode only).")
     ap.add_argument("--rounding", default="default", choices=["default", "exact"],
-                    help="AdamW only: default = flashoptim_adamw_step (faithfully rounded square root and division, "
+                    help="AdamW only: default = flashoptim_adamw_step (faithfully rounded division, "
                          "inside the parity bar); exact = flashoptim_adamw_step_exact (bit-identical to the oracle)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true",

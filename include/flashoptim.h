@@ -36,7 +36,7 @@
  *    weight keeps rho = 0; the rho byte stored next to a NaN weight is unspecified.
  *  - Arithmetic: IEEE binary32, round-to-nearest-even, subnormals kept, no fused
  *    multiply-add, in the order the algorithms print it (one documented exception: the
- *    default AdamW step rounds two operations faithfully, see flashoptim_adamw_step); divisions by a group scale
+ *    default AdamW step rounds one division faithfully, see flashoptim_adamw_step); divisions by a group scale
  *    or by a bias correction 1 - beta^t multiply by the correctly rounded FP32
  *    reciprocal of that scalar.
  *  - There is no CPU fallback: without a HIP device every compute entry point
@@ -105,21 +105,19 @@ typedef struct flashoptim_lion_hp { float beta1, beta2; } flashoptim_lion_hp;
  *   theta <- theta - eta (u + lambda theta)); sign(0) = 0.
  * tensors: host array of n_tensors descriptors (n_tensors >= 0).
  *
- * Rounding of the AdamW update (the two per-element operations sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps)):
- *   flashoptim_adamw_step        faithful: each is the hardware estimate (reciprocal square root, reciprocal)
- *                                plus one FMA residual correction.  The result is within one ulp of the correctly
- *                                rounded one (flashoptim_selftest bounds this on the device) and differs from it
- *                                only when the exact value lies very close to the midpoint of two FP32 numbers;
- *                                flashoptim_faithful_rounding_stats counts such inputs (on MI355X: none among
- *                                1.3e8).  A 1-ulp difference can move the new master weight by one FP32 ulp,
- *                                hence rho by one unit on a rare element.  Momentum codes, variance codes and
- *                                all scales are the exact ones in either case (the variance-code estimate reuses
- *                                the square root, and its tie test allows for the extra ulp).  Used when
- *                                2^-37 <= eps <= 1 and the operands are inside 2^-60 .. 2^60; otherwise this entry
- *                                point takes the correctly rounded general sequences (slower, same results as
- *                                the exact entry point).
- *   flashoptim_adamw_step_exact  both are correctly rounded for every input: the whole step is bit-identical
- *                                to the arithmetic stated above.  About 5 % slower on MI355X.
+ * Rounding of the quotient m_hat / (sqrt(v_hat) + eps) of the AdamW update:
+ *   flashoptim_adamw_step        faithful: the hardware reciprocal estimate, the quotient and one FMA residual
+ *                                correction.  The result is within one ulp of the correctly rounded quotient
+ *                                (flashoptim_selftest bounds this on the device) and differs from it only when
+ *                                the exact quotient lies within 2^-23 ulp of the midpoint of two FP32 numbers:
+ *                                about one operand pair in 10^9 (flashoptim_faithful_rounding_stats counts them).
+ *                                Such a difference can move the new master weight by one FP32 ulp, hence rho by
+ *                                one unit on a rare element.  Momentum codes, variance codes and all scales do
+ *                                not depend on the quotient and are the exact ones in either case.  Used when
+ *                                2^-60 <= eps <= 1 and the operands do not exceed 2^60; otherwise this entry point
+ *                                takes the IEEE division (slower, same results as the exact entry point).
+ *   flashoptim_adamw_step_exact  the quotient is correctly rounded for every input: the whole step is
+ *                                bit-identical to the arithmetic stated above.  About 3 % slower on MI355X.
  * Everything else is identical between the two. */
 int flashoptim_adamw_step(const flashoptim_tensor* tensors, int64_t n_tensors,
                           const flashoptim_adamw_hp* hp, void* stream);
@@ -263,18 +261,18 @@ const char* flashoptim_strerror(int status);
  * hardware reciprocal and square root are within 1 ulp.  This call checks those provisions on
  * the current device against plain IEEE operations, exhaustively where the domain is small:
  *   [0] Newton reciprocal of every positive finite FP16 value      [1] v_rcp_f32 within 1 ulp on [1, 4)
- *   [2] short square root == sqrtf on 2^25 spread values and all of [1, 4)
+ *   [2] short square root (reciprocal-square-root estimate + one correction) == sqrtf for EVERY FP32 value
+ *       of its range [2^-96, FLT_MAX] (1,879,048,192 values)
  *   [3] momentum codes (Algorithm 2) and [4] variance codes (Algorithm 3): the estimate equals the
  *       exact code wherever the kernel's tie test does not ask for the exact evaluation.
- *   [5] short division == IEEE division on 2^26 + 2^24 operand pairs inside its range.
- *   [6] faithful square root and [7] faithful division of flashoptim_adamw_step: within 1 ulp of the IEEE
- *       result on the inputs of [2] and [5].
- * n_checked, n_failed: HOST arrays of 8 counters (one per section above).  Waits for completion.
- * Returns FLASHOPTIM_OK, FLASHOPTIM_ERR_SELFTEST if any check failed, or another status. */
+ *   [5] short division == IEEE division on 2^30 + 2^24 operand pairs inside its range.
+ *   [6] faithful division of flashoptim_adamw_step: within 1 ulp of the IEEE quotient on the pairs of [5].
+ * n_checked, n_failed: HOST arrays of 7 counters (one per section above).  Waits for completion (about
+ * 0.1 s).  Returns FLASHOPTIM_OK, FLASHOPTIM_ERR_SELFTEST if any check failed, or another status. */
 int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream);
-/* How often the faithful forms differ from the exactly rounded results at all, measured on this device:
- * counts (HOST, 4 entries) = {square-root inputs, of these not exact, division operand pairs, of these not
- * exact}.  Waits for completion.  FLASHOPTIM_ERR_SELFTEST if any result is off by more than one ulp. */
+/* How often the faithful division differs from the exactly rounded quotient at all, measured on this device:
+ * counts (HOST, 2 entries) = {operand pairs checked (2^30 + 2^24), of these not exact}.  Waits for
+ * completion.  FLASHOPTIM_ERR_SELFTEST if any quotient is off by more than one ulp. */
 int flashoptim_faithful_rounding_stats(int64_t* counts, void* stream);
 /* Number of kernel launches one step call of `kind` issues for a list with these element counts
  * (host arithmetic only; for reading profiles: per-kernel durations are per launch).  Negative

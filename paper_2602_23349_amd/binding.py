@@ -372,16 +372,17 @@ def checkpoint_unpack(kind, blob, tensors, stream=None):
 
 
 def faithful_rounding_stats(stream=None):
-    """(square-root inputs, of these not exactly rounded, division operand pairs, of these not exactly rounded)."""
-    counts = (C.c_int64 * 4)()
+    """(division operand pairs checked, quotients of the default AdamW step's division that are not the exactly
+    rounded one)."""
+    counts = (C.c_int64 * 2)()
     _check(load_library().flashoptim_faithful_rounding_stats(counts, _stream(stream)), "flashoptim_faithful_rounding_stats")
     return tuple(counts)
 
 
 def selftest(stream=None):
-    """Runs the device self-test; returns (status, checked[8], failed[8])."""
-    checked = (C.c_int64 * 8)()
-    failed = (C.c_int64 * 8)()
+    """Runs the device self-test; returns (status, checked[7], failed[7])."""
+    checked = (C.c_int64 * 7)()
+    failed = (C.c_int64 * 7)()
     status = load_library().flashoptim_selftest(checked, failed, _stream(stream))
     if status not in (0, -6):
         raise FlashOptimError(status, "flashoptim_selftest")

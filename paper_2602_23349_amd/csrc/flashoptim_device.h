@@ -106,8 +106,8 @@ void launch_dequantize(bool variance, bool linear, const void* q, const uint16_t
                        hipStream_t s);
 void launch_nmse(bool variance, bool linear, const float* x, int64_t n, double* sums, hipStream_t s);
 void launch_copy(const CopySegment* segs, const uint2* chunks, int64_t n_chunks, hipStream_t s);
-constexpr int kSelftestSectionCount = 8;
-constexpr int kSelftestCounters = 18;   // two per section, then the inexact counts of sections 6 and 7
+constexpr int kSelftestSectionCount = 7;
+constexpr int kSelftestCounters = 15;   // two per section, then the inexact count of section 6
 hipError_t launch_selftest(unsigned long long* counters, int section, const StepConsts& c, float scale_r,
                            hipStream_t s);
 

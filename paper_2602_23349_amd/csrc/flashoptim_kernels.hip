@@ -8,9 +8,9 @@
 // default), because 8-bit codes and correction bytes are compared bit for bit
 // against an independent CPU implementation of the same algorithms.
 // One exception, selected by the EXACT template flag of the AdamW step: with EXACT = false
-// (the default entry point) sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps) are faithfully
-// rounded (within one ulp of the correctly rounded value, and equal to it for nearly every
-// input); the state codes and scales are unaffected, the master weight can differ by one ulp.
+// (the default entry point) the quotient m_hat / (sqrt(v_hat) + eps) is faithfully rounded
+// (within one ulp of the correctly rounded value, and equal to it for all but about one operand
+// pair in 10^9); the state codes and scales are unaffected, the master weight can differ by one ulp.
 //
 // The step is bandwidth-bound by definition (12.25 algorithmic bytes per parameter
 // for AdamW), but an exactly rounded body costs on the order of a hundred VALU
@@ -35,11 +35,12 @@
 //     lane of the wavefront is that close to a tie (a few percent of the wavefronts) are the
 //     few elements concerned recomputed with the exact sequence.  Codes are bit-identical
 //     to the exact evaluation in every case;
-//   * sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps) use the 1-ulp hardware root / reciprocal
-//     followed by FMA residual corrections that yield the correctly rounded result for
-//     operands inside a stated range; a wave-uniform range test selects the general
-//     sequence otherwise.  With EXACT = false each takes one residual correction instead
-//     (sqrt_faithful, div_faithful).
+//   * sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps) use the 1-ulp hardware reciprocal square
+//     root / reciprocal followed by FMA residual corrections that yield the correctly rounded
+//     result for operands inside a stated range (the square root: verified for every value of
+//     the range by the device self-test; the division: the classical refinement); a
+//     wave-uniform range test selects the general sequence otherwise.  With EXACT = false the
+//     division takes one residual correction instead of a refined reciprocal and two (div_faithful).
 //
 // Work decomposition.  A lane owns 8 consecutive elements per tile: BF16 streams move as
 // 128-bit and byte streams as 64-bit accesses, and a quantisation group (32 elements) is a
@@ -150,20 +151,21 @@ __device__ __forceinline__ uint32_t group_scale_fast(float absmax, float* r) {
     return (uint32_t)__builtin_bit_cast(uint16_t, h);
 }
 
-// Correctly rounded square root for x = 0, x >= 2^-96, inf (negative / NaN give NaN): the
-// hardware root is within 1 ulp, and the signs of the two residuals x - s*(s -+ ulp), each one
-// fused multiply-add, pick the neighbour when it is the nearer one.  Below 2^-96 the residuals
-// would leave the normal range; callers check the range and use sqrtf() otherwise.
+// Correctly rounded square root for 2^-96 <= x <= FLT_MAX: the hardware reciprocal-square-root
+// estimate (1 ulp) and one Newton correction, each step one FMA.  That this sequence returns the
+// correctly rounded root for EVERY FP32 value of that range is a property of the hardware estimate
+// which flashoptim_selftest verifies exhaustively on the device (all 1,879,048,192 values).  Below
+// 2^-96 the residual x - s*s leaves the normal range and the result is only within one ulp; zero,
+// infinity and NaN give NaN.  Callers check the range and use sqrtf() otherwise.
 constexpr float kSqrtFastMin = 1.2621774483536189e-29f;   // 2^-96
+constexpr float kSqrtFastMax = 3.4028234663852886e38f;    // largest finite value
 __device__ __forceinline__ float sqrt_rn_midrange(float x) {
-    float s = __builtin_amdgcn_sqrtf(x);
-    const float s_dn = u2f(f2u(s) - 1u), s_up = u2f(f2u(s) + 1u);
-    const float r_dn = fmaf(-s_dn, s, x);
-    const float r_up = fmaf(-s_up, s, x);
-    s = (r_dn <= 0.0f) ? s_dn : s;
-    s = (r_up > 0.0f) ? s_up : s;
-    return s;
+    const float y = __builtin_amdgcn_rsqf(x);
+    const float s = x * y, h = 0.5f * y;
+    return fmaf(fmaf(-s, s, x), h, s);
 }
+// True when every value between lo and hi (lo <= hi) is in the range of sqrt_rn_midrange; false for NaN.
+__device__ __forceinline__ bool sqrt_range_ok(float lo, float hi) { return lo >= kSqrtFastMin && hi <= kSqrtFastMax; }
 
 // Correctly rounded n / d for operands well inside the normal range: 2^-60 <= |n|, d <= 2^60.
 // This is the usual refinement of the 1-ulp hardware reciprocal (one Newton step on the
@@ -182,21 +184,13 @@ __device__ __forceinline__ float div_rn_midrange(float n, float d) {
     return q;
 }
 
-// Faithful square root and division: one Newton-type correction of the 1-ulp hardware estimate, each
-// step one FMA.  The value before the final rounding is within a small fraction of an ulp of the exact
-// one, so the result is the correctly rounded one except when the exact value lies that close to the
-// middle between two FP32 numbers; then it is the other neighbour (the device self-test bounds the
-// difference to one ulp and counts such inputs: none among 1.3e8 on MI355X).  Operand ranges as for
-// the exact short forms; the square root clamps its argument at the smallest normal number: for a zero
-// or subnormal v_hat it returns 2^-63 instead of a value in [0, 2^-63], and callers use it only with
-// eps >= kFaithfulEpsMin = 2^-37, whose half ulp (2^-61) exceeds that, so that sqrt(v_hat) + eps
-// rounds to eps either way.
-constexpr float kFaithfulEpsMin = 7.275957614183426e-12f;   // 2^-37
-__device__ __forceinline__ float sqrt_faithful(float x) {
-    const float y = __builtin_amdgcn_rsqf(fmaxf(x, 1.17549435e-38f));
-    const float s = x * y, h = 0.5f * y;
-    return fmaf(fmaf(-s, s, x), h, s);
-}
+// Faithful division: one residual correction of the quotient formed with the 1-ulp hardware reciprocal,
+// each step one FMA.  The value before the final rounding is within 2^-23 ulp of the exact quotient, so the
+// result is the correctly rounded one except when the exact quotient lies that close to the middle between
+// two FP32 numbers; then it is the other neighbour (the device self-test bounds the difference to one ulp and
+// counts such operand pairs: 52 among 2^36 random pairs on MI355X, 7.6e-10).  Denominator range as for
+// div_rn_midrange.  A numerator below 2^-60 is admitted: down to 2^-103 nothing changes; below that the
+// residual can leave the normal range and the error can reach a few ulp of a quotient smaller than 2^-43.
 __device__ __forceinline__ float div_faithful(float n, float d) {
     const float r = __builtin_amdgcn_rcpf(d);
     const float q = n * r;
@@ -235,18 +229,16 @@ __device__ __forceinline__ uint32_t v_code_exact(float v, float r) {
     return round_to_int_bits(y);
 }
 
-// The same value when v is known to be 0 or at least 2^-96 (the range of sqrt_rn_midrange).
+// The same value when v is known to be inside the range of sqrt_rn_midrange.
 __device__ __forceinline__ uint32_t v_code_exact_midrange(float v, float r) {
     const float y = __builtin_amdgcn_fmed3f((sqrt_rn_midrange(v) * r) * 255.0f, 0.0f, 255.0f);
     return round_to_int_bits(y);
 }
 
-// Same code from root_hat = sqrt(v * rbc2) (already computed for the update) and
-// kr255 = ((sqrt(1/rbc2) rounded) * r) * 255.  Relative errors in units of 2^-24: v*rbc2 (1), its
-// root (0.5 + 1 when exactly rounded, 0.5 + 2 when faithfully rounded), the three roundings inside
-// kr255 (3), this product (1), against the three roundings of the exact chain (3): below
-// 9.5 * 2^-24 * 255 < 1.45e-4 in y with the exact root, 10.5 * 2^-24 * 255 < 1.6e-4 with the
-// faithful one; the window covers both.
+// Same code from root_hat = sqrt(v * rbc2) (exactly rounded, already computed for the update)
+// and kr255 = ((sqrt(1/rbc2) rounded) * r) * 255.  Relative errors: v*rbc2 (1), its root
+// (0.5 + 1), the three roundings inside kr255 (3), this product (1), against the three
+// roundings of the exact chain (3): below 9.5 * 2^-24 * 255 < 1.45e-4 in y.
 constexpr float kTieWindowV = 1.8e-4f;
 __device__ __forceinline__ uint32_t v_code_fast(float root_hat, float kr255, float* resid) {
     const float y = __builtin_amdgcn_fmed3f(root_hat * kr255, 0.0f, 255.0f);
@@ -736,13 +728,13 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
         // lane are the products of the extreme raw values: no separate running extremes are needed.
         const float vmin = amin_v * c.rbc2, vmax = amax_v * c.rbc2;
         const float nmin = amin_m * c.rbc1, nmax = amax_m * c.rbc1;
-        // sqrt(v_hat): the short sequence unless some lane holds a value below 2^-96
-        // (exact zeros take the general sequence too: one comparison covers both)
-        const bool sqrt_general = EXACT && any_lane(vmin < kSqrtFastMin);
+        // sqrt(v_hat): the short sequence unless some lane holds a value outside its range (below
+        // 2^-96 - exact zeros included - or not finite)
+        const bool sqrt_general = any_lane(!sqrt_range_ok(vmin, vmax));
         // m_hat / (sqrt(v_hat) + eps): the short division when every operand of the lane is well
         // inside the normal range (eps <= den <= sqrt(v_hat max) + eps), else the general one
         // (the faithful division has no lower limit on the numerator)
-        const bool div_fast = (c.eps >= (EXACT ? kDivFastLo : kFaithfulEpsMin)) && (c.eps <= 1.0f) &&
+        const bool div_fast = (c.eps >= kDivFastLo) && (c.eps <= 1.0f) &&
                               !any_lane(!((!EXACT || nmin >= kDivFastLo) && nmax <= kDivFastHi && vmax <= kDivFastHi));
 #pragma unroll
         for (int j = 0; j < VEC / 4; ++j) {
@@ -752,33 +744,22 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
                 mh4[k] = mt[4 * j + k] * c.rbc1;
                 vh4[k] = vt[4 * j + k] * c.rbc2;
             }
-            if (EXACT) {
-                if (sqrt_general) {
+            if (sqrt_general) {
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrtf(vh4[k]);
-                } else {
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrt_rn_midrange(vh4[k]);
-                }
-                if (div_fast) {
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) quo[k] = div_rn_midrange(mh4[k], rh[4 * j + k] + c.eps);
-                } else {
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) quo[k] = mh4[k] / (rh[4 * j + k] + c.eps);
-                }
-            } else if (div_fast) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    rh[4 * j + k] = sqrt_faithful(vh4[k]);
-                    quo[k] = div_faithful(mh4[k], rh[4 * j + k] + c.eps);
-                }
+                for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrtf(vh4[k]);
             } else {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    rh[4 * j + k] = sqrtf(vh4[k]);
-                    quo[k] = mh4[k] / (rh[4 * j + k] + c.eps);
-                }
+                for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrt_rn_midrange(vh4[k]);
+            }
+            if (!div_fast) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) quo[k] = mh4[k] / (rh[4 * j + k] + c.eps);
+            } else if (EXACT) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) quo[k] = div_rn_midrange(mh4[k], rh[4 * j + k] + c.eps);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) quo[k] = div_faithful(mh4[k], rh[4 * j + k] + c.eps);
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -805,12 +786,12 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
     y.ms = group_scale_fast(amax_m, &r_m);
     if (HAS_V) {
         amax_v = group_max<VEC>(amax_v);
-        const float root_max = any_lane(amax_v < kSqrtFastMin) ? sqrtf(amax_v) : sqrt_rn_midrange(amax_v);
+        const float root_max = any_lane(!sqrt_range_ok(amax_v, amax_v)) ? sqrtf(amax_v) : sqrt_rn_midrange(amax_v);
         y.vs = group_scale_fast(root_max, &r_v);
         kr255 = (c.root_bc2 * r_v) * 255.0f;
     }
 
-    const bool vt_root_general = HAS_V && any_lane(amin_v < kSqrtFastMin);
+    const bool vt_root_general = HAS_V && any_lane(!sqrt_range_ok(amin_v, amax_v));   // amax_v: the group's, at least the lane's
     // epilogue: state codes, four at a time; exact recomputation only near rounding ties
 #pragma unroll
     for (int j = 0; j < VEC / 4; ++j) {
@@ -938,7 +919,7 @@ static hipError_t launch_kind(bool direct, bool split, bool quant, const StepArg
     return launch_variant<KIND, false, false, true>(direct, a, n_blocks, s);
 }
 
-// exact = false selects the faithful square root and division; it exists for AdamW in the compressed
+// exact = false selects the faithful division; it exists for AdamW in the compressed
 // layout only (SGD and Lion have neither operation; the ablation variants are always exact).
 hipError_t launch_step(int kind, bool direct, bool split, bool quant, bool exact, const StepArgs& a, int64_t n_blocks,
                        hipStream_t s) {
@@ -1482,21 +1463,21 @@ hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs
 // IEEE operations:
 //   section 0: recip_of_fp16(s) == 1.0f / s for every positive finite FP16 value s;
 //   section 1: v_rcp_f32(d) within 1 ulp of 1.0f / d for every d in [1, 4);
-//   section 2: sqrt_rn_midrange(x) == sqrtf(x) on 2^25 values spread over [2^-96, 2^128) and on
-//              every value of the two binades [1, 4);
+//   section 2: sqrt_rn_midrange(x) == sqrtf(x) for EVERY FP32 value x of its range [2^-96, FLT_MAX];
 //   section 3: momentum codes: wherever the tie test does not fire, m_code_fast == m_code_exact,
 //              for every m' in [2^-13, 2) of either sign;
 //   section 4: variance codes: same for v_code_fast against v_code_exact, over every FP32 value of
 //              four binades of v, several bias-correction pairs and several group scales.
-//   section 5: div_rn_midrange(n, d) == n / d on 2^26 pseudo-random operand pairs with magnitudes
+//   section 5: div_rn_midrange(n, d) == n / d on 2^30 pseudo-random operand pairs with magnitudes
 //              in [2^-60, 2^60] (n of either sign), plus pairs that share d across all mantissas of n.
-//   section 6: sqrt_faithful(x) within 1 ulp of sqrtf(x) on the inputs of section 2 (2^-96 and up);
-//   section 7: div_faithful(n, d) within 1 ulp of n / d on the operand pairs of section 5.
-//              (Sections 6 and 7 fail on a difference of more than one ulp; how often the faithful
-//              forms differ from the exact ones at all is reported by counters[16] and counters[17].)
+//   section 6: div_faithful(n, d) within 1 ulp of n / d on the operand pairs of section 5.  (It fails on
+//              a difference of more than one ulp; how often the faithful quotient differs from the
+//              exact one at all is reported by counters[14].)
 // counters[2 * section] counts checks, counters[2 * section + 1] failures.
 
-constexpr int kSelftestSections = 8;
+constexpr int kSelftestSections = 7;
+constexpr uint64_t kSelftestSqrtCount = 0x7f800000ull - 0x0f800000ull;   // every FP32 value in [2^-96, FLT_MAX]
+constexpr uint64_t kSelftestDivCount = (1ull << 30) + (1ull << 24);
 
 __device__ __forceinline__ uint32_t selftest_hash(uint64_t x) {
     x ^= x >> 33; x *= 0xff51afd7ed558ccdull; x ^= x >> 33; x *= 0xc4ceb9fe1a85ec53ull; x ^= x >> 33;
@@ -1530,15 +1511,10 @@ __global__ __launch_bounds__(kThreads) void selftest_kernel(unsigned long long* 
             failed = diff > 1 || diff < -1;
         }
     } else if (section == 2) {
-        if (gid < (1ull << 25) + (1ull << 24)) {
-            uint32_t bits;
-            if (gid < (1ull << 25)) bits = 0x0f800000u + (uint32_t)(gid * 55u);   // 2^-96 ... just below 2^128
-            else bits = 0x3f800000u + (uint32_t)(gid - (1ull << 25));             // [1, 4)
-            if (bits < 0x7f800000u) {
-                const float x = u2f(bits);
-                checked = true;
-                failed = f2u(sqrt_rn_midrange(x)) != f2u(sqrtf(x));
-            }
+        if (gid < kSelftestSqrtCount) {
+            const float x = u2f(0x0f800000u + (uint32_t)gid);                     // 2^-96 ... FLT_MAX, every value
+            checked = true;
+            failed = f2u(sqrt_rn_midrange(x)) != f2u(sqrtf(x));
         }
     } else if (section == 3) {
         if (gid < 2ull * 14 * (1ull << 23)) {
@@ -1551,30 +1527,16 @@ __global__ __launch_bounds__(kThreads) void selftest_kernel(unsigned long long* 
             checked = !(resid > 0.5f - kTieWindowM);
             failed = fast != exact;
         }
-    } else if (section == 6) {
-        if (gid < (1ull << 25) + (1ull << 24)) {
-            uint32_t bits;
-            if (gid < (1ull << 25)) bits = 0x0f800000u + (uint32_t)(gid * 55u);
-            else bits = 0x3f800000u + (uint32_t)(gid - (1ull << 25));
-            if (bits < 0x7f800000u) {
-                const float x = u2f(bits);
-                const int32_t diff = (int32_t)f2u(sqrt_faithful(x)) - (int32_t)f2u(sqrtf(x));
-                checked = true;
-                failed = diff > 1 || diff < -1;
-                const unsigned long long inexact = __popcll(__builtin_amdgcn_ballot_w64(diff != 0));
-                if ((threadIdx.x & 63) == 0 && inexact) atomicAdd(&counters[16], inexact);
-            }
-        }
-    } else if (section == 5 || section == 7) {
-        if (gid < (1ull << 26) + (1ull << 24)) {
+    } else if (section == 5 || section == 6) {
+        if (gid < kSelftestDivCount) {
             uint32_t nb, db;
-            if (gid < (1ull << 26)) {
+            if (gid < (1ull << 30)) {
                 const uint32_t h1 = selftest_hash(2 * gid + 1), h2 = selftest_hash(2 * gid + 2);
                 // exponent fields 67..187 = 2^-60 .. 2^60
                 nb = (h1 & 0x807fffffu) | ((67u + (h1 >> 23) % 121u) << 23);
                 db = (h2 & 0x007fffffu) | ((67u + (h2 >> 23) % 121u) << 23);
             } else {
-                const uint32_t k = (uint32_t)(gid - (1ull << 26));
+                const uint32_t k = (uint32_t)(gid - (1ull << 30));
                 nb = 0x3a000000u + (k & 0x7fffffu) + ((k >> 23) << 31);      // all mantissas, both signs
                 db = 0x38d1b717u + (k >> 23) * 0x00345678u;                   // a typical denominator ~1e-4
             }
@@ -1586,7 +1548,7 @@ __global__ __launch_bounds__(kThreads) void selftest_kernel(unsigned long long* 
                 const int32_t diff = (int32_t)f2u(div_faithful(n, d)) - (int32_t)f2u(n / d);
                 failed = diff > 1 || diff < -1;
                 const unsigned long long inexact = __popcll(__builtin_amdgcn_ballot_w64(diff != 0));
-                if ((threadIdx.x & 63) == 0 && inexact) atomicAdd(&counters[17], inexact);
+                if ((threadIdx.x & 63) == 0 && inexact) atomicAdd(&counters[14], inexact);
             }
         }
     } else {
@@ -1613,10 +1575,9 @@ hipError_t launch_selftest(unsigned long long* counters, int section, const Step
     uint64_t n = 0;
     if (section == 0) n = 0x7c00;
     else if (section == 1) n = 1ull << 24;
-    else if (section == 2) n = (1ull << 25) + (1ull << 24);
+    else if (section == 2) n = kSelftestSqrtCount;
     else if (section == 3) n = 2ull * 14 * (1ull << 23);
-    else if (section == 5 || section == 7) n = (1ull << 26) + (1ull << 24);
-    else if (section == 6) n = (1ull << 25) + (1ull << 24);
+    else if (section == 5 || section == 6) n = kSelftestDivCount;
     else n = 4ull * (1ull << 23);
     hipLaunchKernelGGL(selftest_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s,
                        counters, section, c, scale_r);

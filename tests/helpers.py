@@ -150,7 +150,7 @@ def tie_inputs_variance():
 
 # ---- the two AdamW entry points ----------------------------------------------------------------------
 # "exact": flashoptim_adamw_step_exact, bit-identical to the oracle by construction: tests assert ZERO
-# mismatches.  "default": flashoptim_adamw_step, whose square root and division are faithfully rounded:
+# mismatches.  "default": flashoptim_adamw_step, whose division is faithfully rounded:
 # tests assert the parity bar of compare_state (codes and rho within 1 LSB on at most 1e-5 of the elements,
 # scales exact, weights within 1e-6 relative) and print what they find.
 ADAMW_MODES = ("exact", "default")
