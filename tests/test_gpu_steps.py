@@ -191,6 +191,32 @@ def test_zero_variance_with_live_momentum_and_small_eps(eps, mode):
         assert sum(r[1] for r in rep) == 0
 
 
+@pytest.mark.parametrize("kind,hp", [("adamw", ADAMW), ("sgd", SGD), ("lion", LION)])
+def test_zero_element_tensors_and_empty_lists(kind, hp):
+    # tensors without elements are skipped wherever they stand in the list; a list of nothing is a no-op
+    specs = [W.ParamSpec("e0", (0,), "bias"), W.ParamSpec("a", (33,), "matrix"), W.ParamSpec("e1", (0,), "matrix"),
+             W.ParamSpec("b", (4097,), "matrix"), W.ParamSpec("e2", (0,), "gain")]
+    states = [oracle.TensorState(W.theta0(sp, i, seed=8).numpy(), kind) if sp.numel else None for i, sp in enumerate(specs)]
+    bufs = [upload_state(s) if s is not None else fo.ParamBuffers(0, kind) for s in states]
+    for b in bufs:
+        b.lr, b.weight_decay = hp["lr"], hp["wd"]
+    report = []
+    for t in (1, 2):
+        for i, (b, sp) in enumerate(zip(bufs, specs)):
+            if sp.numel:
+                g = W.grad_bf16(sp, i, t, seed=8)
+                b.grad.copy_(g.cuda())
+                _oracle_step(kind, states[i], _g_bits(g), hp["lr"], hp["wd"], hp, t)
+        _gpu_step(kind, fo.TensorList(bufs), hp, t)
+        _gpu_step(kind, fo.TensorList([bufs[0], bufs[2]]), hp, t)        # only empty tensors
+        _gpu_step(kind, fo.TensorList([]), hp, t)                        # no tensors at all
+        _gpu_step(kind, fo.TensorList([bufs[4]]), hp, t)                 # the single-tensor path with nothing in it
+        for i, sp in enumerate(specs):
+            if sp.numel:
+                compare_state(download(bufs[i]), states[i], where=f"{kind} {sp.name} t={t}", report=report)
+    assert_parity(report, "exact", f"{kind} with empty tensors")
+
+
 def _run_list(kind, hp, specs, seed, dist, scale, per_tensor_sigma, steps, nthreads=0, mode="exact"):
     states = [oracle.TensorState(W.theta0(sp, i, seed=seed).numpy(), kind) for i, sp in enumerate(specs)]
     bufs = [upload_state(s) for s in states]
