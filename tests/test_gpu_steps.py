@@ -368,6 +368,56 @@ def test_non_default_stream_and_two_lists_interleaved():
         assert sum(r[1] for r in rep) == 0
 
 
+def test_two_host_threads_step_their_own_lists_at_once():
+    # two host threads, each with its own list and stream, call the library concurrently (the foreign-function
+    # call releases the interpreter lock): the cached tables and their staging are shared, locked state
+    import threading
+    specs = W.odd_sizes()[4:14]
+    work = []
+    for k, (kind, hp) in enumerate((("adamw", ADAMW), ("sgd", SGD))):
+        states = [oracle.TensorState(W.theta0(sp, i, seed=40 + k).numpy(), kind) for i, sp in enumerate(specs)]
+        bufs = [upload_state(s) for s in states]
+        for b, sp in zip(bufs, specs):
+            b.lr, b.weight_decay = hp["lr"], weight_decay_for(sp, hp["wd"])
+        grads = {t: grads_for(specs, t, seed=40 + k) for t in range(1, 21)}
+        dev = {t: [g.cuda() for g in gs] for t, gs in grads.items()}
+        work.append((kind, hp, states, bufs, grads, dev, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    errors = []
+
+    def run(kind, hp, states, bufs, grads, dev, stream):
+        try:
+            tl = fo.TensorList(bufs)
+            for t in range(1, 21):
+                with torch.cuda.stream(stream):
+                    for i, b in enumerate(bufs):
+                        b.grad.copy_(dev[t][i], non_blocking=True)
+                        tl.set_hyper(i, lr=hp["lr"] * (1.0 + 0.01 * t))     # forces a table upload every step
+                    if kind == "adamw":
+                        fo.adamw_step_exact(tl, hp["beta1"], hp["beta2"], hp["eps"], t, stream=stream)
+                    else:
+                        fo.sgd_step(tl, hp["momentum"], stream=stream)
+            stream.synchronize()
+        except Exception as e:                                              # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=run, args=w) for w in work]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=120)
+        assert not th.is_alive()
+    assert not errors, errors
+    for kind, hp, states, bufs, grads, dev, stream in work:
+        for t in range(1, 21):
+            for i, (s, sp) in enumerate(zip(states, specs)):
+                _oracle_step(kind, s, _g_bits(grads[t][i]), float(np.float32(hp["lr"] * (1.0 + 0.01 * t))),
+                             weight_decay_for(sp, hp["wd"]), hp, t)
+        for i, s in enumerate(states):
+            rep = compare_state(download(bufs[i]), s, where=f"threads {kind} {specs[i].name}")
+            assert sum(r[1] for r in rep) == 0
+
+
 def test_many_distinct_lists_evict_cached_tables():
     # more distinct lists than the library keeps cached tables for; every call must still be right
     spec = W.ParamSpec("w", (3000,), "matrix")
