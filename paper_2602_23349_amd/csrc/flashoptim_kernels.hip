@@ -1097,6 +1097,20 @@ __device__ __forceinline__ float reconstruct_n(uint32_t b, int rho) {
     const float q = (float)rho / (float)N;
     return base + ldexpf(q, half_ulp_log2(b));
 }
+// The 8-bit case with rho / 127 read from a staged copy of the table of these divisions.
+__device__ __forceinline__ float reconstruct_tab(const float* rho_over_127, uint32_t b, uint32_t rho_byte) {
+    const float base = u2f(b << 16);
+    if (((b >> 7) & 0xffu) == 255u) return base;
+    return base + ldexpf(rho_over_127[rho_byte], half_ulp_log2(b));
+}
+
+// Copies one 256-entry decode table into LDS, one entry per lane of a 256-lane workgroup, and waits for
+// it.  Every lane of the workgroup must call it.
+__device__ __forceinline__ void stage_table(float* lds, const float* table) {
+    static_assert(kThreads == 256, "one table entry per lane");
+    lds[threadIdx.x] = table[threadIdx.x];
+    __syncthreads();
+}
 
 template <int N, typename RHO>
 __global__ __launch_bounds__(kThreads) void split_kernel(const float* theta, uint16_t* param, RHO* rho, int64_t n) {
@@ -1125,15 +1139,18 @@ template <int N, typename RHO>
 __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const uint16_t* param, const RHO* rho, float* theta,
                                                                int64_t n) {
     const LanePos L = lane_pos(n);
+    __shared__ float rho_over_n[sizeof(RHO) == 1 ? 256 : 1];
+    if constexpr (sizeof(RHO) == 1) stage_table(rho_over_n, g_decode_tables.rho);
     if (L.cnt == 0) return;
     uint32_t pw[kCodecVec / 2];
     load_u16(pw, param, L);
     float th[kCodecVec];
     if constexpr (sizeof(RHO) == 1) {
+        static_assert(sizeof(RHO) != 1 || N == 127, "the table holds rho / 127");
         uint32_t rw[kCodecVec / 4];
         load_u8(rw, rho, L);
 #pragma unroll
-        for (int i = 0; i < kCodecVec; ++i) th[i] = reconstruct_n<N>(half_of(pw, i), (int)(int8_t)byte_of(rw, i));
+        for (int i = 0; i < kCodecVec; ++i) th[i] = reconstruct_tab(rho_over_n, half_of(pw, i), byte_of(rw, i));
     } else {
         uint32_t rw[kCodecVec / 2];
         load_u16(rw, rho, L);
@@ -1242,14 +1259,17 @@ __device__ __forceinline__ uint32_t quantize_lane(const float (&x)[kCodecVec], u
     return sbits;
 }
 
+// Decoders of Algorithms 2 and 3 (and of the linear baseline).  What is multiplied by the group scale
+// is a function of the code byte alone - q / 255, q / 127, phi_m^-1(q / 127) - and comes from a staged
+// copy of the table of those defining divisions instead of one or two IEEE divisions per element.
 template <bool VARIANCE, bool LINEAR>
-__device__ __forceinline__ float dequantize_one(uint8_t q, float s) {
-    if (VARIANCE) {
-        const float v1 = ((float)q / 255.0f) * s;
-        return LINEAR ? v1 : v1 * v1;
-    }
-    const float z = (float)(int)(int8_t)q / 127.0f;
-    return LINEAR ? z * s : (z / (2.0f - fabsf(z))) * s;
+__device__ __forceinline__ const float* decode_table() {
+    return VARIANCE ? g_decode_tables.v : (LINEAR ? g_decode_tables.rho : g_decode_tables.m);
+}
+template <bool VARIANCE, bool LINEAR>
+__device__ __forceinline__ float dequantize_one(const float* tab, uint32_t q, float s) {
+    const float f = tab[q] * s;
+    return (VARIANCE && !LINEAR) ? f * f : f;
 }
 
 __device__ __forceinline__ bool group_leader(const LanePos& L) {
@@ -1273,13 +1293,15 @@ template <bool VARIANCE, bool LINEAR>
 __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* q, const uint16_t* scale, float* x,
                                                               int64_t n) {
     const LanePos L = lane_pos(n);
+    __shared__ float tab[256];
+    stage_table(tab, decode_table<VARIANCE, LINEAR>());
     if (L.cnt == 0) return;
     uint32_t w[kCodecVec / 4];
     load_u8(w, q, L);
     const float s = (float)__builtin_bit_cast(_Float16, scale[(L.tile0 + L.lane_el) >> 5]);
     float v[kCodecVec];
 #pragma unroll
-    for (int i = 0; i < kCodecVec; ++i) v[i] = dequantize_one<VARIANCE, LINEAR>((uint8_t)byte_of(w, i), s);
+    for (int i = 0; i < kCodecVec; ++i) v[i] = dequantize_one<VARIANCE, LINEAR>(tab, byte_of(w, i), s);
     store_f32(x, L, v);
 }
 
@@ -1290,6 +1312,8 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* q, 
 template <bool VARIANCE, bool LINEAR>
 __global__ __launch_bounds__(kThreads) void nmse_kernel(const float* x, int64_t n, double* sums) {
     const int64_t n_tiles = (n + kCodecTile - 1) / kCodecTile;
+    __shared__ float tab[256];
+    stage_table(tab, decode_table<VARIANCE, LINEAR>());
     double err = 0.0, ref = 0.0;
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const LanePos L = lane_pos_at(tile * kCodecTile, n);
@@ -1302,7 +1326,7 @@ __global__ __launch_bounds__(kThreads) void nmse_kernel(const float* x, int64_t 
         for (int i = 0; i < kCodecVec; ++i) {
             if (i < L.cnt) {
                 const double xi = (double)v[i];
-                const double d = (double)dequantize_one<VARIANCE, LINEAR>((uint8_t)codes[i], s) - xi;
+                const double d = (double)dequantize_one<VARIANCE, LINEAR>(tab, codes[i], s) - xi;
                 err += d * d;
                 ref += xi * xi;
             }
@@ -1377,7 +1401,8 @@ void launch_nmse(bool variance, bool linear, const float* x, int64_t n, double* 
 //
 // Migration between a standard FP32 optimizer state (theta, m, v: 12 B/param for AdamW) and
 // the compressed layout: COMPRESS applies C, Q_m, Q_v (Algorithms 1-3) in one pass over a list;
-// the other direction applies the inverses.  Written with the plain exact forms; same tile
+// the other direction applies the inverses (its per-code factors from staged tables of the defining
+// divisions).  Written with the plain exact forms; same tile
 // look-up and lane layout (8 elements per lane, a lane quad per group) as the step kernels.
 static_assert(kCodecTile == kConvChunkElems, "the host builds the conversion's tables for tiles of this size");
 
@@ -1418,24 +1443,28 @@ __global__ __launch_bounds__(kThreads) void convert_kernel(StepArgs a) {
             if (group_leader(L)) T.v_scale[group] = (uint16_t)vs;
         }
     } else {
+        __shared__ float tab[3][256];        // rho / 127, phi_m^-1(q / 127), q / 255
+        tab[0][threadIdx.x] = g_decode_tables.rho[threadIdx.x];
+        tab[1][threadIdx.x] = g_decode_tables.m[threadIdx.x];
+        stage_table(tab[2], g_decode_tables.v);
         if (L.cnt == 0) return;
         uint32_t pw[kCodecVec / 2], w[kCodecVec / 4];
         float f[kCodecVec];
         load_u16(pw, T.param, L);
         load_u8(w, T.rho, L);
 #pragma unroll
-        for (int i = 0; i < kCodecVec; ++i) f[i] = reconstruct_n<127>(half_of(pw, i), (int)(int8_t)byte_of(w, i));
+        for (int i = 0; i < kCodecVec; ++i) f[i] = reconstruct_tab(tab[0], half_of(pw, i), byte_of(w, i));
         store_f32(T.theta32, L, f);
         const float s_m = (float)__builtin_bit_cast(_Float16, T.m_scale[group]);
         load_u8(w, T.m_q, L);
 #pragma unroll
-        for (int i = 0; i < kCodecVec; ++i) f[i] = dequantize_one<false, false>((uint8_t)byte_of(w, i), s_m);
+        for (int i = 0; i < kCodecVec; ++i) f[i] = dequantize_one<false, false>(tab[1], byte_of(w, i), s_m);
         store_f32(T.m32, L, f);
         if (HAS_V) {
             const float s_v = (float)__builtin_bit_cast(_Float16, T.v_scale[group]);
             load_u8(w, T.v_q, L);
 #pragma unroll
-            for (int i = 0; i < kCodecVec; ++i) f[i] = dequantize_one<true, false>((uint8_t)byte_of(w, i), s_v);
+            for (int i = 0; i < kCodecVec; ++i) f[i] = dequantize_one<true, false>(tab[2], byte_of(w, i), s_v);
             store_f32(T.v32, L, f);
         }
     }
