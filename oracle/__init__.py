@@ -48,6 +48,10 @@ def _declare(L):
     L.fo_oracle_split.argtypes = [vp, vp, vp, i64, i32]
     L.fo_oracle_reconstruct.restype = None
     L.fo_oracle_reconstruct.argtypes = [vp, vp, vp, i64, i32]
+    L.fo_oracle_split_directional.restype = None
+    L.fo_oracle_split_directional.argtypes = [vp, vp, vp, i64, i32]
+    L.fo_oracle_reconstruct_directional.restype = None
+    L.fo_oracle_reconstruct_directional.argtypes = [vp, vp, vp, i64, i32]
     for name in ("fo_oracle_quantize_momentum", "fo_oracle_dequantize_momentum",
                  "fo_oracle_quantize_variance", "fo_oracle_dequantize_variance",
                  "fo_oracle_quantize_momentum_linear", "fo_oracle_dequantize_momentum_linear",
@@ -71,6 +75,8 @@ def _declare(L):
     L.fo_oracle_checkpoint_unpack.argtypes = [i32, vp, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
     L.fo_oracle_split_sweep.restype = None
     L.fo_oracle_split_sweep.argtypes = [C.c_uint64, C.c_uint64, i32, vp, vp, i32]
+    L.fo_oracle_split_sweep_ex.restype = None
+    L.fo_oracle_split_sweep_ex.argtypes = [C.c_uint64, C.c_uint64, i32, i32, vp, vp, vp, vp, i32]
     L.fo_oracle_max_threads.restype = i32
     L.fo_oracle_max_threads.argtypes = []
 
@@ -126,20 +132,23 @@ def half_ulp_log2(thp_bits):
 
 # ------------------------------------------------------------------- codecs --
 
-def split(theta, N=127):
-    """C(theta) -> (theta' as uint16 BF16 bits, rho as int8 for N=127 else int16)."""
+def split(theta, N=127, directional=False):
+    """C(theta) -> (theta' as uint16 BF16 bits, rho as int8 for N=127 else int16).  directional=True: the
+    alternative reading of ULP(theta') that exists for the Section 4.4 experiment only."""
     theta = _c(theta, np.float32)
     thp = np.empty(theta.shape, np.uint16)
     rho = np.empty(theta.shape, np.int16)
-    lib().fo_oracle_split(_p(theta), _p(thp), _p(rho), theta.size, int(N))
+    fn = lib().fo_oracle_split_directional if directional else lib().fo_oracle_split
+    fn(_p(theta), _p(thp), _p(rho), theta.size, int(N))
     return thp, (rho.astype(np.int8) if N == 127 else rho)
 
 
-def reconstruct(thp, rho, N=127):
+def reconstruct(thp, rho, N=127, directional=False):
     thp = _c(thp, np.uint16)
     rho16 = _c(rho, np.int16)
     out = np.empty(thp.shape, np.float32)
-    lib().fo_oracle_reconstruct(_p(thp), _p(rho16), _p(out), thp.size, int(N))
+    fn = lib().fo_oracle_reconstruct_directional if directional else lib().fo_oracle_reconstruct
+    fn(_p(thp), _p(rho16), _p(out), thp.size, int(N))
     return out
 
 
@@ -309,12 +318,17 @@ def checkpoint_unpack(kind, blob, states):
 
 # -------------------------------------------------------------------- sweep --
 
-def split_sweep(first=0, stride=1, N=127, nthreads=0):
+def split_sweep(first=0, stride=1, N=127, nthreads=0, directional=False):
     out = np.zeros(9, np.float64)
     mean_rel = np.zeros(256, np.float64)
-    lib().fo_oracle_split_sweep(int(first), int(stride), int(N), _p(out), _p(mean_rel), int(nthreads))
+    exact_by = np.zeros(256, np.float64)
+    count_by = np.zeros(256, np.float64)
+    lib().fo_oracle_split_sweep_ex(int(first), int(stride), int(N), int(bool(directional)), _p(out), _p(mean_rel),
+                                   _p(exact_by), _p(count_by), int(nthreads))
     keys = ["measured", "skipped", "interval_violations", "max_err_over_bound", "max_rel_err",
             "bit_exact", "rho_out_of_range", "tie_rule_differs", "not_nearest"]
     d = {k: float(v) for k, v in zip(keys, out)}
     d["mean_rel_by_exponent"] = mean_rel
+    d["bit_exact_by_exponent"] = exact_by
+    d["count_by_exponent"] = count_by
     return d

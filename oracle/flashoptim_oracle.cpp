@@ -22,6 +22,10 @@
 //   [R-A2] ULP(theta') = 2^(max(E,1)-134) with E the biased exponent field of
 //          theta'; zero and BF16 subnormals share the spacing of the lowest
 //          binade.  The sign of the error is not consulted.
+//          An alternative reading, "directional", exists ONLY for the Section 4.4 sweep (see
+//          split_one_directional): the paper prints 99.92 % bit-exact 16-bit reconstructions, which
+//          the literal reading does not reach and the directional one does.  The steps, the
+//          codecs and the checkpoint never use it.
 //   [R-A3] Round(.) in Algorithm 1 is round-half-to-even.
 //   [R-A6] Non-finite theta': rho = 0 and reconstruction returns theta'.
 //   [R-Q1] A group whose stored scale is zero encodes to all-zero codes and
@@ -154,6 +158,38 @@ float reconstruct_one(uint16_t thp, int rho, int N) {
     float q = (float)rho / (float)N;                      // Float32(rho) / N
     float e = (q * std::ldexp(1.0f, h)) * std::ldexp(1.0f, l - h);
     return base + e;
+}
+
+// "Directional" reading of ULP(theta') for the Section 4.4 experiment.  Algorithm 1 takes one spacing
+// u per theta'.  The BF16 grid, however, is twice as fine just below a power of two as above it: when
+// theta' = +-2^k (mantissa field 0, exponent field >= 2) and theta lies on the side of zero, the values
+// that round to theta' fill only [theta' - u/4, theta'], so e / (u/2) uses half of [-1, 1].  Under this
+// reading the spacing is taken on the side of theta' on which theta lies: u/2 in that one case, u
+// otherwise.  The decoder recognises the case from the signs of rho and theta' (rho has the sign of e).
+inline bool below_power_of_two(uint16_t thp, bool error_is_negative) {
+    int E = (thp >> 7) & 0xff;
+    bool negative = (thp & 0x8000) != 0;
+    return (thp & 0x7f) == 0 && E >= 2 && (error_is_negative != negative);
+}
+void split_one_directional(float theta, int N, uint16_t* thp_out, int* rho_out) {
+    uint16_t thp = bf16_rne(theta);
+    *thp_out = thp;
+    if (!bf16_is_finite(thp)) { *rho_out = 0; return; }
+    float e = theta - bf16_to_f32(thp);
+    int l = half_ulp_log2(thp);
+    if (e != 0.0f && below_power_of_two(thp, e < 0.0f)) l -= 1;
+    float e_norm = std::ldexp(e, -l);                     // exact: a power-of-two scaling within range
+    if (e_norm < -1.0f) e_norm = -1.0f;
+    if (e_norm > 1.0f) e_norm = 1.0f;
+    *rho_out = (int)std::rint(e_norm * (float)N);
+}
+float reconstruct_one_directional(uint16_t thp, int rho, int N) {
+    float base = bf16_to_f32(thp);
+    if (!bf16_is_finite(thp)) return base;
+    int l = half_ulp_log2(thp);
+    if (rho != 0 && below_power_of_two(thp, rho < 0)) l -= 1;
+    float q = (float)rho / (float)N;
+    return base + std::ldexp(q, l);                       // one rounding at most (subnormal results)
 }
 
 // --------------------------------------------- companded quantizers, Alg. 2/3 --
@@ -605,29 +641,32 @@ int fo_oracle_checkpoint_unpack(int kind, const uint8_t* blob, int64_t blob_byte
 // out[8] = count where theta' is not the BF16 nearest to theta (checked against both neighbours)
 // mean_rel[E] (256 entries, may be null) = mean relative error of the FP32
 //          values with biased exponent E.
-void fo_oracle_split_sweep(uint64_t first, uint64_t stride, int N, double* out, double* mean_rel,
-                           int nthreads) {
+// directional != 0 runs the experiment under the directional reading of ULP(theta') instead of the
+// literal one.  exact_by_exp / count_by_exp (256 entries each, may be null): bit-exact reconstructions
+// and values measured among the normal FP32 values with biased exponent E.
+void fo_oracle_split_sweep_ex(uint64_t first, uint64_t stride, int N, int directional, double* out,
+                              double* mean_rel, double* exact_by_exp, double* count_by_exp, int nthreads) {
     set_threads(nthreads);
     double measured = 0, skipped = 0, viol = 0, exact = 0, range_bad = 0, tie_diff = 0, not_nearest = 0;
     double max_ratio = 0, max_rel = 0;
-    double rel_sum[256]; double rel_cnt[256];
-    for (int i = 0; i < 256; ++i) { rel_sum[i] = 0; rel_cnt[i] = 0; }
+    double rel_sum[256]; double rel_cnt[256]; double ex_cnt[256];
+    for (int i = 0; i < 256; ++i) { rel_sum[i] = 0; rel_cnt[i] = 0; ex_cnt[i] = 0; }
     const uint64_t count = (first < (1ull << 32)) ? (((1ull << 32) - first + stride - 1) / stride) : 0;
 #pragma omp parallel
     {
         double l_meas = 0, l_skip = 0, l_viol = 0, l_exact = 0, l_range = 0, l_tie = 0, l_near = 0;
         double l_ratio = 0, l_rel = 0;
-        double l_sum[256]; double l_cnt[256];
-        for (int i = 0; i < 256; ++i) { l_sum[i] = 0; l_cnt[i] = 0; }
+        double l_sum[256]; double l_cnt[256]; double l_ex[256];
+        for (int i = 0; i < 256; ++i) { l_sum[i] = 0; l_cnt[i] = 0; l_ex[i] = 0; }
 #pragma omp for schedule(static)
         for (int64_t j = 0; j < (int64_t)count; ++j) {
             uint32_t bits = (uint32_t)(first + (uint64_t)j * stride);
             float theta = bits_f32(bits);
             if (!std::isfinite(theta)) { l_skip += 1; continue; }
             uint16_t thp; int rho;
-            split_one(theta, N, &thp, &rho);
+            if (directional) split_one_directional(theta, N, &thp, &rho); else split_one(theta, N, &thp, &rho);
             if (!bf16_is_finite(thp)) { l_skip += 1; continue; }
-            float hat = reconstruct_one(thp, rho, N);
+            float hat = directional ? reconstruct_one_directional(thp, rho, N) : reconstruct_one(thp, rho, N);
             l_meas += 1;
             double th = (double)theta, tp = (double)bf16_to_f32(thp);
             int E = (thp >> 7) & 0xff; if (E < 1) E = 1;
@@ -649,10 +688,11 @@ void fo_oracle_split_sweep(uint64_t first, uint64_t stride, int N, double* out, 
             double err = std::fabs((double)hat - th);
             double ratio = err / (u / (4.0 * N));
             if (ratio > l_ratio) l_ratio = ratio;
-            if (f32_bits(hat) == bits || (hat == theta)) l_exact += 1;
+            const bool is_exact = f32_bits(hat) == bits || (hat == theta);
+            if (is_exact) l_exact += 1;
             if (rho < -N || rho > N) l_range += 1;
-            // would half-away-from-zero rounding have given a different rho?
-            {
+            // would half-away-from-zero rounding have given a different rho? (literal reading only)
+            if (!directional) {
                 double en = (th - tp) / (u / 2);
                 if (en < -1) en = -1; if (en > 1) en = 1;
                 double y = en * N;
@@ -664,6 +704,7 @@ void fo_oracle_split_sweep(uint64_t first, uint64_t stride, int N, double* out, 
                 double rel = err / std::fabs(th);
                 if (rel > l_rel) l_rel = rel;
                 l_sum[Ef] += rel; l_cnt[Ef] += 1;
+                if (is_exact) l_ex[Ef] += 1;
             }
         }
 #pragma omp critical
@@ -672,12 +713,25 @@ void fo_oracle_split_sweep(uint64_t first, uint64_t stride, int N, double* out, 
             range_bad += l_range; tie_diff += l_tie; not_nearest += l_near;
             if (l_ratio > max_ratio) max_ratio = l_ratio;
             if (l_rel > max_rel) max_rel = l_rel;
-            for (int i = 0; i < 256; ++i) { rel_sum[i] += l_sum[i]; rel_cnt[i] += l_cnt[i]; }
+            for (int i = 0; i < 256; ++i) { rel_sum[i] += l_sum[i]; rel_cnt[i] += l_cnt[i]; ex_cnt[i] += l_ex[i]; }
         }
     }
     out[0] = measured; out[1] = skipped; out[2] = viol; out[3] = max_ratio; out[4] = max_rel;
     out[5] = exact; out[6] = range_bad; out[7] = tie_diff; out[8] = not_nearest;
     if (mean_rel) for (int i = 0; i < 256; ++i) mean_rel[i] = rel_cnt[i] > 0 ? rel_sum[i] / rel_cnt[i] : 0.0;
+    if (exact_by_exp) for (int i = 0; i < 256; ++i) exact_by_exp[i] = ex_cnt[i];
+    if (count_by_exp) for (int i = 0; i < 256; ++i) count_by_exp[i] = rel_cnt[i];
+}
+void fo_oracle_split_sweep(uint64_t first, uint64_t stride, int N, double* out, double* mean_rel,
+                           int nthreads) {
+    fo_oracle_split_sweep_ex(first, stride, N, 0, out, mean_rel, nullptr, nullptr, nthreads);
+}
+// Array forms of the directional reading (tests only).
+void fo_oracle_split_directional(const float* theta, uint16_t* thp, int16_t* rho, int64_t n, int N) {
+    for (int64_t i = 0; i < n; ++i) { int r; split_one_directional(theta[i], N, &thp[i], &r); rho[i] = (int16_t)r; }
+}
+void fo_oracle_reconstruct_directional(const uint16_t* thp, const int16_t* rho, float* theta, int64_t n, int N) {
+    for (int64_t i = 0; i < n; ++i) theta[i] = reconstruct_one_directional(thp[i], (int)rho[i], N);
 }
 
 int fo_oracle_max_threads(void) {

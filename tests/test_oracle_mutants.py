@@ -33,6 +33,10 @@ MUTANTS = [
     ("reconstruction: divides by N + 1", "float q = (float)rho / (float)N;", "float q = (float)rho / (float)(N + 1);"),
     ("variance: square root dropped in the encoder", "vr[i] = std::sqrt(v[i]);", "vr[i] = v[i];"),
     ("variance: square dropped in the decoder", "return v1 * v1;", "return v1;"),
+    ("directional reading: spacing doubled instead of halved below a power of two",
+     "    if (e != 0.0f && below_power_of_two(thp, e < 0.0f)) l -= 1;", "    if (e != 0.0f && below_power_of_two(thp, e < 0.0f)) l += 1;"),
+    ("directional reading: decoder ignores the side", "    if (rho != 0 && below_power_of_two(thp, rho < 0)) l -= 1;", ""),
+    ("directional reading: side test ignores the sign of theta'", "(error_is_negative != negative);", "error_is_negative;"),
     ("AdamW: beta1 and 1 - beta1 swapped", "float mt = (beta1 * m) + (omb1 * gr);          // m_t",
      "float mt = (omb1 * m) + (beta1 * gr);          // m_t"),
     ("AdamW: gradient not squared", "float gg = gr * gr;", "float gg = gr;"),
