@@ -199,6 +199,17 @@ int flashoptim_reconstruct_weights_i16(const void* param_bf16, const int16_t* rh
                                        void* stream);
 int flashoptim_reconstruction_sweep(int correction_bits, uint64_t first, uint64_t stride, double* stats,
                                     void* stream);
+/* The same experiment with a choice of how ULP(theta') is read, and per-exponent counts of bit-exact
+ * reconstructions.  ulp_reading 0: Algorithm 1 as printed, one spacing per theta' (what every other entry
+ * point of this library uses).  ulp_reading 1, "directional": the spacing of the BF16 grid on the side of
+ * theta' on which theta lies, which is half as large when theta' is a power of two and theta lies towards
+ * zero; Section 4.4 prints 99.92 % bit-exact reconstructions for the 16-bit correction, which this reading
+ * reproduces over the mid-range exponents and the printed algorithm does not (99.73 %).  It exists for this
+ * experiment only.  stats: HOST array of 776 doubles, the 520 above followed by [520 + E] bit-exact
+ * reconstructions among the normal values with FP32 exponent field E.  [2] and [3] refer to the printed
+ * ULP under both readings.  Waits for completion. */
+int flashoptim_reconstruction_sweep_ex(int correction_bits, int ulp_reading, uint64_t first, uint64_t stride,
+                                       double* stats, void* stream);
 
 /* ---- companded 8-bit state codecs (Section 3.2, Algorithms 2 and 3) -----------------
  * quantize_momentum:   per group s = FP16(max|m|), code = Round(127 * 2m'/(1+|m'|)), m' = m/s

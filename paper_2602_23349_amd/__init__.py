@@ -7,7 +7,7 @@ from .binding import (  # noqa: F401
     FlashOptimError, TensorList, ParamBuffers, library_path, load_library,
     adamw_step, adamw_step_exact, sgd_step, lion_step, adamw_step_ex, sgd_step_ex, lion_step_ex, TensorListEx,
     SPLIT_WEIGHTS, QUANTIZE_STATES,
-    split_weights, reconstruct_weights, split_weights_i16, reconstruct_weights_i16, reconstruction_sweep,
+    split_weights, reconstruct_weights, split_weights_i16, reconstruct_weights_i16, reconstruction_sweep, reconstruction_sweep_ex,
     quantize_momentum, dequantize_momentum, quantize_variance, dequantize_variance,
     quantize_state, dequantize_state, quantization_nmse, compress_state, decompress_state, stream_probe, step_launch_count,
     checkpoint_size, checkpoint_pack, checkpoint_unpack,

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = [
     "flashoptim_faithful_rounding_stats",
     "flashoptim_step_launch_count",
     "flashoptim_selftest", "flashoptim_split_weights_i16", "flashoptim_reconstruct_weights_i16",
-    "flashoptim_reconstruction_sweep",
+    "flashoptim_reconstruction_sweep", "flashoptim_reconstruction_sweep_ex",
     "flashoptim_adamw_step_ex", "flashoptim_sgd_step_ex", "flashoptim_lion_step_ex",
     "flashoptim_quantize_state", "flashoptim_dequantize_state", "flashoptim_quantization_nmse",
     "flashoptim_compress_state", "flashoptim_decompress_state", "flashoptim_stream_probe",
@@ -86,6 +86,7 @@ def load_library():
     L.flashoptim_sgd_step_ex.argtypes = [C.POINTER(_TensorEx), i64, C.POINTER(_SgdHp), C.c_uint, vp]
     L.flashoptim_lion_step_ex.argtypes = [C.POINTER(_TensorEx), i64, C.POINTER(_LionHp), C.c_uint, vp]
     L.flashoptim_reconstruction_sweep.argtypes = [i32, C.c_uint64, C.c_uint64, C.POINTER(C.c_double), vp]
+    L.flashoptim_reconstruction_sweep_ex.argtypes = [i32, i32, C.c_uint64, C.c_uint64, C.POINTER(C.c_double), vp]
     for name in ("flashoptim_split_weights", "flashoptim_reconstruct_weights", "flashoptim_split_weights_i16",
                  "flashoptim_reconstruct_weights_i16", "flashoptim_quantize_momentum",
                  "flashoptim_dequantize_momentum", "flashoptim_quantize_variance", "flashoptim_dequantize_variance"):
@@ -303,6 +304,15 @@ def reconstruction_sweep(correction_bits, first=0, stride=1, stream=None):
     stats = (C.c_double * 520)()
     _check(load_library().flashoptim_reconstruction_sweep(int(correction_bits), int(first), int(stride), stats,
                                                           _stream(stream)), "flashoptim_reconstruction_sweep")
+    return list(stats)
+
+
+def reconstruction_sweep_ex(correction_bits, ulp_reading, first=0, stride=1, stream=None):
+    """Returns the 776 statistics of flashoptim_reconstruction_sweep_ex (ulp_reading 0 literal, 1 directional)."""
+    stats = (C.c_double * 776)()
+    _check(load_library().flashoptim_reconstruction_sweep_ex(int(correction_bits), int(ulp_reading), int(first),
+                                                             int(stride), stats, _stream(stream)),
+           "flashoptim_reconstruction_sweep_ex")
     return list(stats)
 
 

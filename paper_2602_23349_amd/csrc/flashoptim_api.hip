@@ -596,19 +596,22 @@ int flashoptim_reconstruct_weights_i16(const void* param_bf16, const int16_t* rh
     return FLASHOPTIM_OK;
 }
 
-int flashoptim_reconstruction_sweep(int correction_bits, uint64_t first, uint64_t stride, double* stats,
-                                    void* stream_) {
-    if ((correction_bits != 8 && correction_bits != 16) || stride == 0 || !stats) return FLASHOPTIM_ERR_INVALID_ARG;
+// Runs the sweep and copies the first n_stats statistics to the host.
+static int run_sweep(int correction_bits, int ulp_reading, uint64_t first, uint64_t stride, double* stats,
+                     int n_stats, void* stream_) {
+    if ((correction_bits != 8 && correction_bits != 16) || (ulp_reading != 0 && ulp_reading != 1) || stride == 0 ||
+        !stats)
+        return FLASHOPTIM_ERR_INVALID_ARG;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const uint64_t limit = 1ull << 32;
     const uint64_t count = first < limit ? (limit - first + stride - 1) / stride : 0;
-    for (int i = 0; i < fo::kSweepStats; ++i) stats[i] = 0.0;
+    for (int i = 0; i < n_stats; ++i) stats[i] = 0.0;
     if (count == 0) return FLASHOPTIM_OK;
     double* d = nullptr;
     FO_HIP(hipMalloc((void**)&d, fo::kSweepStats * sizeof(double)));
     hipError_t e = hipMemsetAsync(d, 0, fo::kSweepStats * sizeof(double), stream);
-    if (e == hipSuccess) e = fo::launch_sweep(correction_bits, first, stride, count, d, stream);
-    if (e == hipSuccess) e = hipMemcpyAsync(stats, d, fo::kSweepStats * sizeof(double), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = fo::launch_sweep(correction_bits, ulp_reading == 1, first, stride, count, d, stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(stats, d, (size_t)n_stats * sizeof(double), hipMemcpyDeviceToHost, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     (void)hipFree(d);
     if (e != hipSuccess) {
@@ -617,6 +620,16 @@ int flashoptim_reconstruction_sweep(int correction_bits, uint64_t first, uint64_
         return FLASHOPTIM_ERR_HIP;
     }
     return FLASHOPTIM_OK;
+}
+
+int flashoptim_reconstruction_sweep(int correction_bits, uint64_t first, uint64_t stride, double* stats,
+                                    void* stream) {
+    return run_sweep(correction_bits, 0, first, stride, stats, 8 + 2 * 256, stream);
+}
+
+int flashoptim_reconstruction_sweep_ex(int correction_bits, int ulp_reading, uint64_t first, uint64_t stride,
+                                       double* stats, void* stream) {
+    return run_sweep(correction_bits, ulp_reading, first, stride, stats, fo::kSweepStats, stream);
 }
 
 int flashoptim_quantize_momentum(const float* m, int8_t* q, uint16_t* scale, int64_t n, void* stream) {

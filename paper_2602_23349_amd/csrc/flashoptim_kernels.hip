@@ -1104,6 +1104,33 @@ __device__ __forceinline__ float reconstruct_tab(const float* rho_over_127, uint
     return base + ldexpf(rho_over_127[rho_byte], half_ulp_log2(b));
 }
 
+// The "directional" reading of ULP(theta'), for the experiment of Section 4.4 only.  The BF16 grid is twice
+// as fine just below a power of two as above it, so for theta' = +-2^k (mantissa field 0, exponent field
+// at least 2) with theta on the side of zero the values that round to theta' span a quarter of the upper
+// spacing, not a half.  This reading takes the spacing of the side on which theta lies; the decoder knows
+// the side from the signs of rho and theta'.  With a 16-bit correction it reproduces the fraction of
+// bit-exact reconstructions that Section 4.4 prints.
+__device__ __forceinline__ bool finer_side(uint32_t b, bool toward_negative) {
+    const bool pow2 = (b & 0x7fu) == 0u && ((b >> 7) & 0xffu) >= 2u;
+    return pow2 && (toward_negative != ((b & 0x8000u) != 0u));
+}
+template <int N>
+__device__ __forceinline__ int split_rho_directional(float theta, uint32_t b) {
+    const int E = (int)((b >> 7) & 0xffu);
+    if (E == 255) return 0;
+    const float e = theta - u2f(b << 16);
+    const int shift = 135 - (E < 1 ? 1 : E) + ((e != 0.0f && finer_side(b, e < 0.0f)) ? 1 : 0);
+    const float c = __builtin_amdgcn_fmed3f(ldexpf(e, shift), -1.0f, 1.0f);
+    return (int)rintf(c * (float)N);
+}
+template <int N>
+__device__ __forceinline__ float reconstruct_directional(uint32_t b, int rho) {
+    const float base = u2f(b << 16);
+    if (((b >> 7) & 0xffu) == 255u) return base;
+    const float q = (float)rho / (float)N;
+    return base + ldexpf(q, half_ulp_log2(b) - ((rho != 0 && finer_side(b, rho < 0)) ? 1 : 0));
+}
+
 // Copies one 256-entry decode table into LDS, one entry per lane of a 256-lane workgroup, and waits for
 // it.  Every lane of the workgroup must call it.
 __device__ __forceinline__ void stage_table(float* lds, const float* table) {
@@ -1165,22 +1192,25 @@ __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const uint16_t* p
 // (doubles): [0] values measured, [1] skipped (non-finite theta or theta'), [2] values with
 // |theta - theta'| > ULP(theta')/2, [3] max |theta_hat - theta| / (ULP(theta')/(4N)),
 // [4] max relative error over normal theta, [5] bit-exact reconstructions, [6] rho outside
-// [-N, N], [7] unused, [8 + E] sum of relative errors and [264 + E] count of the normal values
-// with FP32 exponent field E.  [3] and [4] are accumulated as the bit patterns of non-negative
-// doubles with an integer maximum.
+// [-N, N], [7] unused, [8 + E] sum of relative errors, [264 + E] count and [520 + E] bit-exact
+// reconstructions of the normal values with FP32 exponent field E.  [3] and [4] are accumulated as the
+// bit patterns of non-negative doubles with an integer maximum.  DIRECTIONAL selects the alternative
+// reading of ULP(theta') above; [2] and [3] are measured against the printed (literal) ULP in both cases.
 constexpr int kSweepPerLane = 256;
 
-template <int N>
+template <int N, bool DIRECTIONAL>
 __global__ __launch_bounds__(kThreads) void sweep_kernel(uint64_t first, uint64_t stride, uint64_t count,
                                                          double* st) {
     __shared__ double bin_sum[256];
     __shared__ double bin_cnt[256];
+    __shared__ double bin_exact[256];
     bin_sum[threadIdx.x] = 0.0;
     bin_cnt[threadIdx.x] = 0.0;
+    bin_exact[threadIdx.x] = 0.0;
     __syncthreads();
     const uint64_t j0 = ((uint64_t)blockIdx.x * kThreads + threadIdx.x) * kSweepPerLane;
     double measured = 0, skipped = 0, viol = 0, exact = 0, range_bad = 0, max_ratio = 0, max_rel = 0;
-    double run_sum = 0, run_cnt = 0;
+    double run_sum = 0, run_cnt = 0, run_exact = 0;
     int run_exp = -1;
     for (int k = 0; k < kSweepPerLane; ++k) {
         const uint64_t j = j0 + (uint64_t)k;
@@ -1191,8 +1221,8 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(uint64_t first, uint64_
         if (Ef == 255u) { skipped += 1; continue; }
         const uint32_t b = bf16_pack(theta, 0.0f) & 0xffffu;
         if (((b >> 7) & 0xffu) == 255u) { skipped += 1; continue; }
-        const int rho = split_rho<N>(theta, b);
-        const float hat = reconstruct_n<N>(b, rho);
+        const int rho = DIRECTIONAL ? split_rho_directional<N>(theta, b) : split_rho<N>(theta, b);
+        const float hat = DIRECTIONAL ? reconstruct_directional<N>(b, rho) : reconstruct_n<N>(b, rho);
         measured += 1;
         const double th = (double)theta, tp = (double)u2f(b << 16);
         int E = (int)((b >> 7) & 0xffu);
@@ -1208,13 +1238,20 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(uint64_t first, uint64_
             const double rel = err / fabs(th);
             max_rel = rel > max_rel ? rel : max_rel;
             if ((int)Ef != run_exp) {
-                if (run_cnt > 0) { atomicAdd(&bin_sum[run_exp], run_sum); atomicAdd(&bin_cnt[run_exp], run_cnt); }
-                run_exp = (int)Ef; run_sum = 0; run_cnt = 0;
+                if (run_cnt > 0) {
+                    atomicAdd(&bin_sum[run_exp], run_sum); atomicAdd(&bin_cnt[run_exp], run_cnt);
+                    atomicAdd(&bin_exact[run_exp], run_exact);
+                }
+                run_exp = (int)Ef; run_sum = 0; run_cnt = 0; run_exact = 0;
             }
             run_sum += rel; run_cnt += 1;
+            if (hat == theta) run_exact += 1;
         }
     }
-    if (run_cnt > 0) { atomicAdd(&bin_sum[run_exp], run_sum); atomicAdd(&bin_cnt[run_exp], run_cnt); }
+    if (run_cnt > 0) {
+        atomicAdd(&bin_sum[run_exp], run_sum); atomicAdd(&bin_cnt[run_exp], run_cnt);
+        atomicAdd(&bin_exact[run_exp], run_exact);
+    }
     if (measured > 0) atomicAdd(&st[0], measured);
     if (skipped > 0) atomicAdd(&st[1], skipped);
     if (viol > 0) atomicAdd(&st[2], viol);
@@ -1226,6 +1263,7 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(uint64_t first, uint64_
     if (bin_cnt[threadIdx.x] > 0) {
         atomicAdd(&st[8 + threadIdx.x], bin_sum[threadIdx.x]);
         atomicAdd(&st[264 + threadIdx.x], bin_cnt[threadIdx.x]);
+        atomicAdd(&st[520 + threadIdx.x], bin_exact[threadIdx.x]);
     }
 }
 
@@ -1358,11 +1396,14 @@ void launch_reconstruct(int bits, const void* param, const void* rho, float* the
     else hipLaunchKernelGGL((reconstruct_kernel<32767, int16_t>), dim3(tiles_for(n)), dim3(kThreads), 0, s,
                             (const uint16_t*)param, (const int16_t*)rho, theta, n);
 }
-hipError_t launch_sweep(int bits, uint64_t first, uint64_t stride, uint64_t count, double* stats, hipStream_t s) {
+hipError_t launch_sweep(int bits, bool directional, uint64_t first, uint64_t stride, uint64_t count, double* stats,
+                        hipStream_t s) {
     const uint64_t lanes = (count + kSweepPerLane - 1) / kSweepPerLane;
-    const unsigned grid = (unsigned)((lanes + kThreads - 1) / kThreads);
-    if (bits == 8) hipLaunchKernelGGL((sweep_kernel<127>), dim3(grid), dim3(kThreads), 0, s, first, stride, count, stats);
-    else hipLaunchKernelGGL((sweep_kernel<32767>), dim3(grid), dim3(kThreads), 0, s, first, stride, count, stats);
+    const dim3 grid((unsigned)((lanes + kThreads - 1) / kThreads)), block(kThreads);
+#define FO_SWEEP(NN, DIR) hipLaunchKernelGGL((sweep_kernel<NN, DIR>), grid, block, 0, s, first, stride, count, stats)
+    if (bits == 8) { if (directional) FO_SWEEP(127, true); else FO_SWEEP(127, false); }
+    else { if (directional) FO_SWEEP(32767, true); else FO_SWEEP(32767, false); }
+#undef FO_SWEEP
     return hipGetLastError();
 }
 template <bool VARIANCE, bool LINEAR>
