@@ -307,6 +307,19 @@ def test_checkpoint_pack_unpack_small_lists():
         blob2 = blob.clone(); blob2[0] = 0
         with pytest.raises(fo.FlashOptimError):
             fo.checkpoint_unpack(kind, blob2, fresh)
+        # resume: the step after unpacking into new buffers is the step the oracle takes from the saved state
+        hp = ADAMW if kind == "adamw" else SGD
+        resumed = [fo.ParamBuffers(s.n, kind) for s in states]
+        assert fo.checkpoint_unpack(kind, blob, resumed) == 4242
+        grads = grads_for(specs, 4243, seed=9)
+        for b, g, sp, st in zip(resumed, grads, specs, states):
+            b.lr, b.weight_decay = hp["lr"], weight_decay_for(sp, hp["wd"])
+            b.grad.copy_(g.cuda())
+            _oracle_step(kind, st, _g_bits(g), hp["lr"], weight_decay_for(sp, hp["wd"]), hp, 4243)
+        _gpu_step(kind, fo.TensorList(resumed), hp, 4243)
+        for b, st in zip(resumed, states):
+            rep = compare_state(download(b), st, where="resume")
+            assert sum(r[1] for r in rep) == 0
 
 
 def test_hyperparameters_and_gradient_buffers_may_change_between_steps():
