@@ -1528,9 +1528,9 @@ hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs
 // ------------------------------------------------------------------ self-test --
 //
 // The step kernels replace some exactly rounded operations by shorter sequences that give
-// the same bits provided the hardware behaves as documented (v_rcp_f32 and v_sqrt_f32 within
-// 1 ulp).  This kernel checks those provisions on the device it runs on, against the plain
-// IEEE operations:
+// the same bits provided the hardware estimates behave as documented (v_rcp_f32 within 1 ulp) or,
+// for the square root built on v_rsq_f32, as verified here value by value.  This kernel checks
+// those provisions on the device it runs on, against the plain IEEE operations:
 //   section 0: recip_of_fp16(s) == 1.0f / s for every positive finite FP16 value s;
 //   section 1: v_rcp_f32(d) within 1 ulp of 1.0f / d for every d in [1, 4);
 //   section 2: sqrt_rn_midrange(x) == sqrtf(x) for EVERY FP32 value x of its range [2^-96, FLT_MAX];
