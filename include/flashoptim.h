@@ -285,6 +285,15 @@ int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream);
  * counts (HOST, 2 entries) = {operand pairs checked (2^30 + 2^24), of these not exact}.  Waits for
  * completion.  FLASHOPTIM_ERR_SELFTEST if any quotient is off by more than one ulp. */
 int flashoptim_faithful_rounding_stats(int64_t* counts, void* stream);
+/* The AdamW kernels take sqrt(v_hat) as the hardware reciprocal-square-root estimate plus one correction,
+ * which is the correctly rounded root only if the estimate makes it so.  The library therefore checks every
+ * FP32 value of that sequence's range, [2^-96, FLT_MAX], against sqrtf on the device before the first AdamW
+ * step there (once per process and device: a kernel of about 2 ms and a wait on the caller's stream, so that
+ * first call must not be made under stream capture), and uses sqrtf in the kernels if the check fails or if
+ * FLASHOPTIM_FORCE_GENERAL_SQRT is set to a non-zero value in the environment.  Returns the state for the
+ * current device: 0 not checked yet, 1 verified (short sequence in use), 2 not in use; negative status on
+ * a HIP error. */
+int flashoptim_short_sqrt_state(void);
 /* Number of kernel launches one step call of `kind` issues for a list with these element counts
  * (host arithmetic only; for reading profiles: per-kernel durations are per launch).  Negative
  * status on invalid arguments. */

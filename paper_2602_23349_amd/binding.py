@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "flashoptim_quantize_variance", "flashoptim_dequantize_variance",
     "flashoptim_checkpoint_size", "flashoptim_checkpoint_pack", "flashoptim_checkpoint_unpack",
     "flashoptim_strerror", "flashoptim_last_hip_error", "flashoptim_release_cache", "flashoptim_version",
-    "flashoptim_faithful_rounding_stats",
+    "flashoptim_faithful_rounding_stats", "flashoptim_short_sqrt_state",
     "flashoptim_step_launch_count",
     "flashoptim_selftest", "flashoptim_split_weights_i16", "flashoptim_reconstruct_weights_i16",
     "flashoptim_reconstruction_sweep", "flashoptim_reconstruction_sweep_ex",
@@ -387,6 +387,11 @@ def faithful_rounding_stats(stream=None):
     counts = (C.c_int64 * 2)()
     _check(load_library().flashoptim_faithful_rounding_stats(counts, _stream(stream)), "flashoptim_faithful_rounding_stats")
     return tuple(counts)
+
+
+def short_sqrt_state():
+    """0 not checked yet, 1 verified on this device, 2 not in use (check failed or switched off by the environment)."""
+    return int(load_library().flashoptim_short_sqrt_state())
 
 
 def selftest(stream=None):

@@ -7,7 +7,9 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
+#include <cstdlib>
 #include <cstdint>
 #include <cstring>
 #include <list>
@@ -317,6 +319,53 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
     return FLASHOPTIM_OK;
 }
 
+// The short square root of the AdamW kernels (reciprocal-square-root estimate plus one correction) is
+// exactly rounded on a device only if the hardware estimate makes it so; that is checked for every value of
+// its range once per process and device, before the first AdamW step there (a ~2 ms kernel and a wait on
+// the stream).  If the check fails, or FLASHOPTIM_FORCE_GENERAL_SQRT is set in the environment (for testing
+// that path), the kernels use sqrtf throughout.
+constexpr int kMaxDevices = 64;
+std::atomic<int> g_sqrt_state[kMaxDevices];      // 0 not checked, 1 verified, 2 not to be used
+std::mutex g_sqrt_mu;
+
+int short_sqrt_verified(hipStream_t stream, bool* verified) {
+    *verified = false;
+    int dev = 0;
+    FO_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return FLASHOPTIM_OK;
+    int st = g_sqrt_state[dev].load(std::memory_order_acquire);
+    if (st == 0) {
+        std::lock_guard<std::mutex> lock(g_sqrt_mu);
+        st = g_sqrt_state[dev].load(std::memory_order_acquire);
+        if (st == 0) {
+            const char* force = std::getenv("FLASHOPTIM_FORCE_GENERAL_SQRT");
+            if (force && force[0] != '\0' && force[0] != '0') {
+                st = 2;
+            } else {
+                unsigned long long h[2] = {0, 0};
+                unsigned long long* d = nullptr;
+                FO_HIP(hipMalloc((void**)&d, fo::kSelftestCounters * sizeof(unsigned long long)));
+                hipError_t e = hipMemsetAsync(d, 0, fo::kSelftestCounters * sizeof(unsigned long long), stream);
+                StepConsts c0;
+                std::memset(&c0, 0, sizeof(c0));
+                if (e == hipSuccess) e = fo::launch_selftest(d, 2, c0, 1.0f, stream);
+                if (e == hipSuccess) e = hipMemcpyAsync(h, d + 4, sizeof(h), hipMemcpyDeviceToHost, stream);
+                if (e == hipSuccess) e = hipStreamSynchronize(stream);
+                (void)hipFree(d);
+                if (e != hipSuccess) {
+                    g_last_hip_error = (int)e;
+                    (void)hipGetLastError();
+                    return FLASHOPTIM_ERR_HIP;
+                }
+                st = (h[0] == fo::kSelftestSqrtValues && h[1] == 0) ? 1 : 2;
+            }
+            g_sqrt_state[dev].store(st, std::memory_order_release);
+        }
+    }
+    *verified = (st == 1);
+    return FLASHOPTIM_OK;
+}
+
 int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, const StepConsts& c, void* stream_,
              LiveOp op = kOpStep) {
     const bool has_v = (kind == FLASHOPTIM_ADAMW);
@@ -331,7 +380,14 @@ int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, cons
     live.reserve((size_t)n_tensors);
     for (int64_t i = 0; i < n_tensors; ++i)
         if (tensors[i].numel > 0) live.push_back(to_dev(tensors[i], has_v));
-    return launch_live(kind, true, true, live, c, static_cast<hipStream_t>(stream_), op);
+    StepConsts cc = c;
+    if (has_v && op != kOpProbe && !live.empty()) {
+        bool verified = false;
+        rc = short_sqrt_verified(static_cast<hipStream_t>(stream_), &verified);
+        if (rc != FLASHOPTIM_OK) return rc;
+        cc.general_sqrt = verified ? 0 : 1;
+    }
+    return launch_live(kind, true, true, live, cc, static_cast<hipStream_t>(stream_), op);
 }
 
 // Conversion between the FP32 state and the compressed layout: every buffer of both layouts is needed.
@@ -370,8 +426,15 @@ int run_step_ex(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors
     std::vector<TensorDev> live;
     int rc = to_dev_ex(tensors, n_tensors, kind == FLASHOPTIM_ADAMW, split, quant, live);
     if (rc != FLASHOPTIM_OK) return rc;
+    StepConsts cc = c;
+    if (kind == FLASHOPTIM_ADAMW && !live.empty()) {
+        bool verified = false;
+        rc = short_sqrt_verified(static_cast<hipStream_t>(stream_), &verified);
+        if (rc != FLASHOPTIM_OK) return rc;
+        cc.general_sqrt = verified ? 0 : 1;
+    }
     // the ablation and reference variants always use the exactly rounded arithmetic
-    return launch_live(kind, split, quant, live, c, static_cast<hipStream_t>(stream_), kOpStepExact);
+    return launch_live(kind, split, quant, live, cc, static_cast<hipStream_t>(stream_), kOpStepExact);
 }
 
 // 1 / (float)(1 - beta^t): the bias correction is formed in double and rounded to FP32
@@ -821,6 +884,13 @@ int flashoptim_faithful_rounding_stats(int64_t* counts, void* stream) {
     if (rc != FLASHOPTIM_OK) return rc;
     counts[0] = (int64_t)h[12]; counts[1] = (int64_t)h[14];     // operand pairs, quotients that are not the exactly rounded one
     return h[13] == 0 ? FLASHOPTIM_OK : FLASHOPTIM_ERR_SELFTEST;
+}
+
+int flashoptim_short_sqrt_state(void) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return FLASHOPTIM_ERR_HIP; }
+    if (dev < 0 || dev >= kMaxDevices) return 2;
+    return g_sqrt_state[dev].load(std::memory_order_acquire);
 }
 
 const char* flashoptim_strerror(int status) {

@@ -58,6 +58,7 @@ struct StepConsts {
     float rbc1, rbc2;     // 1.0f / (float)(1 - beta^t), AdamW only
     float eps;
     float root_bc2;       // (float)sqrt(1 / (double)rbc2): used only to pre-estimate variance codes
+    int32_t general_sqrt; // non-zero: the short square root has not passed its check on this device: use sqrtf
 };
 
 // A multi-tensor launch maps workgroup b to (tensor, tile) in two steps: coarse[b >> coarse_shift] is
@@ -108,6 +109,7 @@ void launch_dequantize(bool variance, bool linear, const void* q, const uint16_t
 void launch_nmse(bool variance, bool linear, const float* x, int64_t n, double* sums, hipStream_t s);
 void launch_copy(const CopySegment* segs, const uint2* chunks, int64_t n_chunks, hipStream_t s);
 constexpr int kSelftestSectionCount = 7;
+constexpr unsigned long long kSelftestSqrtValues = 0x7f800000ull - 0x0f800000ull;   // section 2: every FP32 value in [2^-96, FLT_MAX]
 constexpr int kSelftestCounters = 15;   // two per section, then the inexact count of section 6
 hipError_t launch_selftest(unsigned long long* counters, int section, const StepConsts& c, float scale_r,
                            hipStream_t s);

@@ -154,7 +154,9 @@ __device__ __forceinline__ uint32_t group_scale_fast(float absmax, float* r) {
 // Correctly rounded square root for 2^-96 <= x <= FLT_MAX: the hardware reciprocal-square-root
 // estimate (1 ulp) and one Newton correction, each step one FMA.  That this sequence returns the
 // correctly rounded root for EVERY FP32 value of that range is a property of the hardware estimate
-// which flashoptim_selftest verifies exhaustively on the device (all 1,879,048,192 values).  Below
+// which is verified exhaustively on the device (all 1,879,048,192 values): by the host before the first
+// AdamW step on a device (StepConsts::general_sqrt switches the kernels to sqrtf otherwise) and by
+// flashoptim_selftest.  Below
 // 2^-96 the residual x - s*s leaves the normal range and the result is only within one ulp; zero,
 // infinity and NaN give NaN.  Callers check the range and use sqrtf() otherwise.
 constexpr float kSqrtFastMin = 1.2621774483536189e-29f;   // 2^-96
@@ -730,7 +732,7 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
         const float nmin = amin_m * c.rbc1, nmax = amax_m * c.rbc1;
         // sqrt(v_hat): the short sequence unless some lane holds a value outside its range (below
         // 2^-96 - exact zeros included - or not finite)
-        const bool sqrt_general = any_lane(!sqrt_range_ok(vmin, vmax));
+        const bool sqrt_general = c.general_sqrt != 0 || any_lane(!sqrt_range_ok(vmin, vmax));
         // m_hat / (sqrt(v_hat) + eps): the short division when every operand of the lane is well
         // inside the normal range (eps <= den <= sqrt(v_hat max) + eps), else the general one
         // (the faithful division has no lower limit on the numerator)
@@ -786,12 +788,14 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
     y.ms = group_scale_fast(amax_m, &r_m);
     if (HAS_V) {
         amax_v = group_max<VEC>(amax_v);
-        const float root_max = any_lane(!sqrt_range_ok(amax_v, amax_v)) ? sqrtf(amax_v) : sqrt_rn_midrange(amax_v);
+        const float root_max = (c.general_sqrt != 0 || any_lane(!sqrt_range_ok(amax_v, amax_v))) ? sqrtf(amax_v)
+                                                                                             : sqrt_rn_midrange(amax_v);
         y.vs = group_scale_fast(root_max, &r_v);
         kr255 = (c.root_bc2 * r_v) * 255.0f;
     }
 
-    const bool vt_root_general = HAS_V && any_lane(!sqrt_range_ok(amin_v, amax_v));   // amax_v: the group's, at least the lane's
+    // amax_v is the group's here, which is at least the lane's
+    const bool vt_root_general = HAS_V && (c.general_sqrt != 0 || any_lane(!sqrt_range_ok(amin_v, amax_v)));
     // epilogue: state codes, four at a time; exact recomputation only near rounding ties
 #pragma unroll
     for (int j = 0; j < VEC / 4; ++j) {
@@ -1546,7 +1550,7 @@ hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs
 // counters[2 * section] counts checks, counters[2 * section + 1] failures.
 
 constexpr int kSelftestSections = 7;
-constexpr uint64_t kSelftestSqrtCount = 0x7f800000ull - 0x0f800000ull;   // every FP32 value in [2^-96, FLT_MAX]
+constexpr uint64_t kSelftestSqrtCount = kSelftestSqrtValues;
 constexpr uint64_t kSelftestDivCount = (1ull << 30) + (1ull << 24);
 
 __device__ __forceinline__ uint32_t selftest_hash(uint64_t x) {

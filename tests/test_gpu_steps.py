@@ -2,6 +2,10 @@
 workloads: flat 2^20 tensor (AdamW, 1 and 100 steps after 10 warm-up steps), the GPT-2 124M
 list (SGD, Lion), the ResNet-50 list (AdamW, heavy-tailed gradients), ragged tensor sizes, and
 hand-built edge cases.  All calls go through the C ABI via the Python binding."""
+import os
+import subprocess
+import sys
+
 import numpy as np
 import pytest
 import torch
@@ -13,6 +17,7 @@ from helpers import (ADAMW_MODES, adamw_step_fn, assert_parity, bits16, compare_
                      to_dev_u16, total_mismatches, upload_state, weight_decay_for)
 
 pytestmark = pytest.mark.gpu
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 ADAMW = dict(lr=1e-3, wd=0.01, beta1=0.9, beta2=0.999, eps=1e-8)
 SGD = dict(lr=1e-2, wd=5e-4, momentum=0.9)
@@ -429,6 +434,30 @@ def test_two_host_threads_step_their_own_lists_at_once():
         for i, s in enumerate(states):
             rep = compare_state(download(bufs[i]), s, where=f"threads {kind} {specs[i].name}")
             assert sum(r[1] for r in rep) == 0
+
+
+def test_short_square_root_is_verified_on_this_device_before_use():
+    # the library checks the short square-root sequence against sqrtf for every value of its range before the
+    # first AdamW step on a device; the environment can tell it not to use the sequence at all
+    b = fo.ParamBuffers(64, "adamw")
+    b.lr = 1e-3
+    fo.adamw_step([b], 0.9, 0.999, 1e-8, 1)
+    torch.cuda.synchronize()
+    forced = os.environ.get("FLASHOPTIM_FORCE_GENERAL_SQRT", "0") not in ("", "0")
+    assert fo.short_sqrt_state() == (2 if forced else 1)
+
+
+def test_adamw_parity_holds_with_the_general_square_root():
+    # the same AdamW parity tests in a child process that tells the library not to trust the short sequence
+    if os.environ.get("FLASHOPTIM_FORCE_GENERAL_SQRT"):
+        pytest.skip("already inside that child process")
+    env = dict(os.environ, FLASHOPTIM_FORCE_GENERAL_SQRT="1")
+    r = subprocess.run([sys.executable, "-u", "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "-m", "gpu",
+                        os.path.join(ROOT, "tests", "test_gpu_steps.py"), "--timeout", "200", "--timeout-method", "thread",
+                        "-k", "short_square_root or flat_tensor or ragged or edge_values or zero_variance or resnet50"],
+                       cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=600)
+    assert r.returncode == 0, r.stdout[-3000:]
+    assert "passed" in r.stdout
 
 
 def test_many_distinct_lists_evict_cached_tables():
