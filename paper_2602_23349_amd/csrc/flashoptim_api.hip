@@ -385,7 +385,7 @@ int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, cons
         bool verified = false;
         rc = short_sqrt_verified(static_cast<hipStream_t>(stream_), &verified);
         if (rc != FLASHOPTIM_OK) return rc;
-        cc.general_sqrt = verified ? 0 : 1;
+        cc.sqrt_min = verified ? 1.2621774483536189e-29f /* 2^-96 */ : INFINITY;
     }
     return launch_live(kind, true, true, live, cc, static_cast<hipStream_t>(stream_), op);
 }
@@ -431,7 +431,7 @@ int run_step_ex(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors
         bool verified = false;
         rc = short_sqrt_verified(static_cast<hipStream_t>(stream_), &verified);
         if (rc != FLASHOPTIM_OK) return rc;
-        cc.general_sqrt = verified ? 0 : 1;
+        cc.sqrt_min = verified ? 1.2621774483536189e-29f /* 2^-96 */ : INFINITY;
     }
     // the ablation and reference variants always use the exactly rounded arithmetic
     return launch_live(kind, split, quant, live, cc, static_cast<hipStream_t>(stream_), kOpStepExact);

@@ -58,7 +58,8 @@ struct StepConsts {
     float rbc1, rbc2;     // 1.0f / (float)(1 - beta^t), AdamW only
     float eps;
     float root_bc2;       // (float)sqrt(1 / (double)rbc2): used only to pre-estimate variance codes
-    int32_t general_sqrt; // non-zero: the short square root has not passed its check on this device: use sqrtf
+    float sqrt_min;       // smallest argument given to the short square root: 2^-96, or +inf when that sequence
+                          // has not passed its check on this device (the kernels then use sqrtf throughout)
 };
 
 // A multi-tensor launch maps workgroup b to (tensor, tile) in two steps: coarse[b >> coarse_shift] is

@@ -155,7 +155,7 @@ __device__ __forceinline__ uint32_t group_scale_fast(float absmax, float* r) {
 // estimate (1 ulp) and one Newton correction, each step one FMA.  That this sequence returns the
 // correctly rounded root for EVERY FP32 value of that range is a property of the hardware estimate
 // which is verified exhaustively on the device (all 1,879,048,192 values): by the host before the first
-// AdamW step on a device (StepConsts::general_sqrt switches the kernels to sqrtf otherwise) and by
+// AdamW step on a device (StepConsts::sqrt_min = +inf switches the kernels to sqrtf otherwise) and by
 // flashoptim_selftest.  Below
 // 2^-96 the residual x - s*s leaves the normal range and the result is only within one ulp; zero,
 // infinity and NaN give NaN.  Callers check the range and use sqrtf() otherwise.
@@ -167,7 +167,10 @@ __device__ __forceinline__ float sqrt_rn_midrange(float x) {
     return fmaf(fmaf(-s, s, x), h, s);
 }
 // True when every value between lo and hi (lo <= hi) is in the range of sqrt_rn_midrange; false for NaN.
-__device__ __forceinline__ bool sqrt_range_ok(float lo, float hi) { return lo >= kSqrtFastMin && hi <= kSqrtFastMax; }
+// lower_limit is kSqrtFastMin, or +inf from the host when the sequence is not to be used on this device.
+__device__ __forceinline__ bool sqrt_range_ok(float lo, float hi, float lower_limit) {
+    return lo >= lower_limit && hi <= kSqrtFastMax;
+}
 
 // Correctly rounded n / d for operands well inside the normal range: 2^-60 <= |n|, d <= 2^60.
 // This is the usual refinement of the 1-ulp hardware reciprocal (one Newton step on the
@@ -732,7 +735,7 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
         const float nmin = amin_m * c.rbc1, nmax = amax_m * c.rbc1;
         // sqrt(v_hat): the short sequence unless some lane holds a value outside its range (below
         // 2^-96 - exact zeros included - or not finite)
-        const bool sqrt_general = c.general_sqrt != 0 || any_lane(!sqrt_range_ok(vmin, vmax));
+        const bool sqrt_general = any_lane(!sqrt_range_ok(vmin, vmax, c.sqrt_min));
         // m_hat / (sqrt(v_hat) + eps): the short division when every operand of the lane is well
         // inside the normal range (eps <= den <= sqrt(v_hat max) + eps), else the general one
         // (the faithful division has no lower limit on the numerator)
@@ -788,14 +791,14 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
     y.ms = group_scale_fast(amax_m, &r_m);
     if (HAS_V) {
         amax_v = group_max<VEC>(amax_v);
-        const float root_max = (c.general_sqrt != 0 || any_lane(!sqrt_range_ok(amax_v, amax_v))) ? sqrtf(amax_v)
-                                                                                             : sqrt_rn_midrange(amax_v);
+        const float root_max = any_lane(!sqrt_range_ok(amax_v, amax_v, c.sqrt_min)) ? sqrtf(amax_v)
+                                                                                     : sqrt_rn_midrange(amax_v);
         y.vs = group_scale_fast(root_max, &r_v);
         kr255 = (c.root_bc2 * r_v) * 255.0f;
     }
 
     // amax_v is the group's here, which is at least the lane's
-    const bool vt_root_general = HAS_V && (c.general_sqrt != 0 || any_lane(!sqrt_range_ok(amin_v, amax_v)));
+    const bool vt_root_general = HAS_V && any_lane(!sqrt_range_ok(amin_v, amax_v, c.sqrt_min));
     // epilogue: state codes, four at a time; exact recomputation only near rounding ties
 #pragma unroll
     for (int j = 0; j < VEC / 4; ++j) {
