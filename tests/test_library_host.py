@@ -24,6 +24,42 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
 
 
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 with warnings as errors, the struct sizes seen
+    # by a C compiler must be the ones the binding assumes, and a C program that takes the address of every
+    # declared function must link against the shared library
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    header = open(os.path.join(ROOT, "include", "flashoptim.h")).read()
+    names = sorted(set(re.findall(r"\b(flashoptim_[a-z0-9_]+)\s*\(", re.sub(r"/\*.*?\*/", "", header, flags=re.S))))
+    src = tmp_path / "use_header.c"
+    refs = "\n".join(f"    (void (*)(void))&{n}," for n in names)
+    src.write_text(f"""#include <stdio.h>
+#include "flashoptim.h"
+typedef void (*fn_t)(void);
+static const fn_t all_entry_points[] = {{
+{refs}
+}};
+int main(void) {{
+    printf("%zu %zu %zu %zu %zu\\n", sizeof(flashoptim_tensor), sizeof(flashoptim_tensor_ex), sizeof(flashoptim_adamw_hp),
+           sizeof(all_entry_points) / sizeof(all_entry_points[0]), sizeof(flashoptim_lion_hp));
+    return flashoptim_version() >= 1 ? 0 : 1;
+}}
+""")
+    lib_dir = os.path.join(ROOT, "paper_2602_23349_amd")
+    exe = tmp_path / "use_header"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", lib_dir, "-l:libflashoptim.so", "-Wl,-rpath," + lib_dir,
+                    "-Wl,-rpath-link,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    t, tex, hp, n, lion = (int(x) for x in r.stdout.split())
+    assert t == C.sizeof(B._Tensor) == 72 and hp == C.sizeof(B._AdamWHp) == 24 and n == len(names)
+    assert tex == C.sizeof(B._TensorEx) and lion == 8
+
+
 def test_struct_layout_matches_header():
     # flashoptim_tensor: 7 pointers, int64, 2 floats = 72 bytes on LP64
     assert C.sizeof(B._Tensor) == 72
