@@ -386,6 +386,7 @@ int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, cons
         rc = short_sqrt_verified(static_cast<hipStream_t>(stream_), &verified);
         if (rc != FLASHOPTIM_OK) return rc;
         cc.sqrt_min = verified ? 1.2621774483536189e-29f /* 2^-96 */ : INFINITY;
+        cc.div_max = (cc.eps >= fo::kDivFastLo && cc.eps <= 1.0f) ? fo::kDivFastHi : -1.0f;
     }
     return launch_live(kind, true, true, live, cc, static_cast<hipStream_t>(stream_), op);
 }
@@ -432,6 +433,7 @@ int run_step_ex(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors
         rc = short_sqrt_verified(static_cast<hipStream_t>(stream_), &verified);
         if (rc != FLASHOPTIM_OK) return rc;
         cc.sqrt_min = verified ? 1.2621774483536189e-29f /* 2^-96 */ : INFINITY;
+        cc.div_max = (cc.eps >= fo::kDivFastLo && cc.eps <= 1.0f) ? fo::kDivFastHi : -1.0f;
     }
     // the ablation and reference variants always use the exactly rounded arithmetic
     return launch_live(kind, split, quant, live, cc, static_cast<hipStream_t>(stream_), kOpStepExact);

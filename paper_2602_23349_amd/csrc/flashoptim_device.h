@@ -52,12 +52,18 @@ struct TensorDev {
 };
 
 // Per-call scalars, computed once on the host.
+// Operand range of the short divisions of the AdamW kernels (numerator, denominator and eps inside it).
+constexpr float kDivFastLo = 8.673617379884035e-19f;    // 2^-60
+constexpr float kDivFastHi = 1.152921504606847e18f;     // 2^60
+
 struct StepConsts {
     float beta1, beta2;   // AdamW/Lion betas; SGD: beta1 = momentum
     float omb1, omb2;     // 1.0f - beta (FP32 subtraction)
     float rbc1, rbc2;     // 1.0f / (float)(1 - beta^t), AdamW only
     float eps;
     float root_bc2;       // (float)sqrt(1 / (double)rbc2): used only to pre-estimate variance codes
+    float div_max;        // largest operand given to the short division: 2^60, or -1 when eps is outside [2^-60, 1]
+                          // (the kernels then use the IEEE division throughout)
     float sqrt_min;       // smallest argument given to the short square root: 2^-96, or +inf when that sequence
                           // has not passed its check on this device (the kernels then use sqrtf throughout)
 };

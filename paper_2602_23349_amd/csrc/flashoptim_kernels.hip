@@ -94,14 +94,25 @@ __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 
 // Maximum over the lanes that share a 32-element group: a lane pair (16 elements per lane)
-// or a lane quad (8 per lane), by DPP quad permutes.  Inputs are non-negative.
+// or a lane quad (8 per lane).  Each step is ONE instruction, v_max_f32 with its first operand taken
+// from the neighbouring lane through a DPP quad permute (written as inline assembly: from the
+// builtin the compiler makes a DPP move, two canonicalising maxima and the maximum itself).  The
+// s_nop covers the two wait states a DPP read needs after the instruction that wrote its source.
+// v_max_f32 returns the other operand when one is NaN, like fmaxf.
+__device__ __forceinline__ float max_across_lane_pair(float x) {
+    float r;
+    asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+    return r;
+}
+__device__ __forceinline__ float max_across_pair_of_pairs(float x) {
+    float r;
+    asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+    return r;
+}
 template <int VEC>
 __device__ __forceinline__ float group_max(float x) {
-    x = fmaxf(x, u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), 0xB1 /* quad_perm [1,0,3,2] */,
-                                                           0xf, 0xf, true)));
-    if (VEC == 8)
-        x = fmaxf(x, u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), 0x4E /* quad_perm [2,3,0,1] */,
-                                                               0xf, 0xf, true)));
+    x = max_across_lane_pair(x);
+    if (VEC == 8) x = max_across_pair_of_pairs(x);
     return x;
 }
 
@@ -166,10 +177,13 @@ __device__ __forceinline__ float sqrt_rn_midrange(float x) {
     const float s = x * y, h = 0.5f * y;
     return fmaf(fmaf(-s, s, x), h, s);
 }
-// True when every value between lo and hi (lo <= hi) is in the range of sqrt_rn_midrange; false for NaN.
-// lower_limit is kSqrtFastMin, or +inf from the host when the sequence is not to be used on this device.
-__device__ __forceinline__ bool sqrt_range_ok(float lo, float hi, float lower_limit) {
-    return lo >= lower_limit && hi <= kSqrtFastMax;
+// Wave-uniform range test: true when some lane holds a value between lo and hi (lo <= hi) outside the
+// range of sqrt_rn_midrange, or a NaN.  lower_limit is kSqrtFastMin, or +inf from the host when the
+// sequence is not to be used on this device.  (One ballot per comparison: a ballot of a combined
+// condition costs two more vector instructions.)
+__device__ __forceinline__ bool any_lane(bool p);
+__device__ __forceinline__ bool sqrt_out_of_range(float lo, float hi, float lower_limit) {
+    return any_lane(!(lo >= lower_limit)) | any_lane(!(hi <= kSqrtFastMax));
 }
 
 // Correctly rounded n / d for operands well inside the normal range: 2^-60 <= |n|, d <= 2^60.
@@ -177,8 +191,6 @@ __device__ __forceinline__ bool sqrt_range_ok(float lo, float hi, float lower_li
 // reciprocal, two residual corrections of the quotient, every step one FMA); with the operands
 // in that range no intermediate result leaves the normal range, so the range scaling and the
 // special-case fix-up of the general division are not needed.  Callers check the range.
-constexpr float kDivFastLo = 8.673617379884035e-19f;    // 2^-60
-constexpr float kDivFastHi = 1.152921504606847e18f;     // 2^60
 __device__ __forceinline__ float div_rn_midrange(float n, float d) {
     float r = __builtin_amdgcn_rcpf(d);
     const float e = fmaf(-d, r, 1.0f);
@@ -735,12 +747,13 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
         const float nmin = amin_m * c.rbc1, nmax = amax_m * c.rbc1;
         // sqrt(v_hat): the short sequence unless some lane holds a value outside its range (below
         // 2^-96 - exact zeros included - or not finite)
-        const bool sqrt_general = any_lane(!sqrt_range_ok(vmin, vmax, c.sqrt_min));
+        const bool sqrt_general = sqrt_out_of_range(vmin, vmax, c.sqrt_min);
         // m_hat / (sqrt(v_hat) + eps): the short division when every operand of the lane is well
-        // inside the normal range (eps <= den <= sqrt(v_hat max) + eps), else the general one
-        // (the faithful division has no lower limit on the numerator)
-        const bool div_fast = (c.eps >= kDivFastLo) && (c.eps <= 1.0f) &&
-                              !any_lane(!((!EXACT || nmin >= kDivFastLo) && nmax <= kDivFastHi && vmax <= kDivFastHi));
+        // inside the normal range (eps <= den <= sqrt(v_hat max) + eps), else the general one.
+        // c.div_max is 2^60, or -1 from the host when eps is outside [2^-60, 1]: every test then fails.
+        // (The faithful division has no lower limit on the numerator.)
+        const bool div_fast = !(any_lane(!(nmax <= c.div_max)) | any_lane(!(vmax <= c.div_max)) |
+                                (EXACT ? any_lane(!(nmin >= kDivFastLo)) : false));
 #pragma unroll
         for (int j = 0; j < VEC / 4; ++j) {
             float mh4[4], vh4[4], quo[4], tht[4];
@@ -791,14 +804,13 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
     y.ms = group_scale_fast(amax_m, &r_m);
     if (HAS_V) {
         amax_v = group_max<VEC>(amax_v);
-        const float root_max = any_lane(!sqrt_range_ok(amax_v, amax_v, c.sqrt_min)) ? sqrtf(amax_v)
-                                                                                     : sqrt_rn_midrange(amax_v);
+        const float root_max = sqrt_out_of_range(amax_v, amax_v, c.sqrt_min) ? sqrtf(amax_v) : sqrt_rn_midrange(amax_v);
         y.vs = group_scale_fast(root_max, &r_v);
         kr255 = (c.root_bc2 * r_v) * 255.0f;
     }
 
     // amax_v is the group's here, which is at least the lane's
-    const bool vt_root_general = HAS_V && any_lane(!sqrt_range_ok(amin_v, amax_v, c.sqrt_min));
+    const bool vt_root_general = HAS_V && sqrt_out_of_range(amin_v, amax_v, c.sqrt_min);
     // epilogue: state codes, four at a time; exact recomputation only near rounding ties
 #pragma unroll
     for (int j = 0; j < VEC / 4; ++j) {
