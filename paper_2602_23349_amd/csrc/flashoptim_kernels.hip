@@ -801,16 +801,19 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
     // is monotone, so the group maximum of sqrt(v) is the square root of the maximum of v.
     amax_m = group_max<VEC>(amax_m);
     float r_m, r_v = 0.0f, kr255 = 0.0f;
+    bool amax_v_not_finite = false;     // wave-uniform
     y.ms = group_scale_fast(amax_m, &r_m);
     if (HAS_V) {
         amax_v = group_max<VEC>(amax_v);
-        const float root_max = sqrt_out_of_range(amax_v, amax_v, c.sqrt_min) ? sqrtf(amax_v) : sqrt_rn_midrange(amax_v);
+        amax_v_not_finite = any_lane(!(amax_v <= kSqrtFastMax));
+        const bool root_max_general = any_lane(!(amax_v >= c.sqrt_min)) | amax_v_not_finite;
+        const float root_max = root_max_general ? sqrtf(amax_v) : sqrt_rn_midrange(amax_v);
         y.vs = group_scale_fast(root_max, &r_v);
         kr255 = (c.root_bc2 * r_v) * 255.0f;
     }
 
     // amax_v is the group's here, which is at least the lane's
-    const bool vt_root_general = HAS_V && sqrt_out_of_range(amin_v, amax_v, c.sqrt_min);
+    const bool vt_root_general = HAS_V && (any_lane(!(amin_v >= c.sqrt_min)) | amax_v_not_finite);
     // epilogue: state codes, four at a time; exact recomputation only near rounding ties
 #pragma unroll
     for (int j = 0; j < VEC / 4; ++j) {
