@@ -79,10 +79,13 @@ std::unordered_map<std::string, std::list<std::pair<std::string, Plan>>::iterato
 std::list<std::pair<std::string, Plan>> g_plans;   // most recently used first
 constexpr size_t kMaxPlans = 256;   // least recently used beyond this are freed (after a device synchronisation)
 
+// Frees a plan's device and pinned buffers.  Work that was enqueued with this plan may still read them, so
+// the plan's own device is synchronised first (plans are freed rarely: on eviction and on release_cache).
 void destroy_plan(Plan& p) {
     int cur = 0;
     (void)hipGetDevice(&cur);
     (void)hipSetDevice(p.device);
+    if (p.d_table || p.d_index) (void)hipDeviceSynchronize();
     for (auto& s : p.ring) {
         if (s.done) { if (s.in_flight) (void)hipEventSynchronize(s.done); (void)hipEventDestroy(s.done); }
         if (s.host) (void)hipHostFree(s.host);
@@ -139,8 +142,6 @@ int get_plan(const std::string& key, size_t table_bytes, const void* index, size
     g_plans.emplace_front(key, p);
     g_index[key] = g_plans.begin();
     while (g_plans.size() > kMaxPlans) {
-        // the evicted plan's buffers may still be read by enqueued work: wait for the device
-        (void)hipDeviceSynchronize();
         destroy_plan(g_plans.back().second);
         g_index.erase(g_plans.back().first);
         g_plans.pop_back();
@@ -924,7 +925,6 @@ int64_t flashoptim_step_launch_count(int kind, const int64_t* numels, int64_t n_
 
 int flashoptim_release_cache(void) {
     std::lock_guard<std::mutex> lock(g_mu);
-    if (!g_plans.empty()) (void)hipDeviceSynchronize();
     for (auto& kv : g_plans) destroy_plan(kv.second);
     g_plans.clear();
     g_index.clear();
