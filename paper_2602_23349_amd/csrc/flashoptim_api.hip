@@ -220,8 +220,8 @@ int to_dev_ex(const flashoptim_tensor_ex* t, int64_t n, bool has_v, bool split, 
     return FLASHOPTIM_OK;
 }
 
-// What a multi-tensor launch runs: an optimizer step (kOpStepExact: with the exactly rounded square root
-// and division of the AdamW update), a layout conversion, or the stream probe.
+// What a multi-tensor launch runs: an optimizer step (kOpStepExact: with the exactly rounded division of
+// the AdamW update), a layout conversion, or the stream probe.
 enum LiveOp { kOpStep = 0, kOpCompress = 1, kOpDecompress = 2, kOpProbe = 3, kOpStepExact = 4 };
 
 hipError_t launch_segment(LiveOp op, int kind, bool direct, bool split, bool quant, const StepArgs& a, int64_t blocks,

@@ -662,9 +662,9 @@ __device__ __forceinline__ void split_block(LaneIO<VEC>& y, const DecodeTables& 
 // group (lane ^ 1, and lane ^ 2, lane ^ 3 when VEC == 8) must execute this function with it.
 // SPLIT / QUANT: the paper's ablations (Section 4.3).  SPLIT = false keeps the master weight in
 // FP32 (x.th32 -> y.th32); QUANT = false keeps the states in FP32 (x.m32, x.v32 -> y.m32, y.v32).
-// EXACT (AdamW only): sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps) are the correctly rounded results for
-// every input; otherwise they are the faithful forms above.  Everything else, the state codes and
-// scales included, is exact in both modes.
+// EXACT (AdamW only): the quotient m_hat / (sqrt(v_hat) + eps) is the correctly rounded one for every
+// input; otherwise it is the faithful form above.  Everything else, the square root, the state codes and
+// the scales included, is exact in both modes.
 template <int KIND, int VEC, bool SPLIT, bool QUANT, bool EXACT>
 __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y, const DecodeTables& tab,
                                             const StepConsts& c, float lr, float wd) {
