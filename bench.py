@@ -179,22 +179,6 @@ def cpu_baseline(W, specs, kind, hp, dist, scale, seed, target_seconds):
             "single_thread_value": n / single}
 
 
-ALU_PEAK_SLOTS = 256 * 4 * 16 * 2.4e9   # CUs x SIMDs x lanes per cycle x peak clock: non-packed vector issue slots / s
-
-
-def read_issue_slots(kind, workload, exact):
-    """Vector-ALU issue slots per step (SQ_ACTIVE_INST_VALU x 64 lanes) of the step kernel, if a counter summary
-    for this workload has been recorded under profiles/ (columns: default entry point, exact entry point)."""
-    path = os.path.join(ROOT, "profiles", f"{kind}_step_{workload}_sq_counters.txt")
-    if not os.path.exists(path):
-        return None
-    for ln in open(path):
-        f = ln.split()
-        if f and f[0] == "SQ_ACTIVE_INST_VALU":
-            return 64.0 * float(f[2 if exact else 1])
-    return None
-
-
 def read_traffic(kind, workload):
     """HBM bytes per step (all kernel launches of one call) measured with rocprofv3 --pmc (FETCH_SIZE,
     WRITE_SIZE), if a summary for this workload has been recorded under profiles/."""
@@ -337,13 +321,6 @@ def main():
         eg = algo_bytes / (ems * 1e-3) / 1e9
         exact_line = {"entry_point": "flashoptim_adamw_step_exact", "ms_per_step": ems, "achieved": eg,
                       "frac": eg / HBM_PEAK_GBPS}
-    # second roof of the same kernel: vector-instruction issue (counter summary under profiles/)
-    alu = None
-    slots = read_issue_slots(kind, args.workload, exact) if (args.variant == "flash" and args.mode == "fused") else None
-    if slots:
-        alu = {"bound": "alu", "unit": "lane issue slots/s", "issue_slots_per_param": slots / n_params,
-               "achieved": slots / (ms_per_step * 1e-3), "peak": ALU_PEAK_SLOTS,
-               "frac": slots / (ms_per_step * 1e-3) / ALU_PEAK_SLOTS}
     out = {
         "metric": "optimizer_step_params_per_sec", "value": value, "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -369,8 +346,7 @@ def main():
                      "bytes_per_param": bytes_per_param,
                      "same_traffic_without_arithmetic": probe,
                      "frac_of_that": (achieved / probe) if probe else None,
-                     "bit_exact_entry_point": exact_line,
-                     "vector_issue": alu},
+                     "bit_exact_entry_point": exact_line},
     }
     if not args.no_cpu_baseline and not ckpt and args.variant == "flash":
         del bufs, tl

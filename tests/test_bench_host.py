@@ -36,11 +36,7 @@ def test_counter_summaries_under_profiles_parse():
     for kind in ("sgd", "lion"):
         t = bench.read_traffic(kind, f"llama31_8b_{kind}")
         assert t is not None and 0.98 < t / (10.125 * n) < 1.05
-    d = bench.read_issue_slots("adamw", "llama31_8b_adamw", exact=False)
-    e = bench.read_issue_slots("adamw", "llama31_8b_adamw", exact=True)
-    assert 60 < d / n < e / n < 100
     assert bench.read_traffic("adamw", "no_such_workload") is None
-    assert bench.read_issue_slots("sgd", "llama31_8b_sgd", exact=False) is None
 
 
 @pytest.mark.skipif(os.path.exists("/dev/kfd"), reason="a GPU is present")
