@@ -305,6 +305,30 @@ def main():
         p1.record(stream)
         torch.cuda.synchronize()
         probe = algo_bytes / (p0.elapsed_time(p1) / args.steps * 1e-3) / 1e9
+    # the clock the compute units run at during the step and during the probe (the step kernels run under the
+    # package power limit): a one-wavefront monitor on a stream of its own samples it while K more steps run
+    clocks = None
+    if args.variant == "flash" and args.mode == "fused" and not args.no_probe:
+        import numpy as np
+
+        def clock_during(fn, approx_ms):
+            mon = fo.ClockMonitor(n_samples=max(8, int(0.6 * args.steps * approx_ms)), seconds_per_sample=1e-3)
+            mon.start()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return float(np.median(mon.ghz()))
+
+        def one_more_step():
+            nonlocal t
+            t += 1
+            do_step(t)
+
+        idle = fo.ClockMonitor(n_samples=8, seconds_per_sample=1e-3)
+        idle.start()
+        clocks = {"idle": float(np.median(idle.ghz())),
+                  "step": clock_during(one_more_step, ms_per_step),
+                  "same_traffic_without_arithmetic": clock_during(lambda: fo.stream_probe(kind, tl), ms_per_step)}
     # the bit-exact AdamW entry point beside the default one, same list, same number of steps
     exact_line = None
     if kind == "adamw" and args.variant == "flash" and args.mode == "fused" and not exact and not args.no_probe:
@@ -346,7 +370,8 @@ def main():
                      "bytes_per_param": bytes_per_param,
                      "same_traffic_without_arithmetic": probe,
                      "frac_of_that": (achieved / probe) if probe else None,
-                     "bit_exact_entry_point": exact_line},
+                     "bit_exact_entry_point": exact_line,
+                     "shader_clock_ghz": clocks},
     }
     if not args.no_cpu_baseline and not ckpt and args.variant == "flash":
         del bufs, tl

@@ -294,6 +294,16 @@ int flashoptim_faithful_rounding_stats(int64_t* counts, void* stream);
  * current device: 0 not checked yet, 1 verified (short sequence in use), 2 not in use; negative status on
  * a HIP error. */
 int flashoptim_short_sqrt_state(void);
+/* A measurement aid: samples the clock the compute units run at while other kernels execute (a step kernel
+ * under the package power limit runs well below the nominal clock).  Enqueues a one-wavefront kernel on
+ * `stream` (use a stream of its own, next to the work to be observed) that takes n_samples samples of
+ * seconds_per_sample each and then ends; it writes 2 * n_samples uint64 values to `samples` (DEVICE memory,
+ * owned by the caller, valid until the kernel has finished): for each sample the ticks of the fixed-frequency
+ * counter that went by and the shader-clock cycles in the same interval.  *tick_hz (HOST) receives the tick
+ * rate, so that clock = cycles / ticks * tick_hz.  1 <= n_samples <= 100000, 0 < seconds_per_sample <= 1.
+ * Does not wait for completion. */
+int flashoptim_clock_monitor(uint64_t* samples, int64_t n_samples, double seconds_per_sample, double* tick_hz,
+                             void* stream);
 /* Number of kernel launches one step call of `kind` issues for a list with these element counts
  * (host arithmetic only; for reading profiles: per-kernel durations are per launch).  Negative
  * status on invalid arguments. */

@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     quantize_momentum, dequantize_momentum, quantize_variance, dequantize_variance,
     quantize_state, dequantize_state, quantization_nmse, compress_state, decompress_state, stream_probe, step_launch_count,
     checkpoint_size, checkpoint_pack, checkpoint_unpack,
-    strerror, release_cache, version, selftest, faithful_rounding_stats, short_sqrt_state, EXPORTED_SYMBOLS, KIND,
+    strerror, release_cache, version, selftest, faithful_rounding_stats, short_sqrt_state, ClockMonitor, EXPORTED_SYMBOLS, KIND,
 )

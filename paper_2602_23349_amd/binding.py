@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "flashoptim_quantize_variance", "flashoptim_dequantize_variance",
     "flashoptim_checkpoint_size", "flashoptim_checkpoint_pack", "flashoptim_checkpoint_unpack",
     "flashoptim_strerror", "flashoptim_last_hip_error", "flashoptim_release_cache", "flashoptim_version",
-    "flashoptim_faithful_rounding_stats", "flashoptim_short_sqrt_state",
+    "flashoptim_faithful_rounding_stats", "flashoptim_short_sqrt_state", "flashoptim_clock_monitor",
     "flashoptim_step_launch_count",
     "flashoptim_selftest", "flashoptim_split_weights_i16", "flashoptim_reconstruct_weights_i16",
     "flashoptim_reconstruction_sweep", "flashoptim_reconstruction_sweep_ex",
@@ -105,6 +105,7 @@ def load_library():
     L.flashoptim_checkpoint_unpack.argtypes = [i32, vp, i64, C.POINTER(_Tensor), i64, C.POINTER(i64), vp]
     L.flashoptim_selftest.argtypes = [C.POINTER(i64), C.POINTER(i64), vp]
     L.flashoptim_faithful_rounding_stats.argtypes = [C.POINTER(i64), vp]
+    L.flashoptim_clock_monitor.argtypes = [C.POINTER(C.c_uint64), i64, C.c_double, C.POINTER(C.c_double), vp]
     L.flashoptim_strerror.argtypes = [i32]
     L.flashoptim_strerror.restype = C.c_char_p
     for name in EXPORTED_SYMBOLS:
@@ -387,6 +388,30 @@ def faithful_rounding_stats(stream=None):
     counts = (C.c_int64 * 2)()
     _check(load_library().flashoptim_faithful_rounding_stats(counts, _stream(stream)), "flashoptim_faithful_rounding_stats")
     return tuple(counts)
+
+
+class ClockMonitor:
+    """Samples the shader clock on a stream of its own while other work runs: start(), run the work, then
+    ghz() waits for the monitor and returns one value per sample (numpy array)."""
+
+    def __init__(self, n_samples=200, seconds_per_sample=1e-3, device="cuda"):
+        self.n, self.dt = int(n_samples), float(seconds_per_sample)
+        self.samples = torch.zeros(2 * self.n, dtype=torch.int64, device=device)
+        self.stream = torch.cuda.Stream(device=device)
+        self.tick_hz = C.c_double(0.0)
+
+    def start(self):
+        self.samples.zero_()
+        torch.cuda.current_stream().synchronize()
+        self.stream.wait_stream(torch.cuda.current_stream())
+        _check(load_library().flashoptim_clock_monitor(C.cast(self.samples.data_ptr(), C.POINTER(C.c_uint64)), self.n,
+                                                       self.dt, C.byref(self.tick_hz), _stream(self.stream)),
+               "flashoptim_clock_monitor")
+
+    def ghz(self):
+        self.stream.synchronize()
+        o = self.samples.cpu().numpy().reshape(self.n, 2).astype("float64")
+        return o[:, 1] / o[:, 0] * self.tick_hz.value / 1e9
 
 
 def short_sqrt_state():

@@ -889,6 +889,22 @@ int flashoptim_faithful_rounding_stats(int64_t* counts, void* stream) {
     return h[13] == 0 ? FLASHOPTIM_OK : FLASHOPTIM_ERR_SELFTEST;
 }
 
+int flashoptim_clock_monitor(uint64_t* samples, int64_t n_samples, double seconds_per_sample, double* tick_hz,
+                             void* stream) {
+    if (!samples || n_samples < 1 || n_samples > 100000 || !(seconds_per_sample > 0.0) || seconds_per_sample > 1.0 ||
+        !tick_hz)
+        return FLASHOPTIM_ERR_INVALID_ARG;
+    int dev = 0, khz = 0;
+    FO_HIP(hipGetDevice(&dev));
+    FO_HIP(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    if (khz <= 0) return FLASHOPTIM_ERR_HIP;
+    *tick_hz = 1e3 * (double)khz;
+    const unsigned long long ticks = (unsigned long long)(seconds_per_sample * *tick_hz);
+    FO_HIP(fo::launch_clock_monitor(reinterpret_cast<unsigned long long*>(samples), (int)n_samples, ticks ? ticks : 1,
+                                    static_cast<hipStream_t>(stream)));
+    return FLASHOPTIM_OK;
+}
+
 int flashoptim_short_sqrt_state(void) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return FLASHOPTIM_ERR_HIP; }

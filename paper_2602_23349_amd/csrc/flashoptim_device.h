@@ -108,6 +108,8 @@ hipError_t launch_probe(int kind, bool direct, const StepArgs& a, int64_t n_bloc
 void launch_split(int bits, const float* theta, void* param, void* rho, int64_t n, hipStream_t s);
 void launch_reconstruct(int bits, const void* param, const void* rho, float* theta, int64_t n, hipStream_t s);
 constexpr int kSweepStats = 8 + 3 * 256;
+hipError_t launch_clock_monitor(unsigned long long* samples, int n_samples, unsigned long long ticks_per_sample,
+                                hipStream_t s);
 hipError_t launch_sweep(int bits, bool directional, uint64_t first, uint64_t stride, uint64_t count, double* stats,
                         hipStream_t s);
 void launch_quantize(bool variance, bool linear, const float* x, void* q, uint16_t* scale, int64_t n, hipStream_t s);

@@ -993,6 +993,31 @@ hipError_t launch_probe(int kind, bool direct, const StepArgs& a, int64_t n_bloc
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------ clock monitor --
+//
+// A measurement aid: ONE lane samples the shader clock while other kernels run.  Each sample spans
+// ticks_per_sample ticks of the fixed-frequency counter (wall_clock64) and stores how many ticks and how many
+// shader-clock cycles (clock64) went by; cycles / ticks x tick rate is the clock the compute units ran at
+// in that interval.  The wait is bounded, so the kernel ends by itself after n_samples samples at the latest.
+__global__ __launch_bounds__(64) void clock_monitor_kernel(unsigned long long* samples, int n_samples,
+                                                           unsigned long long ticks_per_sample) {
+    if (threadIdx.x != 0) return;
+    for (int s = 0; s < n_samples; ++s) {
+        const unsigned long long r0 = wall_clock64(), c0 = clock64();
+        for (int it = 0; it < (1 << 22); ++it) {
+            if (wall_clock64() - r0 >= ticks_per_sample) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        samples[2 * s] = wall_clock64() - r0;
+        samples[2 * s + 1] = clock64() - c0;
+    }
+}
+hipError_t launch_clock_monitor(unsigned long long* samples, int n_samples, unsigned long long ticks_per_sample,
+                                hipStream_t s) {
+    hipLaunchKernelGGL(clock_monitor_kernel, dim3(1), dim3(64), 0, s, samples, n_samples, ticks_per_sample);
+    return hipGetLastError();
+}
+
 // -------------------------------------------------------- standalone codecs --
 //
 // Not on the per-step path (used at initialisation, for inspection and by tests).  They share

@@ -460,6 +460,16 @@ def test_adamw_parity_holds_with_the_general_square_root():
     assert "passed" in r.stdout
 
 
+def test_clock_monitor_reports_a_plausible_shader_clock():
+    # the measurement aid: a one-wavefront kernel on its own stream that samples cycles per fixed-rate tick
+    mon = fo.ClockMonitor(n_samples=20, seconds_per_sample=5e-4)
+    mon.start()
+    ghz = mon.ghz()
+    assert ghz.shape == (20,) and (ghz > 0.3).all() and (ghz < 3.5).all()
+    L = fo.load_library()
+    assert L.flashoptim_clock_monitor(None, 4, 1e-3, None, None) == -1
+
+
 def test_many_distinct_lists_evict_cached_tables():
     # more distinct lists than the library keeps cached tables for; every call must still be right
     spec = W.ParamSpec("w", (3000,), "matrix")
