@@ -128,6 +128,19 @@ int flashoptim_sgd_step(const flashoptim_tensor* tensors, int64_t n_tensors,
 int flashoptim_lion_step(const flashoptim_tensor* tensors, int64_t n_tensors,
                          const flashoptim_lion_hp* hp, void* stream);
 
+/* ---- sharding a flat tensor over ranks (Section 3.4, "Distributed training") ----------------
+ * With ZeRO / FSDP-style sharding each rank owns a contiguous piece of every flattened tensor, keeps rho, the
+ * state codes and their scales for that piece only, and steps it with the calls above; nothing but the BF16
+ * weights is exchanged.  Quantisation groups must not straddle ranks, and every stream of a shard (the
+ * 2-byte-per-group scales included) must start 16-byte aligned: this call cuts [0, numel) into `world`
+ * consecutive shards on multiples of 256 elements, as evenly as that allows (sizes differ by at most 256; only
+ * the last non-empty shard can be ragged; with fewer than `world` units the trailing ranks get len 0).
+ * *begin, *len (HOST): the element range of `rank`.  A shard's descriptor is the tensor's descriptor with
+ * param, rho, grad, m_q, v_q advanced by begin elements, m_scale and v_scale by begin / 32, numel = len;
+ * stepping the shards (in one list or in `world` calls) gives the same bits as stepping the whole tensor.
+ * Host arithmetic only. */
+int flashoptim_shard_range(int64_t numel, int64_t world, int64_t rank, int64_t* begin, int64_t* len);
+
 /* ---- ablation and reference variants of the steps (Section 4.3) -----------------------
  * The paper isolates its two techniques: "Weight Split" (split weights, FP32 states) and
  * "Opt. Quant." (FP32 master weights, 8-bit states); with both off the step is the plain FP32

@@ -29,6 +29,7 @@ EXPORTED_SYMBOLS = [
     "flashoptim_adamw_step_ex", "flashoptim_sgd_step_ex", "flashoptim_lion_step_ex",
     "flashoptim_quantize_state", "flashoptim_dequantize_state", "flashoptim_quantization_nmse",
     "flashoptim_compress_state", "flashoptim_decompress_state", "flashoptim_stream_probe",
+    "flashoptim_shard_range",
 ]
 
 
@@ -80,6 +81,8 @@ def load_library():
     L = C.CDLL(_LIB_PATH)
     vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int
     L.flashoptim_adamw_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_AdamWHp), vp]
+    L.flashoptim_adamw_step_exact.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_AdamWHp), vp]
+    L.flashoptim_shard_range.argtypes = [i64, i64, i64, C.POINTER(i64), C.POINTER(i64)]
     L.flashoptim_sgd_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_SgdHp), vp]
     L.flashoptim_lion_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_LionHp), vp]
     L.flashoptim_adamw_step_ex.argtypes = [C.POINTER(_TensorEx), i64, C.POINTER(_AdamWHp), C.c_uint, vp]
@@ -155,6 +158,21 @@ class ParamBuffers:
     @property
     def flags(self):
         return (SPLIT_WEIGHTS if self.split_weights else 0) | (QUANTIZE_STATES if self.quantize_states else 0)
+
+    def shard(self, begin, length):
+        """The same buffers restricted to elements [begin, begin + length): views (pointer offsets), no copy.
+        begin must be a multiple of 256 (see flashoptim_shard_range)."""
+        assert begin % 256 == 0 and 0 <= begin and begin + length <= self.numel
+        out = ParamBuffers.__new__(ParamBuffers)
+        out.numel, out.kind = int(length), self.kind
+        out.split_weights, out.quantize_states = self.split_weights, self.quantize_states
+        el = lambda t: None if t is None else t[begin:begin + length]
+        gr = lambda t: None if t is None else t[begin // 32:begin // 32 + (length + 31) // 32]
+        out.param, out.rho, out.theta, out.grad = el(self.param), el(self.rho), el(self.theta), el(self.grad)
+        out.m_q, out.v_q, out.m, out.v = el(self.m_q), el(self.v_q), el(self.m), el(self.v)
+        out.m_scale, out.v_scale = gr(self.m_scale), gr(self.v_scale)
+        out.lr, out.weight_decay = self.lr, self.weight_decay
+        return out
 
 
 class TensorList:
@@ -257,6 +275,14 @@ def adamw_step_exact(tensors, beta1, beta2, eps, step, stream=None):
     hp = _AdamWHp(beta1, beta2, eps, int(step))
     _check(load_library().flashoptim_adamw_step_exact(tl.array, tl.n, C.byref(hp), _stream(stream)),
            "flashoptim_adamw_step_exact")
+
+
+def shard_range(numel, world, rank):
+    """(begin, len) of `rank`'s shard of a flat tensor cut on multiples of 256 elements."""
+    begin, length = C.c_int64(0), C.c_int64(0)
+    _check(load_library().flashoptim_shard_range(int(numel), int(world), int(rank), C.byref(begin), C.byref(length)),
+           "flashoptim_shard_range")
+    return int(begin.value), int(length.value)
 
 
 def sgd_step(tensors, momentum, stream=None):

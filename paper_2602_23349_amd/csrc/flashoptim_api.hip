@@ -68,6 +68,7 @@ struct Plan {
     void* d_table = nullptr;       // TensorDev[] or CopySegment[]
     size_t table_bytes = 0;
     void* d_index = nullptr;       // uint32 coarse table (steps, conversions) or uint2 chunk table (copies)
+    void* h_index = nullptr;       // pinned source of the index table's one upload (kept until the plan is freed)
     int64_t n_chunks = 0;          // workgroups of a launch over this plan
     std::string uploaded;          // bytes of the table the device currently holds
     Staging ring[4];
@@ -93,12 +94,15 @@ void destroy_plan(Plan& p) {
     }
     if (p.d_table) (void)hipFree(p.d_table);
     if (p.d_index) (void)hipFree(p.d_index);
-    p.d_table = nullptr; p.d_index = nullptr;
+    if (p.h_index) (void)hipHostFree(p.h_index);
+    p.d_table = nullptr; p.d_index = nullptr; p.h_index = nullptr;
     (void)hipSetDevice(cur);
 }
 
-// Puts `bytes` of `src` into p.d_table in stream order, via a pinned ring slot.
-int upload_table(Plan& p, const void* src, size_t bytes, hipStream_t stream) {
+// Puts `bytes` of `src` (host memory that the caller may reuse at once) into device memory `dst` in stream
+// order, via one of the plan's pinned ring slots.  Never waits for the stream: a slot is waited for only
+// when its own copy of four uploads ago is still in flight.
+int stage_and_copy(Plan& p, void* dst, const void* src, size_t bytes, hipStream_t stream) {
     Staging& s = p.ring[p.next_slot];
     p.next_slot = (p.next_slot + 1) % 4;
     if (s.in_flight) { FO_HIP(hipEventSynchronize(s.done)); s.in_flight = false; }
@@ -109,16 +113,25 @@ int upload_table(Plan& p, const void* src, size_t bytes, hipStream_t stream) {
     }
     if (!s.done) FO_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
     std::memcpy(s.host, src, bytes);
-    FO_HIP(hipMemcpyAsync(p.d_table, s.host, bytes, hipMemcpyHostToDevice, stream));
+    FO_HIP(hipMemcpyAsync(dst, s.host, bytes, hipMemcpyHostToDevice, stream));
     FO_HIP(hipEventRecord(s.done, stream));
     s.in_flight = true;
-    p.uploaded.assign(static_cast<const char*>(src), bytes);
     return FLASHOPTIM_OK;
 }
 
-// Finds or creates the plan for `key`.  The index table is consumed only on creation.
+// Puts `bytes` of `src` into p.d_table in stream order and remembers what the device now holds.
+int upload_table(Plan& p, const void* src, size_t bytes, hipStream_t stream) {
+    const int rc = stage_and_copy(p, p.d_table, src, bytes, stream);
+    if (rc == FLASHOPTIM_OK) p.uploaded.assign(static_cast<const char*>(src), bytes);
+    return rc;
+}
+
+// Finds or creates the plan for `key`.  The index table is consumed only on creation: it is copied to a
+// pinned buffer of the plan and uploaded in stream order on `stream`, ahead of the launch that the
+// creating call enqueues there (later calls with the same list touch the same tensors, so the caller
+// orders them after this one like any other work on those tensors).  Nothing here waits for the stream.
 int get_plan(const std::string& key, size_t table_bytes, const void* index, size_t index_bytes, int64_t n_chunks,
-             Plan** out) {
+             hipStream_t stream, Plan** out) {
     auto it = g_index.find(key);
     if (it != g_index.end()) {
         g_plans.splice(g_plans.begin(), g_plans, it->second);
@@ -131,8 +144,11 @@ int get_plan(const std::string& key, size_t table_bytes, const void* index, size
     p.n_chunks = n_chunks;
     hipError_t e = hipMalloc(&p.d_table, table_bytes);
     if (e == hipSuccess) e = hipMalloc(&p.d_index, index_bytes);
-    // one-time, blocking upload of the index table (it never changes for this list)
-    if (e == hipSuccess) e = hipMemcpy(p.d_index, index, index_bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipHostMalloc(&p.h_index, index_bytes, hipHostMallocDefault);
+    if (e == hipSuccess) {
+        std::memcpy(p.h_index, index, index_bytes);
+        e = hipMemcpyAsync(p.d_index, p.h_index, index_bytes, hipMemcpyHostToDevice, stream);
+    }
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;
         (void)hipGetLastError();
@@ -304,7 +320,7 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
         }
     }
     int rc = get_plan(key, live.size() * sizeof(TensorDev), coarse.data(), coarse.size() * sizeof(uint32_t),
-                      total_chunks, &plan);
+                      total_chunks, stream, &plan);
     if (rc != FLASHOPTIM_OK) return rc;
 
     const size_t bytes = live.size() * sizeof(TensorDev);
@@ -500,8 +516,10 @@ void build_segments(int kind, const flashoptim_tensor* t, int64_t n, uint8_t* bl
     }
 }
 
-int run_copy(const std::vector<CopySegment>& segs, hipStream_t stream) {
-    if (segs.empty()) return FLASHOPTIM_OK;
+// header (pack only): `header_bytes` of host memory that go to `header_dst` in stream order, ahead of the copy.
+int run_copy(const std::vector<CopySegment>& segs, hipStream_t stream, const void* header = nullptr,
+             size_t header_bytes = 0, void* header_dst = nullptr) {
+    if (segs.empty() && !header) return FLASHOPTIM_OK;
     std::vector<uint2> chunks;
     for (size_t si = 0; si < segs.size(); ++si) {
         const int64_t nc = (segs[si].pad_bytes + fo::kCopyChunkBytes - 1) / fo::kCopyChunkBytes;
@@ -515,9 +533,19 @@ int run_copy(const std::vector<CopySegment>& segs, hipStream_t stream) {
     append(key, segs.data(), segs.size() * sizeof(CopySegment));
     std::lock_guard<std::mutex> lock(g_mu);
     Plan* plan = nullptr;
-    int rc = get_plan(key, segs.size() * sizeof(CopySegment), chunks.data(), chunks.size() * sizeof(uint2),
-                      (int64_t)chunks.size(), &plan);
+    // (a list without any element still has a header: one dummy entry keeps the allocations non-empty)
+    const uint2 none = make_uint2(0u, 0u);
+    const CopySegment no_seg = {nullptr, nullptr, 0, 0};
+    int rc = get_plan(key, segs.empty() ? sizeof(CopySegment) : segs.size() * sizeof(CopySegment),
+                      chunks.empty() ? &none : chunks.data(), (chunks.empty() ? 1 : chunks.size()) * sizeof(uint2),
+                      (int64_t)chunks.size(), stream, &plan);
     if (rc != FLASHOPTIM_OK) return rc;
+    (void)no_seg;
+    if (header) {
+        rc = stage_and_copy(*plan, header_dst, header, header_bytes, stream);
+        if (rc != FLASHOPTIM_OK) return rc;
+    }
+    if (segs.empty()) return FLASHOPTIM_OK;
     if (plan->uploaded.empty()) {
         rc = upload_table(*plan, segs.data(), segs.size() * sizeof(CopySegment), stream);
         if (rc != FLASHOPTIM_OK) return rc;
@@ -535,6 +563,8 @@ int check_elementwise(const void* a, const void* b, const void* c, int64_t n) {
     if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return FLASHOPTIM_ERR_MISALIGNED;
     return FLASHOPTIM_OK;
 }
+
+constexpr int64_t kShardUnit = 256;     // elements: a shard that starts on a multiple has every stream 16-byte aligned
 
 }  // namespace
 
@@ -799,13 +829,12 @@ int flashoptim_checkpoint_pack(int kind, const flashoptim_tensor* tensors, int64
     if (total < 0) return (int)total;
     if (blob_bytes < total) return FLASHOPTIM_ERR_BAD_BLOB;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
+    // header and table: staged in pinned memory and copied in stream order, like the sections themselves
+    // (the blob may still be in use by earlier work on the stream); the call does not wait
     const std::vector<uint8_t> header = build_header(kind, tensors, n_tensors, step, total);
-    // header: small blocking copy after the stream's earlier work (the blob may be in use by it)
-    FO_HIP(hipStreamSynchronize(stream));
-    FO_HIP(hipMemcpy(blob, header.data(), header.size(), hipMemcpyHostToDevice));
     std::vector<CopySegment> segs;
     build_segments(kind, tensors, n_tensors, static_cast<uint8_t*>(blob), true, segs);
-    return run_copy(segs, stream);
+    return run_copy(segs, stream, header.data(), header.size(), blob);
 }
 
 int flashoptim_checkpoint_unpack(int kind, const void* blob, int64_t blob_bytes, const flashoptim_tensor* tensors,
@@ -846,13 +875,17 @@ static int run_selftest(unsigned long long (&h)[fo::kSelftestCounters], bool onl
     if (!only_faithful) {
         for (int section = 0; section < 4 && e == hipSuccess; ++section) e = fo::launch_selftest(d, section, c, 1.0f, stream);
         if (e == hipSuccess) e = fo::launch_selftest(d, 5, c, 1.0f, stream);
-        // variance codes: bias corrections of steps 1, 2, 10, 1000 and "infinity", three group scales
-        const int64_t steps[5] = {1, 2, 10, 1000, 100000000};
+        // variance codes: the estimate depends on the call's bias correction through (rbc2, root_bc2), so
+        // the section runs with the pairs of steps 1..20 and of a log-spaced set up to 10^6, for four
+        // values of beta2, each with three group scales
+        const float beta2s[4] = {0.95f, 0.99f, 0.999f, 0.9999f};
         const float scales[3] = {0.000244140625f /* 2^-12 */, 0.00131988525390625f, 0.03125f};
-        for (int i = 0; i < 5 && e == hipSuccess; ++i) {
-            c.rbc2 = recip_bias_correction(0.999f, steps[i]);
-            c.root_bc2 = (float)std::sqrt(1.0 / (double)c.rbc2);
-            for (int k = 0; k < 3 && e == hipSuccess; ++k) e = fo::launch_selftest(d, 4, c, 1.0f / scales[k], stream);
+        for (int b = 0; b < 4 && e == hipSuccess; ++b) {
+            for (int i = 0; i < fo::kSelftestVarSteps && e == hipSuccess; ++i) {
+                c.rbc2 = recip_bias_correction(beta2s[b], fo::selftest_var_step(i));
+                c.root_bc2 = (float)std::sqrt(1.0 / (double)c.rbc2);
+                for (int k = 0; k < 3 && e == hipSuccess; ++k) e = fo::launch_selftest(d, 4, c, 1.0f / scales[k], stream);
+            }
         }
     }
     if (e == hipSuccess) e = hipMemcpyAsync(h, d, sizeof(h), hipMemcpyDeviceToHost, stream);
@@ -891,8 +924,9 @@ int flashoptim_faithful_rounding_stats(int64_t* counts, void* stream) {
 
 int flashoptim_clock_monitor(uint64_t* samples, int64_t n_samples, double seconds_per_sample, double* tick_hz,
                              void* stream) {
+    // the kernel's lifetime is bounded by n_samples x seconds_per_sample: at most ten seconds in all
     if (!samples || n_samples < 1 || n_samples > 100000 || !(seconds_per_sample > 0.0) || seconds_per_sample > 1.0 ||
-        !tick_hz)
+        (double)n_samples * seconds_per_sample > 10.0 || !tick_hz)
         return FLASHOPTIM_ERR_INVALID_ARG;
     int dev = 0, khz = 0;
     FO_HIP(hipGetDevice(&dev));
@@ -910,6 +944,19 @@ int flashoptim_short_sqrt_state(void) {
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return FLASHOPTIM_ERR_HIP; }
     if (dev < 0 || dev >= kMaxDevices) return 2;
     return g_sqrt_state[dev].load(std::memory_order_acquire);
+}
+
+int flashoptim_shard_range(int64_t numel, int64_t world, int64_t rank, int64_t* begin, int64_t* len) {
+    if (numel < 0 || numel >= kMaxNumel) return FLASHOPTIM_ERR_NUMEL_RANGE;
+    if (world < 1 || rank < 0 || rank >= world || !begin || !len) return FLASHOPTIM_ERR_INVALID_ARG;
+    const int64_t units = (numel + kShardUnit - 1) / kShardUnit;      // the last unit may be short
+    const int64_t base = units / world, extra = units % world;
+    const int64_t first = rank * base + (rank < extra ? rank : extra);
+    const int64_t count = base + (rank < extra ? 1 : 0);
+    const int64_t b = first * kShardUnit, e = (first + count) * kShardUnit;
+    *begin = b < numel ? b : numel;
+    *len = (e < numel ? e : numel) - *begin;
+    return FLASHOPTIM_OK;
 }
 
 const char* flashoptim_strerror(int status) {

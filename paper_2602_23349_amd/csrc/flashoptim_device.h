@@ -120,6 +120,18 @@ void launch_copy(const CopySegment* segs, const uint2* chunks, int64_t n_chunks,
 constexpr int kSelftestSectionCount = 7;
 constexpr unsigned long long kSelftestSqrtValues = 0x7f800000ull - 0x0f800000ull;   // section 2: every FP32 value in [2^-96, FLT_MAX]
 constexpr int kSelftestCounters = 15;   // two per section, then the inexact count of section 6
+// Section 4 (variance codes) runs once per (beta2, step, group scale): steps 1..20, then 50, 100, 200, 500, ... 10^6.
+constexpr int kSelftestVarSteps = 34;
+constexpr int64_t selftest_var_step(int i) {
+    if (i < 20) return i + 1;
+    const int j = i - 20;                        // 50, 100, 200, 500, 1000, ... (j = 0 .. 13)
+    const int64_t lead[3] = {5, 10, 20};
+    int64_t p = 10;
+    for (int k = 0; k < j / 3; ++k) p *= 10;
+    return lead[j % 3] * p;
+}
+static_assert(selftest_var_step(19) == 20 && selftest_var_step(20) == 50 && selftest_var_step(21) == 100 &&
+              selftest_var_step(22) == 200 && selftest_var_step(33) == 1000000, "");
 hipError_t launch_selftest(unsigned long long* counters, int section, const StepConsts& c, float scale_r,
                            hipStream_t s);
 

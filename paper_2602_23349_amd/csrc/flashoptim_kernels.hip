@@ -28,13 +28,13 @@
 //     mantissa byte is the round-half-even integer in two's complement;
 //   * BF16 rounding uses the hardware v_cvt_pk_bf16_f32 (two elements per issue);
 //   * an 8-bit state code is Round(y) of a value y whose exact evaluation needs an IEEE
-//     division (momentum) or square root (variance).  The kernel first evaluates y with the
-//     1-ulp hardware reciprocal / with the square root it already has from the update; the
-//     result provably differs from the exact y by less than a small delta, so unless it
-//     lands within delta of a rounding tie the code is already decided.  Only when some
-//     lane of the wavefront is that close to a tie (a few percent of the wavefronts) are the
-//     few elements concerned recomputed with the exact sequence.  Codes are bit-identical
-//     to the exact evaluation in every case;
+//     division (momentum) or square root (variance).  The kernel evaluates y with the 1-ulp hardware
+//     reciprocal / with the square root it already has from the update; that estimate provably
+//     differs from the exact y by less than a small w.  It rounds estimate - w and estimate + w
+//     (v_cvt_pk_u8_f32: round-half-even, saturation and byte packing in one instruction); where both
+//     give the same integer the code is decided.  Only when they differ for some lane of the
+//     wavefront (a few percent of the wavefronts) are the four elements concerned recomputed with
+//     the exact sequence.  Codes are bit-identical to the exact evaluation in every case;
 //   * sqrt(v_hat) and m_hat / (sqrt(v_hat) + eps) use the 1-ulp hardware reciprocal square
 //     root / reciprocal followed by FMA residual corrections that yield the correctly rounded
 //     result for operands inside a stated range (the square root: verified for every value of
@@ -225,19 +225,23 @@ __device__ __forceinline__ uint32_t m_code_exact(float m, float r) {
     return round_to_int_bits(y);
 }
 
-// Same code through the hardware reciprocal.  m1 and den are formed exactly as above; the
-// quotient uses v_rcp_f32 (1 ulp), so y differs from the exact y by at most
-// (2 + 1 + 1 + 2) * 2^-24 * 128 < 4.6e-5 wherever the clamp is not active.  *resid is the
-// distance of y from the integer it rounds to.
+// The same code decided from an estimate.  m1 and den are formed exactly as above; the quotient uses
+// v_rcp_f32 (1 ulp), so y* = 254 * (m1 * rc) differs from the exact y by at most
+// (2 + 1 + 1 + 1) * 2^-24 * 128 < 3.9e-5 wherever the clamp is not active.  The function returns
+// y* + 128 -+ w, each formed by ONE fused multiply-add (its rounding, half an ulp of a value below 256,
+// adds 7.7e-6, and 128 -+ w itself is off by at most 3.9e-6): if both round to the same integer no
+// rounding tie lies within 4.7e-5 of y* on either side and that integer is the exact code plus 128.  The
+// integers come from v_cvt_pk_u8_f32 (round-half-even, saturating at 0 and 255, one byte of a word per
+// instruction): its saturation at 255 is the upper clamp of the code (+127); the lower clamp (-127) is
+// the clamp of p at -1/2.
 constexpr float kTieWindowM = 6.0e-5f;
-__device__ __forceinline__ uint32_t m_code_fast(float m, float r, float* resid) {
+__device__ __forceinline__ void m_code_bracket(float m, float r, float* lo, float* hi) {
     const float m1 = m * r;
     const float den = 1.0f + fabsf(m1);
     const float rc = __builtin_amdgcn_rcpf(den);
-    const float y = __builtin_amdgcn_fmed3f((m1 * rc) * 254.0f, -127.0f, 127.0f);
-    const float t = y + 12582912.0f;
-    *resid = fabsf((t - 12582912.0f) - y);
-    return f2u(t);
+    const float p = fmaxf(m1 * rc, -0.5f);
+    *lo = fmaf(p, 254.0f, 128.0f - kTieWindowM);
+    *hi = fmaf(p, 254.0f, 128.0f + kTieWindowM);
 }
 
 // Exact Q_v code of one element from v and the reciprocal group scale (Algorithm 3, encoder).
@@ -252,16 +256,22 @@ __device__ __forceinline__ uint32_t v_code_exact_midrange(float v, float r) {
     return round_to_int_bits(y);
 }
 
-// Same code from root_hat = sqrt(v * rbc2) (exactly rounded, already computed for the update)
-// and kr255 = ((sqrt(1/rbc2) rounded) * r) * 255.  Relative errors: v*rbc2 (1), its root
-// (0.5 + 1), the three roundings inside kr255 (3), this product (1), against the three
-// roundings of the exact chain (3): below 9.5 * 2^-24 * 255 < 1.45e-4 in y.
+// The same code decided from root_hat = sqrt(v * rbc2) (exactly rounded, already computed for the update)
+// and kr255 = ((sqrt(1/rbc2) rounded) * r) * 255.  Relative errors of y* = root_hat * kr255 against the
+// exact y, in units of 2^-24: v*rbc2 (1/2 after the root), the root (1), sqrt(1/rbc2) as held in FP32 (1 for
+// its own rounding, 1/2 for rbc2's), the two products inside kr255 (2), against the three roundings of
+// the exact chain (3): 8 * 2^-24 * 255 < 1.22e-4 in y.  The function returns y* -+ w, each ONE fused
+// multiply-add (rounding: half an ulp of a value below 256, 7.7e-6): if both round to the same integer no
+// rounding tie lies within 1.7e-4 of y*, and that integer is the exact code.  The conversion's saturation
+// at 255 is the clamp of Algorithm 3.
 constexpr float kTieWindowV = 1.8e-4f;
-__device__ __forceinline__ uint32_t v_code_fast(float root_hat, float kr255, float* resid) {
-    const float y = __builtin_amdgcn_fmed3f(root_hat * kr255, 0.0f, 255.0f);
-    const float t = y + 12582912.0f;
-    *resid = fabsf((t - 12582912.0f) - y);
-    return f2u(t);
+__device__ __forceinline__ void v_code_bracket(float root_hat, float kr255, float* lo, float* hi) {
+    *lo = fmaf(root_hat, kr255, -kTieWindowV);
+    *hi = fmaf(root_hat, kr255, kTieWindowV);
+}
+// Round-half-even of x to 0..255 (saturating; NaN gives 0), placed in byte `k` of `word`.
+__device__ __forceinline__ uint32_t put_u8(float x, uint32_t k, uint32_t word) {
+    return __builtin_amdgcn_cvt_pk_u8_f32(x, k, word);
 }
 
 // Low bytes of four words -> one word (c0 in byte 0).
@@ -814,34 +824,39 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
 
     // amax_v is the group's here, which is at least the lane's
     const bool vt_root_general = HAS_V && (any_lane(!(amin_v >= c.sqrt_min)) | amax_v_not_finite);
-    // epilogue: state codes, four at a time; exact recomputation only near rounding ties
+    // epilogue: state codes, four at a time (one word of each code stream).  Each code is converted
+    // twice, from the two ends of an interval that contains the exact argument of Round(); where the
+    // two words differ some element of the block may sit on the other side of a rounding tie, and the
+    // block is recomputed with the exact sequence (for the whole wavefront: a few percent of the blocks).
 #pragma unroll
     for (int j = 0; j < VEC / 4; ++j) {
-        uint32_t cm[4];
-        float dm = 0.0f;
+        uint32_t lo_w = 0, hi_w = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            float d;
-            cm[k] = m_code_fast(mt[4 * j + k], r_m, &d);
-            dm = fmaxf(dm, d);
+            float lo, hi;
+            m_code_bracket(mt[4 * j + k], r_m, &lo, &hi);
+            lo_w = put_u8(lo, k, lo_w);
+            hi_w = put_u8(hi, k, hi_w);
         }
-        if (any_lane(dm > 0.5f - kTieWindowM)) {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) cm[k] = m_code_exact(mt[4 * j + k], r_m);
+        if (any_lane(lo_w != hi_w)) {
+            y.mq[j] = pack_low_bytes(m_code_exact(mt[4 * j], r_m), m_code_exact(mt[4 * j + 1], r_m),
+                                     m_code_exact(mt[4 * j + 2], r_m), m_code_exact(mt[4 * j + 3], r_m));
+        } else {
+            y.mq[j] = lo_w ^ 0x80808080u;      // code + 128 -> two's complement
         }
-        y.mq[j] = pack_low_bytes(cm[0], cm[1], cm[2], cm[3]);
         if (HAS_V) {
-            uint32_t cv[4];
-            float dv = 0.0f;
+            lo_w = 0; hi_w = 0;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                float d;
-                cv[k] = v_code_fast(rh[4 * j + k], kr255, &d);
-                dv = fmaxf(dv, d);
+                float lo, hi;
+                v_code_bracket(rh[4 * j + k], kr255, &lo, &hi);
+                lo_w = put_u8(lo, k, lo_w);
+                hi_w = put_u8(hi, k, hi_w);
             }
-            if (any_lane(dv > 0.5f - kTieWindowV)) {
+            if (any_lane(lo_w != hi_w)) {
                 // exact recomputation; the short exact root serves when every v_t of the wavefront
                 // is in its range (v_t and v_hat differ by the factor rbc2 >= 1: a separate test)
+                uint32_t cv[4];
                 if (vt_root_general) {
 #pragma unroll
                     for (int k = 0; k < 4; ++k) cv[k] = v_code_exact(vt[4 * j + k], r_v);
@@ -849,8 +864,10 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
 #pragma unroll
                     for (int k = 0; k < 4; ++k) cv[k] = v_code_exact_midrange(vt[4 * j + k], r_v);
                 }
+                y.vq[j] = pack_low_bytes(cv[0], cv[1], cv[2], cv[3]);
+            } else {
+                y.vq[j] = lo_w;
             }
-            y.vq[j] = pack_low_bytes(cv[0], cv[1], cv[2], cv[3]);
         }
     }
 }
@@ -1581,10 +1598,10 @@ hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs
 //   section 0: recip_of_fp16(s) == 1.0f / s for every positive finite FP16 value s;
 //   section 1: v_rcp_f32(d) within 1 ulp of 1.0f / d for every d in [1, 4);
 //   section 2: sqrt_rn_midrange(x) == sqrtf(x) for EVERY FP32 value x of its range [2^-96, FLT_MAX];
-//   section 3: momentum codes: wherever the tie test does not fire, m_code_fast == m_code_exact,
-//              for every m' in [2^-13, 2) of either sign;
-//   section 4: variance codes: same for v_code_fast against v_code_exact, over every FP32 value of
-//              four binades of v, several bias-correction pairs and several group scales.
+//   section 3: momentum codes: wherever the two conversions of m_code_bracket agree, they agree with
+//              m_code_exact, for every m' in [2^-13, 2) of either sign;
+//   section 4: variance codes: same for v_code_bracket against v_code_exact, over every FP32 value of
+//              four binades of v, for the bias-correction pair and group scale the host passes.
 //   section 5: div_rn_midrange(n, d) == n / d on 2^30 pseudo-random operand pairs with magnitudes
 //              in [2^-60, 2^60] (n of either sign), plus pairs that share d across all mantissas of n.
 //   section 6: div_faithful(n, d) within 1 ulp of n / d on the operand pairs of section 5.  (It fails on
@@ -1595,25 +1612,18 @@ hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs
 constexpr int kSelftestSections = 7;
 constexpr uint64_t kSelftestSqrtCount = kSelftestSqrtValues;
 constexpr uint64_t kSelftestDivCount = (1ull << 30) + (1ull << 24);
+constexpr uint64_t kSelftestVarCount = 4ull * (1ull << 23);
+constexpr int kSelftestPerLane = 64;
 
 __device__ __forceinline__ uint32_t selftest_hash(uint64_t x) {
     x ^= x >> 33; x *= 0xff51afd7ed558ccdull; x ^= x >> 33; x *= 0xc4ceb9fe1a85ec53ull; x ^= x >> 33;
     return (uint32_t)x;
 }
 
-__device__ __forceinline__ void selftest_tally(unsigned long long* counters, int section, bool checked, bool failed) {
-    const unsigned long long c = __popcll(__builtin_amdgcn_ballot_w64(checked));
-    const unsigned long long f = __popcll(__builtin_amdgcn_ballot_w64(checked && failed));
-    if ((threadIdx.x & 63) == 0) {
-        if (c) atomicAdd(&counters[2 * section], c);
-        if (f) atomicAdd(&counters[2 * section + 1], f);
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void selftest_kernel(unsigned long long* counters, int section,
-                                                            StepConsts c, float scale_r) {
-    const uint64_t gid = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
-    bool checked = false, failed = false;
+// One check of `section` on value number gid of its domain.
+__device__ __forceinline__ void selftest_one(int section, uint64_t gid, const StepConsts& c, float scale_r,
+                                             bool& checked, bool& failed, bool& inexact) {
+    checked = false; failed = false; inexact = false;
     if (section == 0) {
         if (gid >= 1 && gid <= 0x7bffu) {
             const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)gid);
@@ -1638,11 +1648,12 @@ __global__ __launch_bounds__(kThreads) void selftest_kernel(unsigned long long* 
             const uint32_t sign = (uint32_t)(gid & 1) << 31;
             const uint32_t mag = 0x39000000u + (uint32_t)(gid >> 1);     // 2^-13 ... 2
             const float m1 = u2f(sign | mag);
-            float resid;
-            const uint32_t fast = m_code_fast(m1, 1.0f, &resid) & 0xffu;
+            float lo, hi;
+            m_code_bracket(m1, 1.0f, &lo, &hi);
+            const uint32_t a = put_u8(lo, 0, 0), b = put_u8(hi, 0, 0);
             const uint32_t exact = m_code_exact(m1, 1.0f) & 0xffu;
-            checked = !(resid > 0.5f - kTieWindowM);
-            failed = fast != exact;
+            checked = (a == b);
+            failed = (a ^ 0x80u) != exact;
         }
     } else if (section == 5 || section == 6) {
         if (gid < kSelftestDivCount) {
@@ -1664,27 +1675,56 @@ __global__ __launch_bounds__(kThreads) void selftest_kernel(unsigned long long* 
             } else {
                 const int32_t diff = (int32_t)f2u(div_faithful(n, d)) - (int32_t)f2u(n / d);
                 failed = diff > 1 || diff < -1;
-                const unsigned long long inexact = __popcll(__builtin_amdgcn_ballot_w64(diff != 0));
-                if ((threadIdx.x & 63) == 0 && inexact) atomicAdd(&counters[14], inexact);
+                inexact = diff != 0;
             }
         }
     } else {
-        if (gid < 4ull * (1ull << 23)) {
-            // four binades of v starting at 2^-30, 2^-29, 2^-11, 2^-10 (odd and even exponents; with the
+        if (gid < kSelftestVarCount) {
+            // binades of v starting at 2^-30, 2^-29, 2^-11, 2^-10 (odd and even exponents; with the
             // scales used by the host the codes land in 6..64 and in 180..255 and beyond)
             const uint32_t k = (uint32_t)(gid >> 23), mant = (uint32_t)gid & 0x7fffffu;
             const uint32_t ebits = (k == 0 ? 97u : k == 1 ? 98u : k == 2 ? 116u : 117u) << 23;
             const float v = u2f(ebits | mant);
             const float root_hat = sqrtf(v * c.rbc2);
             const float kr255 = (c.root_bc2 * scale_r) * 255.0f;
-            float resid;
-            const uint32_t fast = v_code_fast(root_hat, kr255, &resid) & 0xffu;
+            float lo, hi;
+            v_code_bracket(root_hat, kr255, &lo, &hi);
+            const uint32_t a = put_u8(lo, 0, 0), b = put_u8(hi, 0, 0);
             const uint32_t exact = v_code_exact(v, scale_r) & 0xffu;
-            checked = !(resid > 0.5f - kTieWindowV);
-            failed = fast != exact;
+            checked = (a == b);
+            failed = a != exact;
         }
     }
-    selftest_tally(counters, section, checked, failed);
+}
+
+// A lane checks kSelftestPerLane values (number gid = first + j * lanes in the grid) and keeps its counts in
+// registers; a workgroup adds them up in LDS and issues at most three global atomics.  (One atomic per
+// wavefront and value made the exhaustive square-root section take 350 ms, all of it spent on the
+// 29 million updates of one counter.)
+__global__ __launch_bounds__(kThreads) void selftest_kernel(unsigned long long* counters, int section,
+                                                            StepConsts c, float scale_r) {
+    __shared__ unsigned int tally[3];
+    if (threadIdx.x < 3) tally[threadIdx.x] = 0;
+    __syncthreads();
+    const uint64_t lanes = (uint64_t)gridDim.x * kThreads;
+    uint64_t gid = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    unsigned int n_checked = 0, n_failed = 0, n_inexact = 0;
+    for (int j = 0; j < kSelftestPerLane; ++j, gid += lanes) {
+        bool checked, failed, inexact;
+        selftest_one(section, gid, c, scale_r, checked, failed, inexact);
+        n_checked += checked ? 1u : 0u;
+        n_failed += (checked && failed) ? 1u : 0u;
+        n_inexact += inexact ? 1u : 0u;
+    }
+    if (n_checked) atomicAdd(&tally[0], n_checked);
+    if (n_failed) atomicAdd(&tally[1], n_failed);
+    if (n_inexact) atomicAdd(&tally[2], n_inexact);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (tally[0]) atomicAdd(&counters[2 * section], (unsigned long long)tally[0]);
+        if (tally[1]) atomicAdd(&counters[2 * section + 1], (unsigned long long)tally[1]);
+        if (tally[2]) atomicAdd(&counters[14], (unsigned long long)tally[2]);
+    }
 }
 
 hipError_t launch_selftest(unsigned long long* counters, int section, const StepConsts& c, float scale_r,
@@ -1695,8 +1735,9 @@ hipError_t launch_selftest(unsigned long long* counters, int section, const Step
     else if (section == 2) n = kSelftestSqrtCount;
     else if (section == 3) n = 2ull * 14 * (1ull << 23);
     else if (section == 5 || section == 6) n = kSelftestDivCount;
-    else n = 4ull * (1ull << 23);
-    hipLaunchKernelGGL(selftest_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s,
+    else n = kSelftestVarCount;
+    const uint64_t per_block = (uint64_t)kThreads * kSelftestPerLane;
+    hipLaunchKernelGGL(selftest_kernel, dim3((unsigned)((n + per_block - 1) / per_block)), dim3(kThreads), 0, s,
                        counters, section, c, scale_r);
     return hipGetLastError();
 }

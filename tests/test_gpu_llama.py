@@ -5,10 +5,12 @@ the launch configurations the benchmark times:
   * workload 5: gradient release - one call per tensor in reverse list order through a single
     reused gradient buffer (5 B/param resident) - then checkpoint pack / unpack.
 
-The oracle cannot run 8 G parameters in seconds, and quantisation groups of 32 elements are
-independent of each other, so it runs the same steps on SAMPLED groups of every tensor (first and
-last group, groups on both sides of workgroup-chunk boundaries, random groups), fed with copies of
-the very inputs the GPU used (theta_0 and gradients drawn on the device by the seeded generator).
+This is the FAST form of the full-size check (test_gpu_llama_full.py compares every element and takes
+minutes): quantisation groups of 32 elements are independent of each other, so the oracle runs the
+same steps on SAMPLED groups of every tensor (first and last group, groups on both sides of tile
+boundaries and of the boundaries between the kernel launches of one fused call, random groups), fed
+with copies of the very inputs the GPU used (theta_0 and gradients drawn on the device by the seeded
+generator).
 Whole-list properties that hold at any size are checked on the device: gradient release gives the
 same bits as the fused call, and pack -> unpack restores every buffer.
 """
@@ -29,10 +31,24 @@ GRAD_SCALE = 1e-4
 N_RANDOM_GROUPS = 20
 
 
-def _sample_groups(numel, rng):
+TILE = 2048                       # elements per workgroup of the AdamW step
+LAUNCH_TILES = (1 << 28) // TILE  # workgroups per kernel launch of a fused call
+
+
+def _sample_groups(numel, rng, first_tile=0):
+    """First and last group, both sides of the first tile boundaries, both sides of every boundary between two
+    kernel launches of the fused call that falls inside this tensor (first_tile = index of the tensor's first
+    workgroup in the call), and random groups."""
     ng = (numel + 31) // 32
     pick = {0, ng - 1}
-    for edge in (8192 // 32, 2 * 8192 // 32, 4096 // 32):       # chunk and tile boundaries
+    edges = [TILE // 32, 2 * TILE // 32, 3 * TILE // 32]
+    n_tiles = (numel + TILE - 1) // TILE
+    k = (first_tile + LAUNCH_TILES - 1) // LAUNCH_TILES
+    while k * LAUNCH_TILES < first_tile + n_tiles:
+        if k * LAUNCH_TILES > first_tile:
+            edges.append((k * LAUNCH_TILES - first_tile) * TILE // 32)
+        k += 1
+    for edge in edges:
         for g in (edge - 1, edge):
             if 0 <= g < ng:
                 pick.add(g)
@@ -50,7 +66,11 @@ class _Sampled:
 
     def __init__(self, specs):
         rng = np.random.default_rng(1234)
-        self.groups = [_sample_groups(sp.numel, rng) for sp in specs]
+        self.groups, first = [], 0
+        for sp in specs:
+            self.groups.append(_sample_groups(sp.numel, rng, first))
+            first += (sp.numel + TILE - 1) // TILE
+        assert sum(g.size for g in self.groups) > 7642        # the launch boundaries add to the per-tensor samples
         self.eidx = [_elem_index(g, sp.numel, "cuda") for g, sp in zip(self.groups, specs)]
         self.gidx = [torch.from_numpy(g).cuda() for g in self.groups]
         self.states = [None] * len(specs)

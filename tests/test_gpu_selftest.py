@@ -15,7 +15,8 @@ def test_device_selftest_passes():
     assert checked[2] == 0x7f800000 - 0x0f800000      # every FP32 value in [2^-96, FLT_MAX]
     # code sections: all candidates minus the few inside the tie window
     assert checked[3] > 0.99 * 2 * 14 * (1 << 23)
-    assert checked[4] > 0.95 * 15 * 4 * (1 << 23)
+    # variance codes: 4 values of beta2 x 34 steps (1..20, then log-spaced to 10^6) x 3 group scales
+    assert checked[4] > 0.95 * (4 * 34 * 3) * 4 * (1 << 23)
     assert checked[5] == (1 << 30) + (1 << 24)       # short division against IEEE division
     assert checked[6] == checked[5]                  # faithful division on the same operand pairs
 
