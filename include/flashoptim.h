@@ -58,7 +58,8 @@ typedef enum flashoptim_status {
     FLASHOPTIM_ERR_NUMEL_RANGE = -3, /* numel < 0 or >= 2^40                                  */
     FLASHOPTIM_ERR_HIP = -4,         /* a HIP runtime call failed (see flashoptim_last_hip_error) */
     FLASHOPTIM_ERR_BAD_BLOB = -5,    /* checkpoint blob too small, or header/table mismatch   */
-    FLASHOPTIM_ERR_SELFTEST = -6     /* flashoptim_selftest found a failing check             */
+    FLASHOPTIM_ERR_SELFTEST = -6,    /* flashoptim_selftest found a failing check             */
+    FLASHOPTIM_ERR_LIST_TOO_LONG = -7 /* flashoptim_adamw_step_noalloc: more than 1024 non-empty tensors */
 } flashoptim_status;
 
 /* Optimizer kinds (checkpoint entry points). */
@@ -127,6 +128,21 @@ int flashoptim_sgd_step(const flashoptim_tensor* tensors, int64_t n_tensors,
                         const flashoptim_sgd_hp* hp, void* stream);
 int flashoptim_lion_step(const flashoptim_tensor* tensors, int64_t n_tensors,
                          const flashoptim_lion_hp* hp, void* stream);
+
+/* ---- the FlashAdamW step for callers that cannot allocate ---------------------------------
+ * For code under HIP stream capture, tight serving loops and harnesses that forbid allocation: the same step
+ * as flashoptim_adamw_step_exact, same arguments, same results bit for bit, but the call allocates nothing
+ * (no hipMalloc / hipFree / hipHostMalloc, no host-to-device copy): the two device tables of a multi-tensor
+ * launch are written by small kernels, from kernel arguments, into a fixed 172,032-byte device array that
+ * each GPU holds from library load to process end.
+ * Limits: at most 1024 tensors with numel > 0 (FLASHOPTIM_ERR_LIST_TOO_LONG beyond that, nothing enqueued) and,
+ * as for every step call, at most 2^31 - 1 workgroups.  Every call on a GPU shares that GPU's array: calls on
+ * the same stream are ordered and safe; calls that may overlap on one GPU (different streams, several host
+ * threads) race on it and must be ordered by the caller.  The short square root is used only if an earlier
+ * AdamW step call of another entry point has verified it on this device (flashoptim_short_sqrt_state() == 1);
+ * otherwise the kernels use sqrtf: same results, a few percent slower. */
+int flashoptim_adamw_step_noalloc(const flashoptim_tensor* tensors, int64_t n_tensors,
+                                  const flashoptim_adamw_hp* hp, void* stream);
 
 /* ---- sharding a flat tensor over ranks (Section 3.4, "Distributed training") ----------------
  * With ZeRO / FSDP-style sharding each rank owns a contiguous piece of every flattened tensor, keeps rho, the

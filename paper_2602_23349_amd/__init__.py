@@ -5,7 +5,7 @@ loudly if the library has not been built (python paper_2602_23349_amd/build.py).
 """
 from .binding import (  # noqa: F401
     FlashOptimError, TensorList, ParamBuffers, library_path, load_library,
-    adamw_step, adamw_step_exact, shard_range, sgd_step, lion_step, adamw_step_ex, sgd_step_ex, lion_step_ex, TensorListEx,
+    adamw_step, adamw_step_exact, adamw_step_noalloc, shard_range, sgd_step, lion_step, adamw_step_ex, sgd_step_ex, lion_step_ex, TensorListEx,
     SPLIT_WEIGHTS, QUANTIZE_STATES,
     split_weights, reconstruct_weights, split_weights_i16, reconstruct_weights_i16, reconstruction_sweep, reconstruction_sweep_ex,
     quantize_momentum, dequantize_momentum, quantize_variance, dequantize_variance,

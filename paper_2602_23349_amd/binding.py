@@ -29,7 +29,7 @@ EXPORTED_SYMBOLS = [
     "flashoptim_adamw_step_ex", "flashoptim_sgd_step_ex", "flashoptim_lion_step_ex",
     "flashoptim_quantize_state", "flashoptim_dequantize_state", "flashoptim_quantization_nmse",
     "flashoptim_compress_state", "flashoptim_decompress_state", "flashoptim_stream_probe",
-    "flashoptim_shard_range",
+    "flashoptim_adamw_step_noalloc", "flashoptim_shard_range",
 ]
 
 
@@ -82,6 +82,7 @@ def load_library():
     vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int
     L.flashoptim_adamw_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_AdamWHp), vp]
     L.flashoptim_adamw_step_exact.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_AdamWHp), vp]
+    L.flashoptim_adamw_step_noalloc.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_AdamWHp), vp]
     L.flashoptim_shard_range.argtypes = [i64, i64, i64, C.POINTER(i64), C.POINTER(i64)]
     L.flashoptim_sgd_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_SgdHp), vp]
     L.flashoptim_lion_step.argtypes = [C.POINTER(_Tensor), i64, C.POINTER(_LionHp), vp]
@@ -275,6 +276,13 @@ def adamw_step_exact(tensors, beta1, beta2, eps, step, stream=None):
     hp = _AdamWHp(beta1, beta2, eps, int(step))
     _check(load_library().flashoptim_adamw_step_exact(tl.array, tl.n, C.byref(hp), _stream(stream)),
            "flashoptim_adamw_step_exact")
+
+
+def adamw_step_noalloc(tensors, beta1, beta2, eps, step, stream=None):
+    tl = _as_list(tensors)
+    hp = _AdamWHp(beta1, beta2, eps, int(step))
+    _check(load_library().flashoptim_adamw_step_noalloc(tl.array, tl.n, C.byref(hp), _stream(stream)),
+           "flashoptim_adamw_step_noalloc")
 
 
 def shard_range(numel, world, rank):

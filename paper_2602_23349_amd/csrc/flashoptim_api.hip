@@ -564,7 +564,64 @@ int check_elementwise(const void* a, const void* b, const void* c, int64_t n) {
     return FLASHOPTIM_OK;
 }
 
+// ------------------------------------------ the step entry point that allocates nothing --
+//
+// For callers that cannot allocate device memory (stream capture, tight serving loops): the two device
+// tables of a multi-tensor launch live in a fixed array that every GPU holds from library load to process
+// end, instead of in a cached allocation.  `scratch` is the array's host-side stand-in: host code never
+// passes it anywhere; it asks the runtime once per device for the array's device address and uses that.
 constexpr int64_t kShardUnit = 256;     // elements: a shard that starts on a multiple has every stream 16-byte aligned
+constexpr int kNoAllocMaxTensors = 1024;
+constexpr size_t kScratchTableBytes = kNoAllocMaxTensors * sizeof(TensorDev);                 // 106,496
+constexpr size_t kScratchBytes = kScratchTableBytes + fo::kCoarseMaxEntries * sizeof(uint32_t);   // + 65,536
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+std::atomic<unsigned char*> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mu;
+
+// Device address of the array on `dev`, which must be the current device.
+int scratch_of_device(int dev, unsigned char** out) {
+    if (dev < 0 || dev >= kMaxDevices) return FLASHOPTIM_ERR_INVALID_ARG;
+    unsigned char* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_scratch_mu);
+        p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+        if (!p) {
+            void* sym = nullptr;
+            FO_HIP(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+            if (!sym) return FLASHOPTIM_ERR_HIP;
+            p = static_cast<unsigned char*>(sym);
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return FLASHOPTIM_OK;
+}
+
+// Tensor descriptors reach the table as kernel arguments (no host-to-device copy, hence no staging memory).
+constexpr int kTableBatch = 32;
+struct TableBatch {
+    uint32_t first, count;
+    TensorDev t[kTableBatch];
+};
+static_assert(sizeof(TableBatch) <= 4096, "kernel arguments");
+__global__ __launch_bounds__(64) void noalloc_fill_table(TableBatch b, TensorDev* table) {
+    if (threadIdx.x < b.count) table[b.first + threadIdx.x] = b.t[threadIdx.x];
+}
+// coarse[j] = the tensor that holds tile j << shift: the last one whose first tile is not beyond it
+// (every tensor of the table has at least one tile, so first_tile increases strictly).
+__global__ __launch_bounds__(256) void noalloc_fill_coarse(const TensorDev* table, uint32_t n_tensors,
+                                                           uint32_t* coarse, uint32_t n_coarse, uint32_t shift) {
+    const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n_coarse) return;
+    const uint32_t b = j << shift;
+    uint32_t lo = 0, hi = n_tensors - 1;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) >> 1;
+        if (table[mid].first_tile <= b) lo = mid; else hi = mid - 1;
+    }
+    coarse[j] = lo;
+}
 
 }  // namespace
 
@@ -959,6 +1016,81 @@ int flashoptim_shard_range(int64_t numel, int64_t world, int64_t rank, int64_t* 
     return FLASHOPTIM_OK;
 }
 
+int flashoptim_adamw_step_noalloc(const flashoptim_tensor* tensors, int64_t n_tensors, const flashoptim_adamw_hp* hp,
+                                  void* stream_) {
+    StepConsts c;
+    if (!adamw_consts(hp, c)) return FLASHOPTIM_ERR_INVALID_ARG;
+    int rc = validate_tensors(tensors, n_tensors, true);
+    if (rc != FLASHOPTIM_OK) return rc;
+    const int64_t ce = fo::chunk_elems(FLASHOPTIM_ADAMW);
+    int64_t n_live = 0, total_tiles = 0, only = -1;
+    for (int64_t i = 0; i < n_tensors; ++i) {
+        if (tensors[i].numel == 0) continue;
+        if (!tensors[i].grad) return FLASHOPTIM_ERR_INVALID_ARG;
+        if (!aligned16(tensors[i].grad)) return FLASHOPTIM_ERR_MISALIGNED;
+        ++n_live;
+        only = i;
+        total_tiles += (tensors[i].numel + ce - 1) / ce;
+    }
+    if (n_live == 0) return FLASHOPTIM_OK;
+    if (n_live > kNoAllocMaxTensors) return FLASHOPTIM_ERR_LIST_TOO_LONG;
+    if (total_tiles > (int64_t)0x7fffffff) return FLASHOPTIM_ERR_NUMEL_RANGE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    int dev = 0;
+    FO_HIP(hipGetDevice(&dev));
+    // the short square root only where an earlier call has verified it on this device (that check allocates
+    // and waits, so it is not run from here); sqrtf otherwise: same results
+    const bool verified = dev >= 0 && dev < kMaxDevices && g_sqrt_state[dev].load(std::memory_order_acquire) == 1;
+    c.sqrt_min = verified ? 1.2621774483536189e-29f /* 2^-96 */ : INFINITY;
+    c.div_max = (c.eps >= fo::kDivFastLo && c.eps <= 1.0f) ? fo::kDivFastHi : -1.0f;
+    StepArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.c = c;
+    if (n_live == 1) {          // one tensor: no table at all
+        a.single = to_dev(tensors[only], true);
+        FO_HIP(launch_op(kOpStepExact, FLASHOPTIM_ADAMW, true, true, true, a, total_tiles, ce, stream));
+        return FLASHOPTIM_OK;
+    }
+    unsigned char* base = nullptr;
+    rc = scratch_of_device(dev, &base);
+    if (rc != FLASHOPTIM_OK) return rc;
+    TensorDev* table = reinterpret_cast<TensorDev*>(base);
+    uint32_t* coarse = reinterpret_cast<uint32_t*>(base + kScratchTableBytes);
+    // the tensor table travels as kernel arguments, 32 descriptors per small launch
+    TableBatch batch;
+    batch.first = 0; batch.count = 0;
+    int64_t first_tile = 0;
+    for (int64_t i = 0; i < n_tensors; ++i) {
+        if (tensors[i].numel == 0) continue;
+        TensorDev d = to_dev(tensors[i], true);
+        d.first_tile = (uint32_t)first_tile;
+        d.n_tiles = (uint32_t)((d.numel + ce - 1) / ce);
+        first_tile += d.n_tiles;
+        batch.t[batch.count++] = d;
+        if (batch.count == kTableBatch) {
+            hipLaunchKernelGGL(noalloc_fill_table, dim3(1), dim3(64), 0, stream, batch, table);
+            FO_HIP(hipGetLastError());
+            batch.first += batch.count; batch.count = 0;
+        }
+    }
+    if (batch.count) {
+        hipLaunchKernelGGL(noalloc_fill_table, dim3(1), dim3(64), 0, stream, batch, table);
+        FO_HIP(hipGetLastError());
+    }
+    uint32_t shift = 0;
+    while ((total_tiles >> shift) > (int64_t)fo::kCoarseMaxEntries) ++shift;
+    const uint32_t n_coarse = (uint32_t)(((total_tiles - 1) >> shift) + 1);
+    hipLaunchKernelGGL(noalloc_fill_coarse, dim3((n_coarse + 255) / 256), dim3(256), 0, stream, table,
+                       (uint32_t)n_live, coarse, n_coarse, shift);
+    FO_HIP(hipGetLastError());
+    a.tensors = table;
+    a.coarse = coarse;
+    a.coarse_shift = shift;
+    a.n_tensors = (uint32_t)n_live;
+    FO_HIP(launch_op(kOpStepExact, FLASHOPTIM_ADAMW, false, true, true, a, total_tiles, ce, stream));
+    return FLASHOPTIM_OK;
+}
+
 const char* flashoptim_strerror(int status) {
     switch (status) {
         case FLASHOPTIM_OK: return "ok";
@@ -968,6 +1100,7 @@ const char* flashoptim_strerror(int status) {
         case FLASHOPTIM_ERR_HIP: return "HIP runtime error";
         case FLASHOPTIM_ERR_BAD_BLOB: return "checkpoint blob too small or does not match the tensor list";
         case FLASHOPTIM_ERR_SELFTEST: return "device self-test found a hardware operation outside its documented error bound";
+        case FLASHOPTIM_ERR_LIST_TOO_LONG: return "list has more tensors than the entry point without allocation holds (1024)";
         default: return "unknown status";
     }
 }
