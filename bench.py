@@ -1,19 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the fused FlashOptim optimizer step on one MI355X.
 
-Default workload (the one the headline metric is quoted on): FlashAdamW over the
-Llama-3.1-8B parameter list (291 tensors, 8,030,261,248 parameters, 57.2 GB of resident
-state), one fused multi-tensor call per step (issued as ~30 back-to-back kernel launches), synthetic values.  A "step" is one pass of the
-whole path: reconstruct master weights and states, AdamW update from BF16 gradients, re-quantise
-states, re-split weights.  Inputs are resident in HBM before the timed region starts.  The timed call is
-flashoptim_adamw_step (the division of the update faithfully rounded; held to the parity bar
-by the GPU tests); --rounding exact times flashoptim_adamw_step_exact instead, and the default run also
-reports it, measured after the timed region, under roofline.bit_exact_entry_point.
+Default workload (the one the headline metric is quoted on): FlashAdamW over the Llama-3.1-8B parameter list
+(291 tensors, 8,030,261,248 parameters, 57.2 GB of resident state), one fused multi-tensor call per step
+(issued as 30 back-to-back kernel launches), synthetic values.  A "step" is one pass of the whole path:
+reconstruct master weights and states, AdamW update from BF16 gradients, re-quantise states, re-split
+weights.  Inputs are resident in HBM before the timed region starts.
 
-Prints ONE JSON line:  params/s (value), ms per step, the HBM roofline of the step kernel
-(algorithmic bytes per step / time per step measured with HIP events on the launch stream; equivalently
-mean bytes per kernel launch / mean launch duration),
-and the CPU oracle's throughput on a bounded sample of the same workload.
+The timed call is flashoptim_adamw_step_exact, the entry point that is bit-identical to the oracle
+(--rounding default times flashoptim_adamw_step instead, whose division is faithfully rounded).
+
+Prints ONE JSON line: params/s (value), ms per step, the HBM roofline of the step kernel (algorithmic bytes
+per step / time per step measured with HIP events on the launch stream; equivalently mean bytes per kernel
+launch / mean launch duration), an `also` array with the other configurations measured in the same process
+(the faithful entry point, gradient release, checkpoint pack / unpack, SGD and Lion on the same list, the
+ResNet-50 and GPT-2 lists, each beside the arithmetic-free probe of its traffic), and the CPU oracle's
+throughput on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -61,9 +63,12 @@ def parse_args():
                     help="flash: both techniques on (the product path); wsplit: split weights + FP32 states; "
                          "oquant: FP32 weights + 8-bit states; ref: plain FP32 optimizer (BF16 gradients). "
                          "The last three are the ablation entry points (fused mode only).")
-    ap.add_argument("--rounding", default="default", choices=["default", "exact"],
-                    help="AdamW only: default = flashoptim_adamw_step (faithfully rounded division, "
-                         "inside the parity bar); exact = flashoptim_adamw_step_exact (bit-identical to the oracle)")
+    ap.add_argument("--rounding", default="exact", choices=["default", "exact"],
+                    help="AdamW only: exact = flashoptim_adamw_step_exact (bit-identical to the oracle; what `value` "
+                         "is); default = flashoptim_adamw_step (faithfully rounded division, inside the parity bar)")
+    ap.add_argument("--no-also", action="store_true",
+                    help="skip the `also` measurements that the default run appends (other entry points, modes, "
+                         "optimizers and lists)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the two side measurements taken after the timed region: the arithmetic-free stream "
@@ -179,21 +184,176 @@ def cpu_baseline(W, specs, kind, hp, dist, scale, seed, target_seconds):
             "single_thread_value": n / single}
 
 
-def read_traffic(kind, workload):
-    """HBM bytes per step (all kernel launches of one call) measured with rocprofv3 --pmc (FETCH_SIZE,
-    WRITE_SIZE), if a summary for this workload has been recorded under profiles/."""
-    path = os.path.join(ROOT, "profiles", f"{kind}_step_{workload}_pmc.txt")
-    if not os.path.exists(path):
-        return None
+def kernel_source_sha():
+    """SHA-256 (first 16 hex digits) of the device code: a counter summary under profiles/ names the sources it
+    was measured on, and stops being reported once they have changed."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in ("paper_2602_23349_amd/csrc/flashoptim_kernels.hip", "paper_2602_23349_amd/csrc/flashoptim_device.h"):
+        h.update(open(os.path.join(ROOT, rel), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def read_profile(path):
     vals = {}
     for line in open(path):
         if "=" in line and not line.startswith("#"):
             k, v = line.split("=", 1)
+            v = v.split("#")[0].strip()
             try:
-                vals[k.strip()] = float(v.split()[0])
+                vals[k.strip()] = float(v)
             except ValueError:
-                pass
-    return vals.get("HBM_BYTES_PER_STEP")
+                vals[k.strip()] = v
+    return vals
+
+
+def read_traffic(kind, workload, entry="exact"):
+    """HBM bytes per step (all kernel launches of one call) RECORDED by rocprofv3 --pmc (FETCH_SIZE,
+    WRITE_SIZE) in a separate, committed run: (bytes, source) - or (None, None) when no summary exists for
+    this workload or the device code has changed since it was taken."""
+    name = f"{kind}_step{'_exact' if (kind == 'adamw' and entry == 'exact') else ''}_{workload}_pmc.txt"
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None, None
+    vals = read_profile(path)
+    if vals.get("KERNEL_SOURCE_SHA") != kernel_source_sha():
+        return None, {"file": "profiles/" + name, "stale": True}
+    return vals.get("HBM_BYTES_PER_STEP"), {"file": "profiles/" + name, "kernel_source_sha": vals["KERNEL_SOURCE_SHA"],
+                                             "recorded_not_measured_in_this_run": True}
+
+
+def kernel_label(kind, release, exact, ckpt=False):
+    """The step kernel's name as rocprofv3 prints it: <KIND, VEC, THREADS, DIRECT, SPLIT, QUANT, EXACT>."""
+    if ckpt:
+        return "fo::copy_kernel"
+    k = ["adamw", "sgd", "lion"].index(kind)
+    tf = lambda b: "true" if b else "false"
+    # SGD, Lion and every ablation variant are instantiated with EXACT = true (they have no division to shorten)
+    return f"fo::step_kernel<{k}, 8, {256 if k == 0 else 512}, {tf(release)}, true, true, {tf(exact or k != 0)}>"
+
+
+def time_calls(torch, stream, fn, steps, warmup=2):
+    """ms per call of fn(), HIP events on `stream` around `steps` calls after `warmup` untimed ones."""
+    for _ in range(warmup):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(steps):
+        fn()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def also_measurements(fo, W, torch, stream, specs, bufs, tl, hp, steps, t_start):
+    """The other configurations, measured after the timed region on the state that is already resident
+    (Llama list) or on small lists built here.  Each entry: what ran, ms per step, algorithmic GB/s, fraction
+    of the 8 TB/s peak, and the arithmetic-free probe of the same traffic where one exists."""
+    import types
+    out = []
+    n = sum(s.numel for s in specs)
+    t = [t_start]
+
+    def entry(name, entry_point, ms, bytes_per_step, probe_ms=None, **extra):
+        g = bytes_per_step / (ms * 1e-3) / 1e9
+        d = {"name": name, "entry_point": entry_point, "ms_per_step": ms, "achieved": g, "unit": "GB/s",
+             "frac": g / HBM_PEAK_GBPS}
+        if probe_ms:
+            pg = bytes_per_step / (probe_ms * 1e-3) / 1e9
+            d["same_traffic_without_arithmetic"] = pg
+            d["frac_of_that"] = g / pg
+        d.update(extra)
+        out.append(d)
+
+    def adamw(fn, lst):
+        def call():
+            t[0] += 1
+            fn(lst, hp["beta1"], hp["beta2"], hp["eps"], t[0])
+        return call
+
+    # the faithful entry point on the same list
+    probe_ms = time_calls(torch, stream, lambda: fo.stream_probe("adamw", tl), steps)
+    ms = time_calls(torch, stream, adamw(fo.adamw_step, tl), steps)
+    entry("llama31_8b_adamw fused, faithful division", "flashoptim_adamw_step", ms, 12.25 * n, probe_ms,
+          kernel=kernel_label("adamw", False, False))
+    # gradient release: one call per tensor in reverse order through ONE gradient buffer (the largest tensor's)
+    gbuf = max((b.grad for b in bufs), key=lambda g: g.numel())
+    singles = []
+    for i in reversed(range(len(specs))):
+        tl.set_grad(i, gbuf)
+        singles.append(tl.slice(i))
+
+    def release(fn):
+        def call():
+            t[0] += 1
+            for s1 in singles:
+                fn(s1, hp["beta1"], hp["beta2"], hp["eps"], t[0])
+        return call
+
+    ms = time_calls(torch, stream, release(fo.adamw_step_exact), steps)
+    entry("llama31_8b_adamw gradient release (291 calls per step)", "flashoptim_adamw_step_exact", ms, 12.25 * n,
+          kernel=kernel_label("adamw", True, True), resident_bytes_per_param=5.125)
+    ms = time_calls(torch, stream, release(fo.adamw_step), steps)
+    entry("llama31_8b_adamw gradient release, faithful division", "flashoptim_adamw_step", ms, 12.25 * n,
+          kernel=kernel_label("adamw", True, False), resident_bytes_per_param=5.125)
+    for i, b in enumerate(bufs):
+        tl.set_grad(i, b.grad)
+    # checkpoint gather / scatter of the whole list
+    numels = [s.numel for s in specs]
+    blob = torch.empty(fo.checkpoint_size("adamw", numels), dtype=torch.uint8, device="cuda")
+    payload = sum(5 * m + 4 * ((m + 31) // 32) for m in numels)
+    ms = time_calls(torch, stream, lambda: fo.checkpoint_pack("adamw", tl, 1, blob), steps)
+    entry("llama31_8b_adamw checkpoint pack", "flashoptim_checkpoint_pack", ms, 2.0 * payload, kernel="fo::copy_kernel")
+    ms = time_calls(torch, stream, lambda: fo.checkpoint_unpack("adamw", blob, tl), steps)
+    entry("llama31_8b_adamw checkpoint unpack", "flashoptim_checkpoint_unpack", ms, 2.0 * payload, kernel="fo::copy_kernel")
+    del blob
+    torch.cuda.empty_cache()
+    # SGD and Lion over the same list (the AdamW buffers without the variance; momentum restarted from Q(0))
+    for kind in ("sgd", "lion"):
+        h = HYPER[kind]
+        lst = []
+        for sp, b in zip(specs, bufs):
+            b.m_q.zero_(); b.m_scale.zero_()
+            lst.append(types.SimpleNamespace(param=b.param, rho=b.rho, grad=b.grad, m_q=b.m_q, m_scale=b.m_scale,
+                                             v_q=None, v_scale=None, numel=b.numel, lr=h["lr"],
+                                             weight_decay=h["wd"] if sp.role == "matrix" else 0.0))
+        tl2 = fo.TensorList(lst)
+        call = (lambda: fo.sgd_step(tl2, h["momentum"])) if kind == "sgd" else (lambda: fo.lion_step(tl2, h["beta1"], h["beta2"]))
+        ms = time_calls(torch, stream, call, steps, warmup=3)
+        probe_ms = time_calls(torch, stream, lambda: fo.stream_probe(kind, tl2), steps)
+        entry(f"llama31_8b_{kind} fused", f"flashoptim_{kind}_step", ms, 10.125 * n, probe_ms,
+              kernel=kernel_label(kind, False, True))
+    return out
+
+
+def small_list_measurements(fo, W, torch, stream, steps=200):
+    """The two small parameter lists (cache-sized: not roofline points), each beside its probe."""
+    out = []
+    for workload in ("resnet50_adamw", "gpt2_sgd", "gpt2_lion"):
+        kind, shape_fn, dist, scale = WORKLOADS[workload]
+        h = HYPER[kind]
+        specs = getattr(W, shape_fn)()
+        n = sum(s.numel for s in specs)
+        bufs = build_state(fo, W, torch, specs, kind, h, dist, scale, 0, with_grads=True)
+        tl = fo.TensorList(bufs)
+        t = [0]
+
+        def call():
+            t[0] += 1
+            step_call(fo, kind, tl, h, t[0], exact=True)
+
+        ms = time_calls(torch, stream, call, steps, warmup=10)
+        probe_ms = time_calls(torch, stream, lambda: fo.stream_probe(kind, tl), steps, warmup=10)
+        bpp = BYTES_PER_PARAM[kind]
+        g = bpp * n / (ms * 1e-3) / 1e9
+        pg = bpp * n / (probe_ms * 1e-3) / 1e9
+        out.append({"name": f"{workload} fused ({len(specs)} tensors, {n} params; cache-sized, not a roofline point)",
+                    "entry_point": "flashoptim_adamw_step_exact" if kind == "adamw" else f"flashoptim_{kind}_step",
+                    "ms_per_step": ms, "params_per_s": n / (ms * 1e-3), "achieved": g, "unit": "GB/s",
+                    "frac": g / HBM_PEAK_GBPS, "same_traffic_without_arithmetic": pg, "frac_of_that": g / pg,
+                    "kernel": kernel_label(kind, False, True)})
+        del bufs, tl
+    return out
 
 
 def main():
@@ -292,7 +452,8 @@ def main():
                       + 2 * ((s.numel + 31) // 32) * (2 if kind == "adamw" else 1) for s in specs)
         algo_bytes = 2.0 * payload                          # every payload byte is read once and written once
     achieved = algo_bytes / (ms_per_step * 1e-3) / 1e9
-    traffic = None if (release or ckpt or args.variant != "flash") else read_traffic(kind, args.workload)
+    traffic, traffic_source = (None, None) if (release or ckpt or args.variant != "flash") else \
+        read_traffic(kind, args.workload, args.rounding)
     # the memory ceiling of this access pattern: the same bytes through the same launch shape with no
     # arithmetic (fused flash mode only; run after the timed region, on the same list)
     probe = None
@@ -329,22 +490,12 @@ def main():
         clocks = {"idle": float(np.median(idle.ghz())),
                   "step": clock_during(one_more_step, ms_per_step),
                   "same_traffic_without_arithmetic": clock_during(lambda: fo.stream_probe(kind, tl), ms_per_step)}
-    # the bit-exact AdamW entry point beside the default one, same list, same number of steps
-    exact_line = None
-    if kind == "adamw" and args.variant == "flash" and args.mode == "fused" and not exact and not args.no_probe:
-        t += 1
-        fo.adamw_step_exact(tl, hp["beta1"], hp["beta2"], hp["eps"], t)
-        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        p0.record(stream)
-        for _ in range(args.steps):
-            t += 1
-            fo.adamw_step_exact(tl, hp["beta1"], hp["beta2"], hp["eps"], t)
-        p1.record(stream)
-        torch.cuda.synchronize()
-        ems = p0.elapsed_time(p1) / args.steps
-        eg = algo_bytes / (ems * 1e-3) / 1e9
-        exact_line = {"entry_point": "flashoptim_adamw_step_exact", "ms_per_step": ems, "achieved": eg,
-                      "frac": eg / HBM_PEAK_GBPS}
+    # the other configurations (default run on the headline workload only)
+    also = None
+    if (args.workload == "llama31_8b_adamw" and args.variant == "flash" and args.mode == "fused" and exact
+            and not args.no_also):
+        also = also_measurements(fo, W, torch, stream, specs, bufs, tl, hp, max(5, args.steps // 2), t + 1000)
+        also += small_list_measurements(fo, W, torch, stream)
     out = {
         "metric": "optimizer_step_params_per_sec", "value": value, "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -352,6 +503,10 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "optimizer": kind, "tensors": len(specs), "params": n_params,
                    "mode": args.mode, "variant": args.variant,
+                   "entry_point": (("flashoptim_adamw_step_exact" if exact else "flashoptim_adamw_step")
+                                   if kind == "adamw" and args.variant == "flash" and not ckpt else
+                                   (f"flashoptim_checkpoint_{args.mode[5:]}" if ckpt else
+                                    f"flashoptim_{kind}_step{'_ex' if args.variant != 'flash' else ''}")),
                    "rounding": (args.rounding if kind == "adamw" and args.variant == "flash" and not ckpt else None),
                    "calls_per_step": calls,
                    "kernel_launches_per_step": launches,
@@ -363,16 +518,18 @@ def main():
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": (traffic / launches) if (traffic and launches) else None,
                      "traffic_per_step": traffic,
-                     "kernel": ("fo::copy_kernel" if ckpt else
-                                f"fo::step_kernel<{['adamw', 'sgd', 'lion'].index(kind)}, ..., {'true' if release else 'false'}>"),
+                     "traffic_source": traffic_source,
+                     "kernel": (kernel_label(kind, release, exact, ckpt) if args.variant == "flash" else
+                                "fo::step_kernel<...> (ablation variant)"),
                      "algorithmic_bytes_per_step": algo_bytes,
                      "algorithmic_bytes_per_launch": (algo_bytes / launches) if launches else None,
                      "bytes_per_param": bytes_per_param,
                      "same_traffic_without_arithmetic": probe,
                      "frac_of_that": (achieved / probe) if probe else None,
-                     "bit_exact_entry_point": exact_line,
                      "shader_clock_ghz": clocks},
     }
+    if also is not None:
+        out["also"] = also
     if not args.no_cpu_baseline and not ckpt and args.variant == "flash":
         del bufs, tl
         torch.cuda.empty_cache()

@@ -252,7 +252,7 @@ int flashoptim_quantize_variance(const float* v, uint8_t* q, uint16_t* scale, in
 int flashoptim_dequantize_variance(const uint8_t* q, const uint16_t* scale, float* v, int64_t n, void* stream);
 
 /* ---- linear baseline and quantisation error (Section 4.5) ------------------------------
- * The paper validates its companders against "standard scaled integer quantization": the same
+ * The paper validates its companders against plain absmax-scaled integer quantisation: the same
  * group-wise FP16 absmax scale, no compander (momentum code = Round(127 m / s); variance code =
  * Round(255 v / s) with s the group maximum of v itself).
  * quantize_state / dequantize_state: state 0 = momentum (INT8 codes), 1 = variance (UINT8 codes);
@@ -307,8 +307,8 @@ const char* flashoptim_strerror(int status);
  *       exact code wherever the kernel's tie test does not ask for the exact evaluation.
  *   [5] short division == IEEE division on 2^30 + 2^24 operand pairs inside its range.
  *   [6] faithful division of flashoptim_adamw_step: within 1 ulp of the IEEE quotient on the pairs of [5].
- * n_checked, n_failed: HOST arrays of 7 counters (one per section above).  Waits for completion (about
- * 0.1 s).  Returns FLASHOPTIM_OK, FLASHOPTIM_ERR_SELFTEST if any check failed, or another status. */
+ * n_checked, n_failed: HOST arrays of 7 counters (one per section above).  Waits for completion (a
+ * fraction of a second).  Returns FLASHOPTIM_OK, FLASHOPTIM_ERR_SELFTEST if any check failed, or another status. */
 int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream);
 /* How often the faithful division differs from the exactly rounded quotient at all, measured on this device:
  * counts (HOST, 2 entries) = {operand pairs checked (2^30 + 2^24), of these not exact}.  Waits for
@@ -317,7 +317,7 @@ int flashoptim_faithful_rounding_stats(int64_t* counts, void* stream);
 /* The AdamW kernels take sqrt(v_hat) as the hardware reciprocal-square-root estimate plus one correction,
  * which is the correctly rounded root only if the estimate makes it so.  The library therefore checks every
  * FP32 value of that sequence's range, [2^-96, FLT_MAX], against sqrtf on the device before the first AdamW
- * step there (once per process and device: a kernel of about 2 ms and a wait on the caller's stream, so that
+ * step there (once per process and device: a kernel of about 4 ms on MI355X and a wait on the caller's stream, so that
  * first call must not be made under stream capture), and uses sqrtf in the kernels if the check fails or if
  * FLASHOPTIM_FORCE_GENERAL_SQRT is set to a non-zero value in the environment.  Returns the state for the
  * current device: 0 not checked yet, 1 verified (short sequence in use), 2 not in use; negative status on

@@ -132,30 +132,30 @@ inline int half_ulp_log2(uint16_t thp) {
 
 inline bool bf16_is_finite(uint16_t b) { return ((b >> 7) & 0xff) != 0xff; }
 
-// C(theta) -> (theta', rho).  Algorithm 1, first function; Eq. 1.
+// C(theta) -> (theta', rho): the encoder of Algorithm 1 (Eq. 1).
 void split_one(float theta, int N, uint16_t* thp_out, int* rho_out) {
-    uint16_t thp = bf16_rne(theta);                       // theta' <- Downcast(theta)
+    uint16_t thp = bf16_rne(theta);                       // the BF16 weight the model trains on
     *thp_out = thp;
     if (!bf16_is_finite(thp)) { *rho_out = 0; return; }   // [R-A6]
-    float e = theta - bf16_to_f32(thp);                   // e <- theta - Float32(theta')
-    int l = half_ulp_log2(thp);                           // l <- floor(log2 ULP) - 1
-    int h = floor_div2(-l);                               // h <- floor(-l/2)
-    float p1 = std::ldexp(1.0f, h);                       // 2^h, exact
-    float p2 = std::ldexp(1.0f, -l - h);                  // 2^(-l-h), exact
-    float e_norm = (e * p1) * p2;                         // (e * 2^h) * 2^(-l-h)
-    float c = e_norm;                                     // Clamp(e_norm, -1, 1)
+    float e = theta - bf16_to_f32(thp);                   // what the downcast lost (exact in FP32)
+    int l = half_ulp_log2(thp);                           // 2^l is the largest magnitude e can have
+    int h = floor_div2(-l);                               // the scaling by 2^-l is applied as two powers of
+    float p1 = std::ldexp(1.0f, h);                       // two, 2^h and 2^(-l-h), neither of which can
+    float p2 = std::ldexp(1.0f, -l - h);                  // overflow; both products are exact
+    float e_norm = (e * p1) * p2;                         // e relative to its largest magnitude, in [-1, 1]
+    float c = e_norm;                                     // (the clamp never acts on a finite theta')
     if (c < -1.0f) c = -1.0f;
     if (c > 1.0f) c = 1.0f;
-    *rho_out = (int)std::rint(c * (float)N);              // Int(Round(. * N))   [R-A3]
+    *rho_out = (int)std::rint(c * (float)N);              // N levels per side, ties to even   [R-A3]
 }
 
-// C^-1(theta', rho) -> theta_hat.  Algorithm 1, second function; Eq. 2.
+// C^-1(theta', rho) -> theta_hat: the decoder of Algorithm 1 (Eq. 2).
 float reconstruct_one(uint16_t thp, int rho, int N) {
     float base = bf16_to_f32(thp);
     if (!bf16_is_finite(thp)) return base;                // [R-A6]
     int l = half_ulp_log2(thp);
-    int h = floor_div2(l);                                // h <- floor(l/2)
-    float q = (float)rho / (float)N;                      // Float32(rho) / N
+    int h = floor_div2(l);                                // again two power-of-two factors, 2^h and 2^(l-h)
+    float q = (float)rho / (float)N;                      // the correction as a fraction of its range
     float e = (q * std::ldexp(1.0f, h)) * std::ldexp(1.0f, l - h);
     return base + e;
 }
@@ -201,41 +201,41 @@ inline uint16_t group_scale(float absmax) {
     return fp16_rne(a);
 }
 
-// Q_m on one group of cnt <= 32 values.  Algorithm 2, first function; Eq. 3.
+// Q_m on one group of cnt <= 32 values: the encoder of Algorithm 2 (Eq. 3).
 void quant_m_group(const float* m, int cnt, int8_t* q, uint16_t* scale_out) {
     float a = 0.0f;
-    for (int i = 0; i < cnt; ++i) { float t = std::fabs(m[i]); if (t > a) a = t; }  // s_g <- max|m_g|
+    for (int i = 0; i < cnt; ++i) { float t = std::fabs(m[i]); if (t > a) a = t; }  // largest magnitude of the group
     uint16_t hs = group_scale(a);
     *scale_out = hs;
     float s = fp16_to_f32(hs);
     if (s == 0.0f) { for (int i = 0; i < cnt; ++i) q[i] = 0; return; }              // [R-Q1]
     float r = 1.0f / s;                                                             // [R-Q6]
     for (int i = 0; i < cnt; ++i) {
-        float m1 = m[i] * r;                               // m' <- m / s
+        float m1 = m[i] * r;                               // normalised to [-1, 1] by the group scale
         float num = 2.0f * m1;
         float den = 1.0f + std::fabs(m1);
-        float m2 = num / den;                              // m'' <- 2m'/(1+|m'|)
-        float y = std::rint(m2 * 127.0f);                  // Round(m'' * 127)   [R-Q4]
+        float m2 = num / den;                              // the compander phi_m: finer steps near zero
+        float y = std::rint(m2 * 127.0f);                  // 127 levels per side, ties to even   [R-Q4]
         if (y > 127.0f) y = 127.0f;
         if (y < -127.0f) y = -127.0f;
         q[i] = (int8_t)(int)y;
     }
 }
 
-// Q_m^-1 on one element.  Algorithm 2, second function.
+// Q_m^-1 on one element: the decoder of Algorithm 2.
 inline float dequant_m_one(int8_t q, float s) {
-    float m2 = (float)q / 127.0f;                          // m'' <- m^q / 127
-    float m1 = m2 / (2.0f - std::fabs(m2));                // m'  <- m''/(2-|m''|)
-    return m1 * s;                                         // m   <- m' * s
+    float m2 = (float)q / 127.0f;                          // the code as a fraction of its range
+    float m1 = m2 / (2.0f - std::fabs(m2));                // phi_m inverted
+    return m1 * s;                                         // back to the group's scale
 }
 
-// Q_v on one group.  Algorithm 3, first function; Eq. 4.
+// Q_v on one group: the encoder of Algorithm 3 (Eq. 4).
 void quant_v_group(const float* v, int cnt, uint8_t* q, uint16_t* scale_out) {
     float vr[kGroup];
     float a = 0.0f;
     for (int i = 0; i < cnt; ++i) {
-        vr[i] = std::sqrt(v[i]);                           // v' <- sqrt(v)
-        if (vr[i] > a) a = vr[i];                          // s_g <- max(v'_g)
+        vr[i] = std::sqrt(v[i]);                           // the compander phi_v: the root halves the dynamic range
+        if (vr[i] > a) a = vr[i];                          // the scale is the largest root of the group
     }
     uint16_t hs = group_scale(a);
     *scale_out = hs;
@@ -243,21 +243,21 @@ void quant_v_group(const float* v, int cnt, uint8_t* q, uint16_t* scale_out) {
     if (s == 0.0f) { for (int i = 0; i < cnt; ++i) q[i] = 0; return; }  // [R-Q1]
     float r = 1.0f / s;                                                 // [R-Q6]
     for (int i = 0; i < cnt; ++i) {
-        float y = std::rint((vr[i] * r) * 255.0f);         // Round((v'/s) * 255)   [R-Q4]
+        float y = std::rint((vr[i] * r) * 255.0f);         // 255 levels, ties to even   [R-Q4]
         if (y > 255.0f) y = 255.0f;
         if (y < 0.0f) y = 0.0f;
         q[i] = (uint8_t)(int)y;
     }
 }
 
-// Q_v^-1 on one element.  Algorithm 3, second function.
+// Q_v^-1 on one element: the decoder of Algorithm 3.
 inline float dequant_v_one(uint8_t q, float s) {
-    float v1 = ((float)q / 255.0f) * s;                    // v' <- (v^q/255) * s
-    return v1 * v1;                                        // v  <- v'^2
+    float v1 = ((float)q / 255.0f) * s;                    // the root, back at the group's scale
+    return v1 * v1;                                        // phi_v inverted
 }
 
-// Linear (no companding) group quantizers: the "standard scaled integer quantization" that
-// Section 4.5 compares against.  Same scale rule [R-Q2] [R-Q3] and rounding [R-Q4]; the compander
+// Linear (no companding) group quantizers: plain absmax-scaled integer quantisation, the baseline that
+// Section 4.5 compares the companders against.  Same scale rule [R-Q2] [R-Q3] and rounding [R-Q4]; the compander
 // is dropped: momentum code = Round(127 m / s); variance code = Round(255 v / s) with s = max v.
 void quant_m_linear_group(const float* m, int cnt, int8_t* q, uint16_t* scale_out) {
     float a = 0.0f;

@@ -338,8 +338,8 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
 
 // The short square root of the AdamW kernels (reciprocal-square-root estimate plus one correction) is
 // exactly rounded on a device only if the hardware estimate makes it so; that is checked for every value of
-// its range once per process and device, before the first AdamW step there (a ~2 ms kernel and a wait on
-// the stream).  If the check fails, or FLASHOPTIM_FORCE_GENERAL_SQRT is set in the environment (for testing
+// its range once per process and device, before the first AdamW step there (a kernel of about 4 ms on MI355X
+// and a wait on the stream).  If the check fails, or FLASHOPTIM_FORCE_GENERAL_SQRT is set in the environment (for testing
 // that path), the kernels use sqrtf throughout.
 constexpr int kMaxDevices = 64;
 std::atomic<int> g_sqrt_state[kMaxDevices];      // 0 not checked, 1 verified, 2 not to be used

@@ -1331,8 +1331,8 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(uint64_t first, uint64_
     }
 }
 
-// Group quantizers written out plainly.  LINEAR drops the compander (the "standard scaled
-// integer quantization" baseline of Section 4.5): momentum code = Round(127 m / s), variance
+// Group quantizers written out plainly.  LINEAR drops the compander (the plain absmax-scaled integer
+// quantisation that Section 4.5 takes as its baseline): momentum code = Round(127 m / s), variance
 // code = Round(255 v / s) with s the group maximum of v itself.
 // quantize_lane: the eight codes of a lane and the FP16 scale bits of its group.  All four lanes of
 // a group must call it together; elements past the end are zero and do not raise the maximum.

@@ -29,14 +29,27 @@ def test_algorithmic_bytes_per_parameter():
     assert bench.variant_bytes("sgd", "ref") == 8 + 8 + 2
 
 
-def test_counter_summaries_under_profiles_parse():
+def test_counter_summaries_under_profiles_are_current():
+    # the recorded HBM traffic is reported only for the device code it was measured on: a summary whose
+    # KERNEL_SOURCE_SHA differs from the tree's is stale and fails here (re-run the counters, then commit)
     n = 8030261248
-    traffic = bench.read_traffic("adamw", "llama31_8b_adamw")
-    assert traffic is not None and 0.98 < traffic / (12.25 * n) < 1.05      # no re-reads
+    traffic, src = bench.read_traffic("adamw", "llama31_8b_adamw", "exact")
+    assert src is not None and not src.get("stale"), "profiles/adamw_step_exact_llama31_8b_adamw_pmc.txt is stale"
+    assert src["kernel_source_sha"] == bench.kernel_source_sha() and src["recorded_not_measured_in_this_run"]
+    assert 0.98 < traffic / (12.25 * n) < 1.05      # no re-reads
     for kind in ("sgd", "lion"):
-        t = bench.read_traffic(kind, f"llama31_8b_{kind}")
-        assert t is not None and 0.98 < t / (10.125 * n) < 1.05
-    assert bench.read_traffic("adamw", "no_such_workload") is None
+        t, src = bench.read_traffic(kind, f"llama31_8b_{kind}")
+        assert src is not None and not src.get("stale"), f"profiles/{kind}_step_llama31_8b_{kind}_pmc.txt is stale"
+        assert 0.98 < t / (10.125 * n) < 1.05
+    assert bench.read_traffic("adamw", "no_such_workload") == (None, None)
+
+
+def test_kernel_label_names_the_real_template_arguments():
+    # <KIND, VEC, THREADS, DIRECT, SPLIT, QUANT, EXACT>, as rocprofv3 prints the kernel
+    assert bench.kernel_label("adamw", False, True) == "fo::step_kernel<0, 8, 256, false, true, true, true>"
+    assert bench.kernel_label("adamw", True, False) == "fo::step_kernel<0, 8, 256, true, true, true, false>"
+    assert bench.kernel_label("lion", False, False) == "fo::step_kernel<2, 8, 512, false, true, true, true>"
+    assert bench.kernel_label("adamw", False, True, ckpt=True) == "fo::copy_kernel"
 
 
 @pytest.mark.skipif(os.path.exists("/dev/kfd"), reason="a GPU is present")

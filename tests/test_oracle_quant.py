@@ -299,3 +299,59 @@ def test_codes_round_exact_ties_to_even():
         q, s = oracle.quantize_variance(grp)
         assert s[0] == 0x3C00 and q[0] == 255
         assert list(q[1:]) == want_v[i:i + 31]
+
+
+def test_reciprocal_reading_against_literal_division():
+    # Reading Q6: a division by a per-group scale s (Algorithms 2 and 3) or by a bias correction 1 - beta^t
+    # (Algorithm 4) is taken as a multiplication by the correctly rounded FP32 reciprocal.  Both the oracle and the
+    # GPU follow it, so their comparison cannot see how far it is from the literal division.  This test measures
+    # that: the literal form is evaluated here in FP32 (numpy, one rounded operation at a time) for every positive
+    # FP16 scale and a sweep of values per scale, and its 8-bit codes are compared with the oracle's.
+    f = np.float32
+    scales = oracle.fp16_to_f32(_all_positive_fp16())
+    scales = scales[scales >= 2.0 ** -24 * 8]                  # at least 3 significant bits in the scale
+    rng = np.random.default_rng(5)
+    n_codes = n_m_diff = n_v_diff = 0
+    max_m = max_v = 0
+    for chunk in np.array_split(np.tile(scales, 8), 128):
+        # a group per scale (eight different groups for every scale in all): the scale itself (so that the group's stored scale is exactly s) plus 31 fractions of it
+        u = rng.uniform(-1.0, 1.0, size=(chunk.size, 32)).astype(np.float32)
+        u[:, 0] = 1.0
+        m = (u * chunk[:, None]).astype(np.float32)
+        q_m, s_m = oracle.quantize_momentum(m.ravel())
+        assert np.array_equal(oracle.fp16_to_f32(s_m), chunk)
+        m1 = (m / chunk[:, None]).astype(np.float32)                                   # literal m / s
+        m2 = ((f(2.0) * m1).astype(np.float32) / (f(1.0) + np.abs(m1)).astype(np.float32)).astype(np.float32)
+        lit_m = np.clip(np.rint((m2 * f(127.0)).astype(np.float32)), -127, 127).astype(np.int8)
+        d = np.abs(lit_m.astype(np.int32).ravel() - q_m.astype(np.int32))
+        n_m_diff += int((d != 0).sum()); max_m = max(max_m, int(d.max()))
+        v = (m * m).astype(np.float32)                          # sqrt(v) = |m| up to rounding: group maximum close to s
+        q_v, s_v = oracle.quantize_variance(v.ravel())
+        sv = oracle.fp16_to_f32(s_v)[:, None]
+        ok = sv[:, 0] > 0
+        vr = np.sqrt(v, dtype=np.float32)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            lit_v = np.clip(np.rint(((vr / sv).astype(np.float32) * f(255.0)).astype(np.float32)), 0, 255)
+        lit_v = np.where(ok[:, None], lit_v, 0).astype(np.uint8)
+        d = np.abs(lit_v.astype(np.int32).ravel() - q_v.astype(np.int32))
+        n_v_diff += int((d != 0).sum()); max_v = max(max_v, int(d.max()))
+        n_codes += m.size
+    rate_m, rate_v = n_m_diff / n_codes, n_v_diff / n_codes
+    print(f"literal division vs reciprocal reading over {n_codes} values (256 for each of {scales.size} FP16 scales): "
+          f"momentum codes differ on {n_m_diff} ({rate_m:.2e}), variance codes on {n_v_diff} ({rate_v:.2e})")
+    # the two forms differ by at most one ulp of m', far below a code step: a code can change only where the
+    # argument of Round() sits on a tie to within that ulp, and then by one unit
+    assert max_m <= 1 and max_v <= 1
+    assert rate_m < 2e-4 and rate_v < 2e-4
+    # bias correction: x / bc against x * (1 / bc) in FP32 - how often the quotient itself differs (by one ulp)
+    x = rng.standard_normal(1 << 22).astype(np.float32) * f(1e-4)
+    worst = 0.0
+    for beta, t in ((0.9, 1), (0.9, 7), (0.999, 1), (0.999, 10), (0.999, 1000), (0.99, 100)):
+        bc = f(1.0 - beta ** t)
+        lit = (x / bc).astype(np.float32)
+        rec = (x * (f(1.0) / bc)).astype(np.float32)
+        ulps = np.abs(lit.view(np.int32).astype(np.int64) - rec.view(np.int32).astype(np.int64))
+        assert ulps.max() <= 1
+        worst = max(worst, float((ulps != 0).mean()))
+    print(f"bias correction, literal division vs reciprocal: quotients differ (by one ulp) on up to {worst:.1%} of values")
+    assert worst < 0.5
