@@ -383,6 +383,15 @@ int short_sqrt_verified(hipStream_t stream, bool* verified) {
     return FLASHOPTIM_OK;
 }
 
+// Operand limits of the short square root and division of the AdamW kernels for this call (StepConsts).
+void set_ranges(StepConsts& c, bool short_sqrt_verified) {
+    c.sqrt_min = short_sqrt_verified ? 1.2621774483536189e-29f /* 2^-96 */ : INFINITY;
+    const bool eps_ok = c.eps >= fo::kDivFastLo && c.eps <= 1.0f;
+    const double slack = 1.0 - 1.0 / 1048576.0;       // the limits are rounded to FP32: stay below the exact quotient
+    c.v_max = eps_ok ? (float)((double)fo::kDivFastHi / (double)c.rbc2 * slack) : -1.0f;
+    c.m_max = eps_ok ? (float)((double)fo::kDivFastHi / (double)c.rbc1 * slack) : -1.0f;
+}
+
 int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, const StepConsts& c, void* stream_,
              LiveOp op = kOpStep) {
     const bool has_v = (kind == FLASHOPTIM_ADAMW);
@@ -402,8 +411,7 @@ int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, cons
         bool verified = false;
         rc = short_sqrt_verified(static_cast<hipStream_t>(stream_), &verified);
         if (rc != FLASHOPTIM_OK) return rc;
-        cc.sqrt_min = verified ? 1.2621774483536189e-29f /* 2^-96 */ : INFINITY;
-        cc.div_max = (cc.eps >= fo::kDivFastLo && cc.eps <= 1.0f) ? fo::kDivFastHi : -1.0f;
+        set_ranges(cc, verified);
     }
     return launch_live(kind, true, true, live, cc, static_cast<hipStream_t>(stream_), op);
 }
@@ -449,8 +457,7 @@ int run_step_ex(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors
         bool verified = false;
         rc = short_sqrt_verified(static_cast<hipStream_t>(stream_), &verified);
         if (rc != FLASHOPTIM_OK) return rc;
-        cc.sqrt_min = verified ? 1.2621774483536189e-29f /* 2^-96 */ : INFINITY;
-        cc.div_max = (cc.eps >= fo::kDivFastLo && cc.eps <= 1.0f) ? fo::kDivFastHi : -1.0f;
+        set_ranges(cc, verified);
     }
     // the ablation and reference variants always use the exactly rounded arithmetic
     return launch_live(kind, split, quant, live, cc, static_cast<hipStream_t>(stream_), kOpStepExact);
@@ -627,6 +634,13 @@ __global__ __launch_bounds__(256) void noalloc_fill_coarse(const TensorDev* tabl
 
 extern "C" {
 
+// 255 * sqrt(1 / rbc2), evaluated in double and handed to the kernels as two floats.
+static void set_k255(StepConsts& c) {
+    const double k = 255.0 * std::sqrt(1.0 / (double)c.rbc2);
+    c.k255_hi = (float)k;
+    c.k255_lo = (float)(k - (double)c.k255_hi);
+}
+
 static bool adamw_consts(const flashoptim_adamw_hp* hp, StepConsts& c) {
     if (!hp || hp->step < 1) return false;
     std::memset(&c, 0, sizeof(c));
@@ -635,7 +649,7 @@ static bool adamw_consts(const flashoptim_adamw_hp* hp, StepConsts& c) {
     c.rbc1 = recip_bias_correction(hp->beta1, hp->step);
     c.rbc2 = recip_bias_correction(hp->beta2, hp->step);
     c.eps = hp->eps;
-    c.root_bc2 = (float)std::sqrt(1.0 / (double)c.rbc2);
+    set_k255(c);
     return true;
 }
 static bool sgd_consts(const flashoptim_sgd_hp* hp, StepConsts& c) {
@@ -932,7 +946,7 @@ static int run_selftest(unsigned long long (&h)[fo::kSelftestCounters], bool onl
     if (!only_faithful) {
         for (int section = 0; section < 4 && e == hipSuccess; ++section) e = fo::launch_selftest(d, section, c, 1.0f, stream);
         if (e == hipSuccess) e = fo::launch_selftest(d, 5, c, 1.0f, stream);
-        // variance codes: the estimate depends on the call's bias correction through (rbc2, root_bc2), so
+        // variance codes: the estimate depends on the call's bias correction (rbc2 and the constant derived from it), so
         // the section runs with the pairs of steps 1..20 and of a log-spaced set up to 10^6, for four
         // values of beta2, each with three group scales
         const float beta2s[4] = {0.95f, 0.99f, 0.999f, 0.9999f};
@@ -940,7 +954,7 @@ static int run_selftest(unsigned long long (&h)[fo::kSelftestCounters], bool onl
         for (int b = 0; b < 4 && e == hipSuccess; ++b) {
             for (int i = 0; i < fo::kSelftestVarSteps && e == hipSuccess; ++i) {
                 c.rbc2 = recip_bias_correction(beta2s[b], fo::selftest_var_step(i));
-                c.root_bc2 = (float)std::sqrt(1.0 / (double)c.rbc2);
+                set_k255(c);
                 for (int k = 0; k < 3 && e == hipSuccess; ++k) e = fo::launch_selftest(d, 4, c, 1.0f / scales[k], stream);
             }
         }
@@ -1041,8 +1055,7 @@ int flashoptim_adamw_step_noalloc(const flashoptim_tensor* tensors, int64_t n_te
     // the short square root only where an earlier call has verified it on this device (that check allocates
     // and waits, so it is not run from here); sqrtf otherwise: same results
     const bool verified = dev >= 0 && dev < kMaxDevices && g_sqrt_state[dev].load(std::memory_order_acquire) == 1;
-    c.sqrt_min = verified ? 1.2621774483536189e-29f /* 2^-96 */ : INFINITY;
-    c.div_max = (c.eps >= fo::kDivFastLo && c.eps <= 1.0f) ? fo::kDivFastHi : -1.0f;
+    set_ranges(c, verified);
     StepArgs a;
     std::memset(&a, 0, sizeof(a));
     a.c = c;

@@ -61,11 +61,12 @@ struct StepConsts {
     float omb1, omb2;     // 1.0f - beta (FP32 subtraction)
     float rbc1, rbc2;     // 1.0f / (float)(1 - beta^t), AdamW only
     float eps;
-    float root_bc2;       // (float)sqrt(1 / (double)rbc2): used only to pre-estimate variance codes
-    float div_max;        // largest operand given to the short division: 2^60, or -1 when eps is outside [2^-60, 1]
-                          // (the kernels then use the IEEE division throughout)
-    float sqrt_min;       // smallest argument given to the short square root: 2^-96, or +inf when that sequence
-                          // has not passed its check on this device (the kernels then use sqrtf throughout)
+    float k255_hi, k255_lo;   // 255 * sqrt(1 / rbc2) in double, as two floats: used only to pre-estimate variance codes
+    float v_max, m_max;   // largest v_t and |m_t| for which the short square root and division serve: 2^60 / rbc2 and
+                          // 2^60 / rbc1 rounded down, or -1 when eps is outside [2^-60, 1] (the kernels then use
+                          // sqrtf and the IEEE division throughout)
+    float sqrt_min;       // smallest v_t for the same: 2^-96, or +inf when the short square root has not passed its
+                          // check on this device
 };
 
 // A multi-tensor launch maps workgroup b to (tensor, tile) in two steps: coarse[b >> coarse_shift] is

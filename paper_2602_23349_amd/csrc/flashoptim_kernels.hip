@@ -177,15 +177,6 @@ __device__ __forceinline__ float sqrt_rn_midrange(float x) {
     const float s = x * y, h = 0.5f * y;
     return fmaf(fmaf(-s, s, x), h, s);
 }
-// Wave-uniform range test: true when some lane holds a value between lo and hi (lo <= hi) outside the
-// range of sqrt_rn_midrange, or a NaN.  lower_limit is kSqrtFastMin, or +inf from the host when the
-// sequence is not to be used on this device.  (One ballot per comparison: a ballot of a combined
-// condition costs two more vector instructions.)
-__device__ __forceinline__ bool any_lane(bool p);
-__device__ __forceinline__ bool sqrt_out_of_range(float lo, float hi, float lower_limit) {
-    return any_lane(!(lo >= lower_limit)) | any_lane(!(hi <= kSqrtFastMax));
-}
-
 // Correctly rounded n / d for operands well inside the normal range: 2^-60 <= |n|, d <= 2^60.
 // This is the usual refinement of the 1-ulp hardware reciprocal (one Newton step on the
 // reciprocal, two residual corrections of the quotient, every step one FMA); with the operands
@@ -257,14 +248,14 @@ __device__ __forceinline__ uint32_t v_code_exact_midrange(float v, float r) {
 }
 
 // The same code decided from root_hat = sqrt(v * rbc2) (exactly rounded, already computed for the update)
-// and kr255 = ((sqrt(1/rbc2) rounded) * r) * 255.  Relative errors of y* = root_hat * kr255 against the
-// exact y, in units of 2^-24: v*rbc2 (1/2 after the root), the root (1), sqrt(1/rbc2) as held in FP32 (1 for
-// its own rounding, 1/2 for rbc2's), the two products inside kr255 (2), against the three roundings of
-// the exact chain (3): 8 * 2^-24 * 255 < 1.22e-4 in y.  The function returns y* -+ w, each ONE fused
-// multiply-add (rounding: half an ulp of a value below 256, 7.7e-6): if both round to the same integer no
-// rounding tie lies within 1.7e-4 of y*, and that integer is the exact code.  The conversion's saturation
-// at 255 is the clamp of Algorithm 3.
-constexpr float kTieWindowV = 1.8e-4f;
+// and kr255 = 255 * sqrt(1 / rbc2) * r, formed per group to within one rounding (the host passes the constant
+// in two halves).  Relative errors of y* = root_hat * kr255 against the exact argument y of Round(), in units
+// of 2^-24: the rounding of v * rbc2 (1/2 after the root), of the root (1), of kr255 (1), against the three
+// roundings of the exact chain sqrt, * r, * 255 (3): 5.5 * 2^-24 * 255.5 < 8.4e-5 in y below the saturation
+// point.  The function returns y* -+ w, each ONE fused multiply-add (rounding: half an ulp of a value below
+// 256, 7.7e-6): if both round to the same integer no rounding tie lies within 9.2e-5 of y*, and that integer
+// is the exact code.  The conversion's saturation at 255 is the clamp of Algorithm 3.
+constexpr float kTieWindowV = 1.0e-4f;
 __device__ __forceinline__ void v_code_bracket(float root_hat, float kr255, float* lo, float* hi) {
     *lo = fmaf(root_hat, kr255, -kTieWindowV);
     *hi = fmaf(root_hat, kr255, kTieWindowV);
@@ -688,6 +679,7 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
     float tha[VEC];   // AdamW: master weights, held until the range tests below are known
     float amax_m = 0.0f, amax_v = 0.0f;
     float amin_m = 3.0e38f, amin_v = 3.0e38f;     // AdamW: smallest |m_t| and v_t of the lane
+    bool fast = false;                            // AdamW: the wavefront takes the short square root and division
 
 #pragma unroll
     for (int j = 0; j < VEC / 4; ++j) {
@@ -750,20 +742,18 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
         if (KIND != 0) split_block<VEC, SPLIT>(y, tab, tht, j);
     }
     if (KIND == 0) {
-        // Range tests for the short square root and division, once per lane.  Multiplying by a
-        // positive constant and rounding is monotone, so the extreme bias-corrected values of the
-        // lane are the products of the extreme raw values: no separate running extremes are needed.
-        const float vmin = amin_v * c.rbc2, vmax = amax_v * c.rbc2;
-        const float nmin = amin_m * c.rbc1, nmax = amax_m * c.rbc1;
-        // sqrt(v_hat): the short sequence unless some lane holds a value outside its range (below
-        // 2^-96 - exact zeros included - or not finite)
-        const bool sqrt_general = sqrt_out_of_range(vmin, vmax, c.sqrt_min);
-        // m_hat / (sqrt(v_hat) + eps): the short division when every operand of the lane is well
-        // inside the normal range (eps <= den <= sqrt(v_hat max) + eps), else the general one.
-        // c.div_max is 2^60, or -1 from the host when eps is outside [2^-60, 1]: every test then fails.
-        // (The faithful division has no lower limit on the numerator.)
-        const bool div_fast = !(any_lane(!(nmax <= c.div_max)) | any_lane(!(vmax <= c.div_max)) |
-                                (EXACT ? any_lane(!(nmin >= kDivFastLo)) : false));
+        // One wave-uniform range test, on the raw extremes of every lane, selects the short square root
+        // and the short division for the whole wavefront (else sqrtf and the IEEE division throughout: same
+        // results).  The bias corrections rbc1, rbc2 are at least 1 and multiplying by them is monotone, so
+        //   v_t >= 2^-96 for every element   =>  v_hat, and v_t itself, are in the short square root's range;
+        //   v_t <= c.v_max (2^60 / rbc2, rounded down)   =>  v_hat <= 2^60: finite, and sqrt(v_hat) + eps is a
+        //                                                    denominator well inside the normal range;
+        //   |m_t| <= c.m_max (2^60 / rbc1, rounded down) and, for the correctly rounded division only,
+        //   |m_t| >= 2^-60   =>  the numerator m_hat is in the short division's range.
+        // The host sets v_max = m_max = -1 when eps is outside [2^-60, 1], and sqrt_min = +inf when the short
+        // square root is not to be used on this device: every test then fails.  Exact zeros fail it too.
+        fast = !(any_lane(!(amax_v <= c.v_max)) | any_lane(!(amin_v >= c.sqrt_min)) |
+                 any_lane(!(amax_m <= c.m_max)) | (EXACT ? any_lane(!(amin_m >= kDivFastLo)) : false));
 #pragma unroll
         for (int j = 0; j < VEC / 4; ++j) {
             float mh4[4], vh4[4], quo[4], tht[4];
@@ -772,14 +762,14 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
                 mh4[k] = mt[4 * j + k] * c.rbc1;
                 vh4[k] = vt[4 * j + k] * c.rbc2;
             }
-            if (sqrt_general) {
+            if (!fast) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrtf(vh4[k]);
             } else {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) rh[4 * j + k] = sqrt_rn_midrange(vh4[k]);
             }
-            if (!div_fast) {
+            if (!fast) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) quo[k] = mh4[k] / (rh[4 * j + k] + c.eps);
             } else if (EXACT) {
@@ -811,19 +801,17 @@ __device__ __forceinline__ void update_lane(const LaneIO<VEC>& x, LaneIO<VEC>& y
     // is monotone, so the group maximum of sqrt(v) is the square root of the maximum of v.
     amax_m = group_max<VEC>(amax_m);
     float r_m, r_v = 0.0f, kr255 = 0.0f;
-    bool amax_v_not_finite = false;     // wave-uniform
     y.ms = group_scale_fast(amax_m, &r_m);
     if (HAS_V) {
+        // the group's maximum lies between the extremes of the wavefront's lanes: in the short root's range if they are
         amax_v = group_max<VEC>(amax_v);
-        amax_v_not_finite = any_lane(!(amax_v <= kSqrtFastMax));
-        const bool root_max_general = any_lane(!(amax_v >= c.sqrt_min)) | amax_v_not_finite;
-        const float root_max = root_max_general ? sqrtf(amax_v) : sqrt_rn_midrange(amax_v);
+        const float root_max = fast ? sqrt_rn_midrange(amax_v) : sqrtf(amax_v);
         y.vs = group_scale_fast(root_max, &r_v);
-        kr255 = (c.root_bc2 * r_v) * 255.0f;
+        // 255 * sqrt(1 / rbc2) * r_v to within one rounding: the constant comes from the host as the two halves of
+        // its double-precision value
+        kr255 = fmaf(c.k255_hi, r_v, c.k255_lo * r_v);
     }
-
-    // amax_v is the group's here, which is at least the lane's
-    const bool vt_root_general = HAS_V && (any_lane(!(amin_v >= c.sqrt_min)) | amax_v_not_finite);
+    const bool vt_root_general = !fast;
     // epilogue: state codes, four at a time (one word of each code stream).  Each code is converted
     // twice, from the two ends of an interval that contains the exact argument of Round(); where the
     // two words differ some element of the block may sit on the other side of a rounding tie, and the
@@ -1686,7 +1674,7 @@ __device__ __forceinline__ void selftest_one(int section, uint64_t gid, const St
             const uint32_t ebits = (k == 0 ? 97u : k == 1 ? 98u : k == 2 ? 116u : 117u) << 23;
             const float v = u2f(ebits | mant);
             const float root_hat = sqrtf(v * c.rbc2);
-            const float kr255 = (c.root_bc2 * scale_r) * 255.0f;
+            const float kr255 = fmaf(c.k255_hi, scale_r, c.k255_lo * scale_r);
             float lo, hi;
             v_code_bracket(root_hat, kr255, &lo, &hi);
             const uint32_t a = put_u8(lo, 0, 0), b = put_u8(hi, 0, 0);
