@@ -196,6 +196,57 @@ def test_zero_variance_with_live_momentum_and_small_eps(eps, mode):
         assert sum(r[1] for r in rep) == 0
 
 
+@pytest.mark.parametrize("mode", ADAMW_MODES)
+@pytest.mark.parametrize("scenario", ["v_hat around 2^60", "m_hat around 2^60", "tiny momentum under a live variance",
+                                      "eps below 2^-60", "eps above 1", "mixed wavefronts"])
+def test_operand_range_boundaries_of_the_short_sequences(scenario, mode):
+    # The AdamW kernels take a short square root and a short division when one wave-uniform test finds every
+    # operand of the wavefront inside their ranges (v_t in [2^-96, 2^60 / rbc2], |m_t| <= 2^60 / rbc1 and, for the
+    # correctly rounded division, >= 2^-60; eps in [2^-60, 1]), and the general sequences otherwise.  Both must
+    # give the oracle's bits: inputs on either side of each limit, alone and mixed within wavefronts.
+    n = 2048 * 4 + 160
+    rng = np.random.default_rng(len(scenario))
+    rs = W.random_state(n, 3, seed=33, with_variance=True)
+    st = oracle.TensorState(np.zeros(n, np.float32), "adamw")
+    st.thp = bits16(rs["thp"]); st.rho = rs["rho"].numpy().copy()
+    st.mq = rs["mq"].numpy().copy(); st.ms = bits16(rs["ms"])
+    st.vq = rs["vq"].numpy().copy(); st.vs = bits16(rs["vs"])
+    finite = np.isfinite(oracle.bf16_to_f32(st.thp))
+    st.thp[~finite] = 0x3f80
+    eps, lr = 1e-8, 1e-12                                 # a tiny learning rate keeps the weights finite
+    g = (rng.standard_normal(n) * 1e-4).astype(np.float32)
+    if scenario == "v_hat around 2^60":
+        st.mq[:] = 0; st.vq[:] = 0                         # t = 1 from Q(0): v_hat = g^2 up to rounding
+        g = (2.0 ** 30 * 10.0 ** rng.uniform(-0.3, 0.3, n) * rng.choice([-1.0, 1.0], n)).astype(np.float32)
+    elif scenario == "m_hat around 2^60":
+        st.mq[:] = 0; st.vq[:] = 0                         # m_hat = g; g^2 ~ 1e36 stays finite
+        g = (2.0 ** 60 * 10.0 ** rng.uniform(-0.3, 0.3, n) * rng.choice([-1.0, 1.0], n)).astype(np.float32)
+    elif scenario == "tiny momentum under a live variance":
+        st.mq[:] = 0                                       # m_t = (1 - beta1) g below 2^-60, v_t = beta2 v well above 2^-96
+        st.vq[st.vq == 0] = 1                              # (every element: a zero variance would send the wavefront
+        st.vs[st.vs == 0] = 0x1400                         #  to the general sequences on its own)
+        g = (2.0 ** -58 * 10.0 ** rng.uniform(-1.5, 0.5, n)).astype(np.float32)
+    elif scenario == "eps below 2^-60":
+        eps = 1e-20
+    elif scenario == "eps above 1":
+        eps = 2.5
+    else:
+        # ordinary values with, here and there, one element beyond a limit: the wavefronts that hold one take the
+        # general sequences, their neighbours the short ones
+        for pos, val in ((5, 3.0e9), (700, -1.0e19), (1500, 1e-30), (2049, 0.0), (4100, 2.0e18), (8200, -4.0e9)):
+            g[pos] = val
+    gb = torch.from_numpy(g).to(torch.bfloat16)
+    buf = upload_state(st)
+    buf.lr, buf.weight_decay = lr, 0.01
+    buf.grad.copy_(gb.cuda())
+    tl = fo.TensorList([buf])
+    for t in (1, 2):
+        adamw_step_fn(mode)(tl, 0.9, 0.999, eps, t)
+        oracle.adamw_step(st, _g_bits(gb), lr, 0.01, 0.9, 0.999, eps, t)
+        rep = compare_state(download(buf), st, where=f"{scenario} {mode} t={t}")
+        assert sum(r[1] for r in rep) == 0
+
+
 @pytest.mark.parametrize("kind,hp", [("adamw", ADAMW), ("sgd", SGD), ("lion", LION)])
 def test_zero_element_tensors_and_empty_lists(kind, hp):
     # tensors without elements are skipped wherever they stand in the list; a list of nothing is a no-op
