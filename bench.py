@@ -296,6 +296,42 @@ def also_measurements(fo, W, torch, stream, specs, bufs, tl, hp, steps, t_start)
     ms = time_calls(torch, stream, release(fo.adamw_step), steps)
     entry("llama31_8b_adamw gradient release, faithful division", "flashoptim_adamw_step", ms, 12.25 * n,
           kernel=kernel_label("adamw", True, False), resident_bytes_per_param=5.125)
+    # the same with one call per decoder layer (its 9 tensors as one list; embedding, and final norm + head, apart):
+    # 34 calls per step, the layer's gradients carved out of the same single buffer
+    groups, cur = [], []
+    for i, sp in enumerate(specs):
+        layer = sp.name.split(".")[1] if sp.name.startswith("layers.") else sp.name.split(".")[0]
+        if cur and cur[0][0] != layer and not (cur[0][0] == "norm" and layer == "lm_head"):
+            groups.append([j for _, j in cur]); cur = []
+        cur.append((layer, i))
+    groups.append([j for _, j in cur])
+    layer_lists = []
+    need = max(sum((bufs[j].numel + 255) // 256 * 256 for j in g) for g in groups)
+    glayer = torch.empty(need, dtype=gbuf.dtype, device=gbuf.device)      # one buffer for a whole layer's gradients
+    glayer[:gbuf.numel()].copy_(gbuf[:min(need, gbuf.numel())])
+    if need > gbuf.numel():
+        glayer[gbuf.numel():].copy_(gbuf[:need - gbuf.numel()])
+    for idx in reversed(groups):
+        off, lst = 0, []
+        for j in idx:
+            b = bufs[j]
+            lst.append(types.SimpleNamespace(param=b.param, rho=b.rho, grad=glayer[off:off + b.numel], m_q=b.m_q,
+                                             m_scale=b.m_scale, v_q=b.v_q, v_scale=b.v_scale, numel=b.numel, lr=b.lr,
+                                             weight_decay=b.weight_decay))
+            off += (b.numel + 255) // 256 * 256
+        assert off <= glayer.numel()
+        layer_lists.append(fo.TensorList(lst))
+
+    def release_by_layer():
+        t[0] += 1
+        for l1 in layer_lists:
+            fo.adamw_step_exact(l1, hp["beta1"], hp["beta2"], hp["eps"], t[0])
+
+    ms = time_calls(torch, stream, release_by_layer, steps)
+    entry(f"llama31_8b_adamw gradient release by layer ({len(layer_lists)} calls per step)", "flashoptim_adamw_step_exact",
+          ms, 12.25 * n, kernel=kernel_label("adamw", False, True),
+          resident_bytes_per_param=5.125 + 2.0 * max(sum(bufs[j].numel for j in g) for g in groups) / n)
+    del layer_lists, glayer
     for i, b in enumerate(bufs):
         tl.set_grad(i, b.grad)
     # checkpoint gather / scatter of the whole list
@@ -327,9 +363,10 @@ def also_measurements(fo, W, torch, stream, specs, bufs, tl, hp, steps, t_start)
 
 
 def small_list_measurements(fo, W, torch, stream, steps=200):
-    """The two small parameter lists (cache-sized: not roofline points), each beside its probe."""
+    """The small workloads (cache-sized: not roofline points), each beside its probe: the flat 2^20-element tensor,
+    the ResNet-50 list and the GPT-2 list."""
     out = []
-    for workload in ("resnet50_adamw", "gpt2_sgd", "gpt2_lion"):
+    for workload in ("flat_adamw", "resnet50_adamw", "gpt2_sgd", "gpt2_lion"):
         kind, shape_fn, dist, scale = WORKLOADS[workload]
         h = HYPER[kind]
         specs = getattr(W, shape_fn)()
