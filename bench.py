@@ -388,7 +388,7 @@ def small_list_measurements(fo, W, torch, stream, steps=200):
                     "entry_point": "flashoptim_adamw_step_exact" if kind == "adamw" else f"flashoptim_{kind}_step",
                     "ms_per_step": ms, "params_per_s": n / (ms * 1e-3), "achieved": g, "unit": "GB/s",
                     "frac": g / HBM_PEAK_GBPS, "same_traffic_without_arithmetic": pg, "frac_of_that": g / pg,
-                    "kernel": kernel_label(kind, False, True)})
+                    "kernel": kernel_label(kind, len(specs) == 1, True)})
         del bufs, tl
     return out
 
