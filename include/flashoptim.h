@@ -135,6 +135,8 @@ int flashoptim_lion_step(const flashoptim_tensor* tensors, int64_t n_tensors,
  * (no hipMalloc / hipFree / hipHostMalloc, no host-to-device copy): the two device tables of a multi-tensor
  * launch are written by small kernels, from kernel arguments, into a fixed 172,032-byte device array that
  * each GPU holds from library load to process end.
+ * Every table entry a call's launches read is written by that call first, so nothing left behind by an earlier
+ * call (a longer list, larger tensors) is ever seen.
  * Limits: at most 1024 tensors with numel > 0 (FLASHOPTIM_ERR_LIST_TOO_LONG beyond that, nothing enqueued) and,
  * as for every step call, at most 2^31 - 1 workgroups.  Every call on a GPU shares that GPU's array: calls on
  * the same stream are ordered and safe; calls that may overlap on one GPU (different streams, several host
