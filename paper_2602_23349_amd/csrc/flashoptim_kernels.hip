@@ -372,7 +372,9 @@ __device__ __forceinline__ float reconstruct_lds(const DecodeTables& t, uint32_t
 __device__ __forceinline__ uint32_t rho_bits_lds(const DecodeTables& t, float theta, uint32_t b16, uint32_t E) {
     const float e = theta - u2f(b16 << 16);
     const float2 sc = t.split[E];
-    return round_to_int_bits((e * sc.x) * sc.y);
+    // (e * sc.x) * sc.y is exact, so adding the rounding constant inside one fused multiply-add rounds the same
+    // value as Round() of the product would
+    return f2u(fmaf(e * sc.x, sc.y, 12582912.0f));
 }
 
 // -------------------------------------------------------------- lane vectors --
