@@ -152,3 +152,20 @@ def test_step_launch_count_is_one_launch_per_2_to_28_elements_of_whole_tiles():
     L = fo.load_library()
     assert L.flashoptim_step_launch_count(3, None, 0) == -1
     assert L.flashoptim_step_launch_count(0, (C.c_int64 * 1)(-5), 1) == -3
+
+
+def test_shard_range_arithmetic():
+    # even split on multiples of 256, sizes differ by at most one unit, ragged end on the last non-empty shard
+    for numel, world in ((0, 4), (1, 4), (255, 2), (256, 2), (257, 2), (1_000_037, 7), (1_000_037, 64), (8_030_261_248, 8), (1000, 16)):
+        pieces = [fo.shard_range(numel, world, r) for r in range(world)]
+        assert pieces[0][0] == 0 and sum(l for _, l in pieces) == numel
+        for (b0, l0), (b1, _) in zip(pieces, pieces[1:]):
+            assert b1 == b0 + l0
+        sizes = [l for _, l in pieces if l]
+        assert all(b % 256 == 0 for b, l in pieces if l)
+        assert all(l % 256 == 0 for l in sizes[:-1])
+        if sizes:
+            assert max(sizes) - min(sizes[:-1] or sizes) <= 256
+    for bad in ((10, 0, 0), (10, 2, 2), (10, 2, -1), (-1, 2, 0)):
+        with pytest.raises(fo.FlashOptimError):
+            fo.shard_range(*bad)
