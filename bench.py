@@ -362,6 +362,33 @@ def also_measurements(fo, W, torch, stream, specs, bufs, tl, hp, steps, t_start)
     return out
 
 
+def ablation_measurements(fo, W, torch, stream, specs, steps):
+    """The paper's two ablations and the plain FP32 optimizer (Section 4.3) over the Llama list, through the same
+    multi-tensor machinery: what the compressed layout buys on this chip.  Each variant builds its own state."""
+    out = []
+    kind, hp = "adamw", HYPER["adamw"]
+    n = sum(s.numel for s in specs)
+    names = {"wsplit": "weight split only (FP32 states)", "oquant": "state quantisation only (FP32 weights)",
+             "ref": "plain FP32 AdamW with BF16 gradients"}
+    for variant in ("wsplit", "oquant", "ref"):
+        bufs = build_state(fo, W, torch, specs, kind, hp, "normal", 1e-4, 0, with_grads=True, variant=variant)
+        tl = fo.TensorListEx(bufs)
+        t = [0]
+
+        def call():
+            t[0] += 1
+            fo.adamw_step_ex(tl, hp["beta1"], hp["beta2"], hp["eps"], t[0])
+
+        ms = time_calls(torch, stream, call, steps, warmup=2)
+        bpp = variant_bytes(kind, variant)
+        g = bpp * n / (ms * 1e-3) / 1e9
+        out.append({"name": f"llama31_8b_adamw fused, {names[variant]}", "entry_point": "flashoptim_adamw_step_ex",
+                    "ms_per_step": ms, "bytes_per_param": bpp, "achieved": g, "unit": "GB/s", "frac": g / HBM_PEAK_GBPS})
+        del bufs, tl
+        torch.cuda.empty_cache()
+    return out
+
+
 def small_list_measurements(fo, W, torch, stream, steps=200):
     """The small workloads (cache-sized: not roofline points), each beside its probe: the flat 2^20-element tensor,
     the ResNet-50 list and the GPT-2 list."""
@@ -533,6 +560,10 @@ def main():
             and not args.no_also):
         also = also_measurements(fo, W, torch, stream, specs, bufs, tl, hp, max(5, args.steps // 2), t + 1000)
         also += small_list_measurements(fo, W, torch, stream)
+        del bufs, tl
+        bufs = tl = None
+        torch.cuda.empty_cache()
+        also += ablation_measurements(fo, W, torch, stream, specs, max(5, args.steps // 2))
     out = {
         "metric": "optimizer_step_params_per_sec", "value": value, "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
