@@ -296,6 +296,31 @@ def also_measurements(fo, W, torch, stream, specs, bufs, tl, hp, steps, t_start)
     ms = time_calls(torch, stream, release(fo.adamw_step), steps)
     entry("llama31_8b_adamw gradient release, faithful division", "flashoptim_adamw_step", ms, 12.25 * n,
           kernel=kernel_label("adamw", True, False), resident_bytes_per_param=5.125)
+    # per-tensor calls again, alternating between two side streams (and two gradient buffers, so that a gradient is
+    # never overwritten while the previous call on the other stream may still read its own): consecutive launches
+    # then overlap at their boundaries instead of each waiting for the previous one to drain.  The side streams
+    # start after the work already on the main stream and the main stream waits for both at the end of the step.
+    side = [torch.cuda.Stream(), torch.cuda.Stream()]
+    gbuf2 = gbuf.clone()
+    singles2 = []
+    for k, i in enumerate(reversed(range(len(specs)))):
+        tl.set_grad(i, gbuf if k % 2 == 0 else gbuf2)
+        singles2.append(tl.slice(i))
+
+    def release_two_streams():
+        t[0] += 1
+        for sd in side:
+            sd.wait_stream(stream)
+        for k, s1 in enumerate(singles2):
+            fo.adamw_step_exact(s1, hp["beta1"], hp["beta2"], hp["eps"], t[0], stream=side[k % 2])
+        for sd in side:
+            stream.wait_stream(sd)
+
+    ms = time_calls(torch, stream, release_two_streams, steps)
+    entry("llama31_8b_adamw gradient release, calls alternating between two streams", "flashoptim_adamw_step_exact", ms,
+          12.25 * n, kernel=kernel_label("adamw", True, True),
+          resident_bytes_per_param=5.125 + 2.0 * gbuf.numel() / n)
+    del gbuf2, singles2
     # the same with one call per decoder layer (its 9 tensors as one list; embedding, and final norm + head, apart):
     # 34 calls per step, the layer's gradients carved out of the same single buffer
     groups, cur = [], []
