@@ -170,8 +170,6 @@ __device__ __forceinline__ uint32_t group_scale_fast(float absmax, float* r) {
 // flashoptim_selftest.  Below
 // 2^-96 the residual x - s*s leaves the normal range and the result is only within one ulp; zero,
 // infinity and NaN give NaN.  Callers check the range and use sqrtf() otherwise.
-constexpr float kSqrtFastMin = 1.2621774483536189e-29f;   // 2^-96
-constexpr float kSqrtFastMax = 3.4028234663852886e38f;    // largest finite value
 __device__ __forceinline__ float sqrt_rn_midrange(float x) {
     const float y = __builtin_amdgcn_rsqf(x);
     const float s = x * y, h = 0.5f * y;
@@ -1599,7 +1597,6 @@ hipError_t launch_convert(bool has_v, bool compress, bool direct, const StepArgs
 //              exact one at all is reported by counters[14].)
 // counters[2 * section] counts checks, counters[2 * section + 1] failures.
 
-constexpr int kSelftestSections = 7;
 constexpr uint64_t kSelftestSqrtCount = kSelftestSqrtValues;
 constexpr uint64_t kSelftestDivCount = (1ull << 30) + (1ull << 24);
 constexpr uint64_t kSelftestVarCount = 4ull * (1ull << 23);
