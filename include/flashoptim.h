@@ -140,9 +140,10 @@ int flashoptim_lion_step(const flashoptim_tensor* tensors, int64_t n_tensors,
  * Limits: at most 1024 tensors with numel > 0 (FLASHOPTIM_ERR_LIST_TOO_LONG beyond that, nothing enqueued) and,
  * as for every step call, at most 2^31 - 1 workgroups.  Every call on a GPU shares that GPU's array: calls on
  * the same stream are ordered and safe; calls that may overlap on one GPU (different streams, several host
- * threads) race on it and must be ordered by the caller.  The short square root is used only if an earlier
- * AdamW step call of another entry point has verified it on this device (flashoptim_short_sqrt_state() == 1);
- * otherwise the kernels use sqrtf: same results, a few percent slower. */
+ * threads) race on it and must be ordered by the caller.  This entry point does not start the check of the
+ * short square root (see flashoptim_short_sqrt_state): where no AdamW step call of another entry point has
+ * put it on a stream of this device, or it has not finished yet, the kernels use sqrtf: same results, a few
+ * percent slower. */
 int flashoptim_adamw_step_noalloc(const flashoptim_tensor* tensors, int64_t n_tensors,
                                   const flashoptim_adamw_hp* hp, void* stream);
 
@@ -317,13 +318,17 @@ int flashoptim_selftest(int64_t* n_checked, int64_t* n_failed, void* stream);
  * completion.  FLASHOPTIM_ERR_SELFTEST if any quotient is off by more than one ulp. */
 int flashoptim_faithful_rounding_stats(int64_t* counts, void* stream);
 /* The AdamW kernels take sqrt(v_hat) as the hardware reciprocal-square-root estimate plus one correction,
- * which is the correctly rounded root only if the estimate makes it so.  The library therefore checks every
- * FP32 value of that sequence's range, [2^-96, FLT_MAX], against sqrtf on the device before the first AdamW
- * step there (once per process and device: a kernel of about 4 ms on MI355X and a wait on the caller's stream, so that
- * first call must not be made under stream capture), and uses sqrtf in the kernels if the check fails or if
- * FLASHOPTIM_FORCE_GENERAL_SQRT is set to a non-zero value in the environment.  Returns the state for the
- * current device: 0 not checked yet, 1 verified (short sequence in use), 2 not in use; negative status on
- * a HIP error. */
+ * which is the correctly rounded root only if the estimate makes it so.  They read the lower limit of that
+ * sequence's use from a word of device memory that holds +inf (never used: sqrtf throughout) until the device
+ * has passed a check of every FP32 value of the sequence's range, [2^-96, FLT_MAX], against sqrtf.  The first
+ * AdamW step call on a device (any entry point but flashoptim_adamw_step_noalloc) puts that check on its stream
+ * ahead of its own kernels, once per process and device: about 4 ms on MI355X, no allocation, no wait on the
+ * host.  Kernels that run before the verdict has landed (on another stream, say) use sqrtf, with the same
+ * results.  A first call made under stream capture does not start the check (it belongs in front of a graph,
+ * not inside it); a later call outside capture does.  With FLASHOPTIM_FORCE_GENERAL_SQRT set to a non-zero
+ * value in the environment the check is not run and the word stays at +inf.
+ * Returns the state for the current device: 0 check not started, 1 verified (short sequence in use), 2 not in
+ * use; negative status on a HIP error.  If the check is on its way the call waits for its verdict. */
 int flashoptim_short_sqrt_state(void);
 /* A measurement aid: samples the clock the compute units run at while other kernels execute (a step kernel
  * under the package power limit runs well below the nominal clock).  Enqueues a one-wavefront kernel on

@@ -264,11 +264,12 @@ hipError_t launch_op(LiveOp op, int kind, bool direct, bool split, bool quant, S
 
 // Launches one operation over the live tensors (already validated and converted).
 int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, const StepConsts& c,
-                hipStream_t stream, LiveOp op = kOpStep) {
+                hipStream_t stream, LiveOp op = kOpStep, const float* sqrt_min_word = nullptr) {
     if (live.empty()) return FLASHOPTIM_OK;
     StepArgs a;
     std::memset(&a, 0, sizeof(a));
     a.c = c;
+    a.sqrt_min_word = sqrt_min_word;
     const int64_t ce = (op == kOpCompress || op == kOpDecompress) ? fo::kConvChunkElems : fo::chunk_elems(kind);
     // one workgroup per chunk: the launch grid is a 31-bit count
     int64_t total_chunks = 0;
@@ -337,55 +338,80 @@ int launch_live(int kind, bool split, bool quant, std::vector<TensorDev>& live, 
 }
 
 // The short square root of the AdamW kernels (reciprocal-square-root estimate plus one correction) is
-// exactly rounded on a device only if the hardware estimate makes it so; that is checked for every value of
-// its range once per process and device, before the first AdamW step there (a kernel of about 4 ms on MI355X
-// and a wait on the stream).  If the check fails, or FLASHOPTIM_FORCE_GENERAL_SQRT is set in the environment (for testing
-// that path), the kernels use sqrtf throughout.
+// exactly rounded on a device only if the hardware estimate makes it so.  The kernels therefore read the
+// smallest v_t they may give to it from a word of device memory that starts at +inf (never: sqrtf
+// throughout).  The first AdamW step on a device puts the check of every value of the sequence's range on
+// its stream, ahead of its own kernels (about 4 ms on MI355X), followed by a one-lane kernel that lowers
+// the word to 2^-96 if every value passed.  Nothing is allocated and the host does not wait: work that
+// runs before the verdict has landed (another stream's, say) uses sqrtf and gets the same results.
+// FLASHOPTIM_FORCE_GENERAL_SQRT in the environment leaves the word at +inf (for testing that path).
 constexpr int kMaxDevices = 64;
-std::atomic<int> g_sqrt_state[kMaxDevices];      // 0 not checked, 1 verified, 2 not to be used
+static __device__ float sqrt_min_word = __builtin_inff();
+static __device__ unsigned long long sqrt_check_counters[fo::kSelftestCounters];
+
+__global__ void sqrt_verdict_kernel(unsigned long long* counters, float* word, unsigned long long expected) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const bool ok = counters[4] == expected && counters[5] == 0;
+        *word = ok ? 1.2621774483536189e-29f /* 2^-96 */ : __builtin_inff();
+        counters[4] = 0;
+        counters[5] = 0;
+    }
+}
+
+struct SqrtCheck {
+    std::atomic<int> state;       // 0 not started, 1 verified, 2 not to be used, 3 on its way (see `done`)
+    float* word;                  // device address of sqrt_min_word on this device
+    hipEvent_t done;              // recorded behind the verdict kernel
+};
+SqrtCheck g_sqrt[kMaxDevices];
 std::mutex g_sqrt_mu;
 
-int short_sqrt_verified(hipStream_t stream, bool* verified) {
-    *verified = false;
+// Device address of the word the AdamW kernels read on the current device.  With `start`, the check is put
+// on `stream` first if this device has not had it yet (not while the stream is being captured: the check
+// belongs in front of a graph, not inside it).
+int sqrt_min_word_of_device(hipStream_t stream, bool start, const float** out) {
     int dev = 0;
     FO_HIP(hipGetDevice(&dev));
-    if (dev < 0 || dev >= kMaxDevices) return FLASHOPTIM_OK;
-    int st = g_sqrt_state[dev].load(std::memory_order_acquire);
-    if (st == 0) {
+    if (dev < 0 || dev >= kMaxDevices) return FLASHOPTIM_ERR_INVALID_ARG;
+    SqrtCheck& s = g_sqrt[dev];
+    if (s.state.load(std::memory_order_acquire) == 0 || !s.word) {
         std::lock_guard<std::mutex> lock(g_sqrt_mu);
-        st = g_sqrt_state[dev].load(std::memory_order_acquire);
-        if (st == 0) {
+        if (!s.word) {
+            void* sym = nullptr;
+            FO_HIP(hipGetSymbolAddress(&sym, HIP_SYMBOL(sqrt_min_word)));
+            if (!sym) return FLASHOPTIM_ERR_HIP;
+            s.word = static_cast<float*>(sym);
+        }
+        if (start && s.state.load(std::memory_order_acquire) == 0) {
+            hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+            FO_HIP(hipStreamIsCapturing(stream, &cap));
             const char* force = std::getenv("FLASHOPTIM_FORCE_GENERAL_SQRT");
             if (force && force[0] != '\0' && force[0] != '0') {
-                st = 2;
-            } else {
-                unsigned long long h[2] = {0, 0};
-                unsigned long long* d = nullptr;
-                FO_HIP(hipMalloc((void**)&d, fo::kSelftestCounters * sizeof(unsigned long long)));
-                hipError_t e = hipMemsetAsync(d, 0, fo::kSelftestCounters * sizeof(unsigned long long), stream);
+                s.state.store(2, std::memory_order_release);
+            } else if (cap == hipStreamCaptureStatusNone) {
+                void* sym = nullptr;
+                FO_HIP(hipGetSymbolAddress(&sym, HIP_SYMBOL(sqrt_check_counters)));
+                if (!sym) return FLASHOPTIM_ERR_HIP;
+                unsigned long long* counters = static_cast<unsigned long long*>(sym);
+                if (!s.done) FO_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
                 StepConsts c0;
                 std::memset(&c0, 0, sizeof(c0));
-                if (e == hipSuccess) e = fo::launch_selftest(d, 2, c0, 1.0f, stream);
-                if (e == hipSuccess) e = hipMemcpyAsync(h, d + 4, sizeof(h), hipMemcpyDeviceToHost, stream);
-                if (e == hipSuccess) e = hipStreamSynchronize(stream);
-                (void)hipFree(d);
-                if (e != hipSuccess) {
-                    g_last_hip_error = (int)e;
-                    (void)hipGetLastError();
-                    return FLASHOPTIM_ERR_HIP;
-                }
-                st = (h[0] == fo::kSelftestSqrtValues && h[1] == 0) ? 1 : 2;
+                FO_HIP(fo::launch_selftest(counters, 2, c0, 1.0f, stream));
+                hipLaunchKernelGGL(sqrt_verdict_kernel, dim3(1), dim3(64), 0, stream, counters, s.word,
+                                   (unsigned long long)fo::kSelftestSqrtValues);
+                FO_HIP(hipGetLastError());
+                FO_HIP(hipEventRecord(s.done, stream));
+                s.state.store(3, std::memory_order_release);
             }
-            g_sqrt_state[dev].store(st, std::memory_order_release);
         }
     }
-    *verified = (st == 1);
+    *out = s.word;
     return FLASHOPTIM_OK;
 }
 
 // Operand limits of the short square root and division of the AdamW kernels for this call (StepConsts).
-void set_ranges(StepConsts& c, bool short_sqrt_verified) {
-    c.sqrt_min = short_sqrt_verified ? 1.2621774483536189e-29f /* 2^-96 */ : INFINITY;
+void set_ranges(StepConsts& c) {
+    c.sqrt_min = INFINITY;      // the kernels replace it by the device's word
     const bool eps_ok = c.eps >= fo::kDivFastLo && c.eps <= 1.0f;
     const double slack = 1.0 - 1.0 / 1048576.0;       // the limits are rounded to FP32: stay below the exact quotient
     c.v_max = eps_ok ? (float)((double)fo::kDivFastHi / (double)c.rbc2 * slack) : -1.0f;
@@ -407,13 +433,13 @@ int run_step(int kind, const flashoptim_tensor* tensors, int64_t n_tensors, cons
     for (int64_t i = 0; i < n_tensors; ++i)
         if (tensors[i].numel > 0) live.push_back(to_dev(tensors[i], has_v));
     StepConsts cc = c;
+    const float* word = nullptr;
     if (has_v && op != kOpProbe && !live.empty()) {
-        bool verified = false;
-        rc = short_sqrt_verified(static_cast<hipStream_t>(stream_), &verified);
+        rc = sqrt_min_word_of_device(static_cast<hipStream_t>(stream_), true, &word);
         if (rc != FLASHOPTIM_OK) return rc;
-        set_ranges(cc, verified);
+        set_ranges(cc);
     }
-    return launch_live(kind, true, true, live, cc, static_cast<hipStream_t>(stream_), op);
+    return launch_live(kind, true, true, live, cc, static_cast<hipStream_t>(stream_), op, word);
 }
 
 // Conversion between the FP32 state and the compressed layout: every buffer of both layouts is needed.
@@ -453,14 +479,14 @@ int run_step_ex(int kind, const flashoptim_tensor_ex* tensors, int64_t n_tensors
     int rc = to_dev_ex(tensors, n_tensors, kind == FLASHOPTIM_ADAMW, split, quant, live);
     if (rc != FLASHOPTIM_OK) return rc;
     StepConsts cc = c;
+    const float* word = nullptr;
     if (kind == FLASHOPTIM_ADAMW && !live.empty()) {
-        bool verified = false;
-        rc = short_sqrt_verified(static_cast<hipStream_t>(stream_), &verified);
+        rc = sqrt_min_word_of_device(static_cast<hipStream_t>(stream_), true, &word);
         if (rc != FLASHOPTIM_OK) return rc;
-        set_ranges(cc, verified);
+        set_ranges(cc);
     }
     // the ablation and reference variants always use the exactly rounded arithmetic
-    return launch_live(kind, split, quant, live, cc, static_cast<hipStream_t>(stream_), kOpStepExact);
+    return launch_live(kind, split, quant, live, cc, static_cast<hipStream_t>(stream_), kOpStepExact, word);
 }
 
 // 1 / (float)(1 - beta^t): the bias correction is formed in double and rounded to FP32
@@ -1014,7 +1040,20 @@ int flashoptim_short_sqrt_state(void) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return FLASHOPTIM_ERR_HIP; }
     if (dev < 0 || dev >= kMaxDevices) return 2;
-    return g_sqrt_state[dev].load(std::memory_order_acquire);
+    SqrtCheck& s = g_sqrt[dev];
+    int st = s.state.load(std::memory_order_acquire);
+    if (st == 3) {          // on its way: wait for the verdict and read it
+        std::lock_guard<std::mutex> lock(g_sqrt_mu);
+        st = s.state.load(std::memory_order_acquire);
+        if (st == 3) {
+            float word = INFINITY;
+            FO_HIP(hipEventSynchronize(s.done));
+            FO_HIP(hipMemcpy(&word, s.word, sizeof(word), hipMemcpyDeviceToHost));
+            st = word < INFINITY ? 1 : 2;
+            s.state.store(st, std::memory_order_release);
+        }
+    }
+    return st;
 }
 
 int flashoptim_shard_range(int64_t numel, int64_t world, int64_t rank, int64_t* begin, int64_t* len) {
@@ -1052,13 +1091,16 @@ int flashoptim_adamw_step_noalloc(const flashoptim_tensor* tensors, int64_t n_te
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     int dev = 0;
     FO_HIP(hipGetDevice(&dev));
-    // the short square root only where an earlier call has verified it on this device (that check allocates
-    // and waits, so it is not run from here); sqrtf otherwise: same results
-    const bool verified = dev >= 0 && dev < kMaxDevices && g_sqrt_state[dev].load(std::memory_order_acquire) == 1;
-    set_ranges(c, verified);
+    // the short square root only where an earlier call has put its check on a stream of this device (that
+    // creates an event, so it is not started from here); sqrtf otherwise: same results
+    const float* word = nullptr;
+    rc = sqrt_min_word_of_device(stream, false, &word);
+    if (rc != FLASHOPTIM_OK) return rc;
+    set_ranges(c);
     StepArgs a;
     std::memset(&a, 0, sizeof(a));
     a.c = c;
+    a.sqrt_min_word = word;
     if (n_live == 1) {          // one tensor: no table at all
         a.single = to_dev(tensors[only], true);
         FO_HIP(launch_op(kOpStepExact, FLASHOPTIM_ADAMW, true, true, true, a, total_tiles, ce, stream));

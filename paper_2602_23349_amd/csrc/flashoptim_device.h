@@ -65,8 +65,8 @@ struct StepConsts {
     float v_max, m_max;   // largest v_t and |m_t| for which the short square root and division serve: 2^60 / rbc2 and
                           // 2^60 / rbc1 rounded down, or -1 when eps is outside [2^-60, 1] (the kernels then use
                           // sqrtf and the IEEE division throughout)
-    float sqrt_min;       // smallest v_t for the same: 2^-96, or +inf when the short square root has not passed its
-                          // check on this device
+    float sqrt_min;       // smallest v_t for the same: 2^-96, or +inf while the short square root has not passed its
+                          // check on this device; the step kernels fill it in from StepArgs::sqrt_min_word
 };
 
 // A multi-tensor launch maps workgroup b to (tensor, tile) in two steps: coarse[b >> coarse_shift] is
@@ -92,6 +92,7 @@ struct StepArgs {
     uint32_t block_offset;      // tile index of this launch's workgroup 0 (a list or tensor is covered by several launches)
     TensorDev single;           // the one tensor of a direct launch
     StepConsts c;
+    const float* sqrt_min_word; // AdamW steps: device word that holds StepConsts::sqrt_min for this device
 };
 
 struct CopySegment {

@@ -165,9 +165,9 @@ __device__ __forceinline__ uint32_t group_scale_fast(float absmax, float* r) {
 // Correctly rounded square root for 2^-96 <= x <= FLT_MAX: the hardware reciprocal-square-root
 // estimate (1 ulp) and one Newton correction, each step one FMA.  That this sequence returns the
 // correctly rounded root for EVERY FP32 value of that range is a property of the hardware estimate
-// which is verified exhaustively on the device (all 1,879,048,192 values): by the host before the first
-// AdamW step on a device (StepConsts::sqrt_min = +inf switches the kernels to sqrtf otherwise) and by
-// flashoptim_selftest.  Below
+// which is verified exhaustively on the device (all 1,879,048,192 values): ahead of the first AdamW
+// step on a device (until that check has passed, the device word behind StepConsts::sqrt_min holds +inf
+// and the kernels use sqrtf) and by flashoptim_selftest.  Below
 // 2^-96 the residual x - s*s leaves the normal range and the result is only within one ulp; zero,
 // infinity and NaN give NaN.  Callers check the range and use sqrtf() otherwise.
 __device__ __forceinline__ float sqrt_rn_midrange(float x) {
@@ -920,10 +920,12 @@ __global__ __launch_bounds__(THREADS) void step_kernel(StepArgs a) {
     const int64_t chunk = locate_tile<DIRECT>(a, T);
     const int64_t tile0 = chunk * (int64_t)kTile;              // first element of the tile (wave-uniform)
     const int64_t rem = T.numel - tile0;                       // elements from there to the tensor's end
+    StepConsts c = a.c;
+    if (KIND == 0) c.sqrt_min = *a.sqrt_min_word;              // one scalar load, needed only after the streaming loads
     if (rem >= kTile) {
-        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, EXACT, true>(T, a.c, tab, entries, tile0, kTile, tid);
+        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, EXACT, true>(T, c, tab, entries, tile0, kTile, tid);
     } else {
-        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, EXACT, false>(T, a.c, tab, entries, tile0, rem > 0 ? (int)rem : 0,
+        step_tile<KIND, VEC, THREADS, SPLIT, QUANT, EXACT, false>(T, c, tab, entries, tile0, rem > 0 ? (int)rem : 0,
                                                                  tid);
     }
 }
@@ -950,6 +952,7 @@ static hipError_t launch_kind(bool direct, bool split, bool quant, const StepArg
 // layout only (SGD and Lion have neither operation; the ablation variants are always exact).
 hipError_t launch_step(int kind, bool direct, bool split, bool quant, bool exact, const StepArgs& a, int64_t n_blocks,
                        hipStream_t s) {
+    if (kind == 0 && !a.sqrt_min_word) return hipErrorInvalidValue;     // the AdamW kernels dereference it
     if (kind == 0 && split && quant && !exact) return launch_variant<0, true, true, false>(direct, a, n_blocks, s);
     if (kind == 0) return launch_kind<0>(direct, split, quant, a, n_blocks, s);
     if (kind == 1) return launch_kind<1>(direct, split, quant, a, n_blocks, s);
