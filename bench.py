@@ -53,7 +53,7 @@ def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama31_8b_adamw", choices=sorted(WORKLOADS))
     ap.add_argument("--mode", default="fused", choices=["fused", "grad_release", "ckpt_pack", "ckpt_unpack"],
                     help="fused: one multi-tensor launch per step; grad_release: one call per tensor in "
