@@ -328,7 +328,9 @@ int flashoptim_faithful_rounding_stats(int64_t* counts, void* stream);
  * not inside it); a later call outside capture does.  With FLASHOPTIM_FORCE_GENERAL_SQRT set to a non-zero
  * value in the environment the check is not run and the word stays at +inf.
  * Returns the state for the current device: 0 check not started, 1 verified (short sequence in use), 2 not in
- * use; negative status on a HIP error.  If the check is on its way the call waits for its verdict. */
+ * use; negative status on a HIP error.  If the check is on its way the call waits for its verdict; in states
+ * 0 and 2 it reads the word back (a blocking 4-byte copy) and returns FLASHOPTIM_ERR_SELFTEST unless it holds
+ * +inf. */
 int flashoptim_short_sqrt_state(void);
 /* A measurement aid: samples the clock the compute units run at while other kernels execute (a step kernel
  * under the package power limit runs well below the nominal clock).  Enqueues a one-wavefront kernel on

@@ -1040,18 +1040,23 @@ int flashoptim_short_sqrt_state(void) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return FLASHOPTIM_ERR_HIP; }
     if (dev < 0 || dev >= kMaxDevices) return 2;
+    const float* word_dev = nullptr;
+    const int rc = sqrt_min_word_of_device(nullptr, false, &word_dev);
+    if (rc != FLASHOPTIM_OK) return rc;
     SqrtCheck& s = g_sqrt[dev];
+    std::lock_guard<std::mutex> lock(g_sqrt_mu);
     int st = s.state.load(std::memory_order_acquire);
-    if (st == 3) {          // on its way: wait for the verdict and read it
-        std::lock_guard<std::mutex> lock(g_sqrt_mu);
-        st = s.state.load(std::memory_order_acquire);
-        if (st == 3) {
-            float word = INFINITY;
-            FO_HIP(hipEventSynchronize(s.done));
-            FO_HIP(hipMemcpy(&word, s.word, sizeof(word), hipMemcpyDeviceToHost));
-            st = word < INFINITY ? 1 : 2;
-            s.state.store(st, std::memory_order_release);
-        }
+    if (st == 1) return st;
+    // read the word the kernels read: after the verdict if the check is on its way; in the other states it
+    // must still hold +inf
+    float word = 0.0f;
+    if (st == 3) FO_HIP(hipEventSynchronize(s.done));
+    FO_HIP(hipMemcpy(&word, word_dev, sizeof(word), hipMemcpyDeviceToHost));
+    if (st == 3) {
+        st = word < INFINITY ? 1 : 2;
+        s.state.store(st, std::memory_order_release);
+    } else if (!(word == INFINITY)) {
+        return FLASHOPTIM_ERR_SELFTEST;
     }
     return st;
 }
