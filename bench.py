@@ -431,7 +431,11 @@ def small_list_measurements(fo, W, torch, stream, steps=200):
             t[0] += 1
             step_call(fo, kind, tl, h, t[0], exact=True)
 
-        ms = time_calls(torch, stream, call, steps, warmup=10)
+        # A step of these lists takes 5-200 us and the state was just built on the host: the first ~15 ms of GPU
+        # work after such an idle stretch run ~15 % slower (clocks ramping up), which would cover the whole timed
+        # region.  So the untimed warm-up is sized to 100 ms of work from a first rough timing.
+        rough = time_calls(torch, stream, call, 20, warmup=10)
+        ms = time_calls(torch, stream, call, steps, warmup=max(10, int(100.0 / rough)))
         probe_ms = time_calls(torch, stream, lambda: fo.stream_probe(kind, tl), steps, warmup=10)
         bpp = BYTES_PER_PARAM[kind]
         g = bpp * n / (ms * 1e-3) / 1e9
