@@ -97,7 +97,9 @@ typedef struct flashoptim_lion_hp { float beta1, beta2; } flashoptim_lion_hp;
  * elements).  A list of length one is the gradient-release call (Section 3.4): it needs no
  * table and no device allocation.  Tables of the 256 most recently used lists are kept; a call
  * with a further distinct list frees the least recently used one after synchronising the device.  The grad pointers are not part of the
- * cached identity of a list, so gradients may live in different buffers each step.
+ * cached identity of a list, so gradients may live in different buffers each step.  A call whose descriptors
+ * (pointers, grad pointers, numel, lr, weight_decay) equal those of the previous call on the same list enqueues
+ * kernels only and may be captured into a HIP graph; changed descriptors are uploaded in stream order first.
  *
  * flashoptim_adamw_step: Algorithm 4, the body of the loop after the gradient (reconstruct m, v, theta; AdamW
  *   update with bias correction and decoupled weight decay; quantize m, v; split theta).

@@ -1,7 +1,8 @@
-"""The step entry points that enqueue kernels only - flashoptim_adamw_step_noalloc over a list, and any step call
-on a single tensor (the gradient-release call) - under HIP stream capture: the captured graph is replayed several
+"""The step calls that enqueue kernels only - flashoptim_adamw_step_noalloc over a list, any step call on a single
+tensor (the gradient-release call), and an ordinary multi-tensor call whose tables an earlier call has created and
+whose descriptors have not changed since - under HIP stream capture: the captured graph is replayed several
 times, with eager work and synchronisations in between, and every replay must leave the same bits as the same
-call made eagerly."""
+calls made eagerly."""
 import pytest
 import torch
 
@@ -46,10 +47,12 @@ def test_captured_steps_replay_like_eager_calls():
     ref, got = _twins(specs, seed=41)
     tl_ref, tl_got = fo.TensorList(ref), fo.TensorList(got)
     singles = [tl_got.slice(i) for i in (0, 3, 7)]
-    # eager warm-up: the library's per-device set-up (the square-root check of the first AdamW call allocates and
-    # waits, which a capture does not allow; the fixed table's address is looked up once)
+    # eager warm-up: the library's per-device set-up (the first AdamW call outside a capture puts the check of the
+    # short square root on its stream; the fixed table's address is looked up once) and the tables of tl_got
     fo.adamw_step_exact(tl_ref, B1, B2, EPS, 1)
     fo.adamw_step_noalloc(tl_got, B1, B2, EPS, 1)
+    fo.adamw_step_exact(tl_ref, B1, B2, EPS, 1)
+    fo.adamw_step_exact(tl_got, B1, B2, EPS, 1)                # creates and uploads this list's tables
     _assert_equal(ref, got, "eager warm-up")
     assert fo.short_sqrt_state() in (1, 2)
     graph = torch.cuda.CUDAGraph()
@@ -57,11 +60,13 @@ def test_captured_steps_replay_like_eager_calls():
         fo.adamw_step_noalloc(tl_got, B1, B2, EPS, 2)          # multi-tensor launch, tables from kernel arguments
         for s1 in singles:                                     # single-tensor calls: table-free launches
             fo.adamw_step_exact(s1, B1, B2, EPS, 3)
+        fo.adamw_step_exact(tl_got, B1, B2, EPS, 4)            # cached tables, unchanged descriptors: kernels only
     for replay in range(3):
         graph.replay()
         fo.adamw_step_exact(tl_ref, B1, B2, EPS, 2)            # the same calls, eagerly
         for i in (0, 3, 7):
             fo.adamw_step_exact(tl_ref.slice(i), B1, B2, EPS, 3)
+        fo.adamw_step_exact(tl_ref, B1, B2, EPS, 4)
         _assert_equal(ref, got, f"replay {replay}")
         # eager work of the program itself between the replays
         for b in got:
